@@ -1,0 +1,203 @@
+"""Pins for the oracle's compressors: Top-K (Section 2.1), the contractive
+inequality (Definition 1), Philox, and the b-bit quantiser.  CPU only."""
+import math
+import os
+import struct
+
+import numpy as np
+import pytest
+
+from oracle import adacgd_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- Top-K
+def brute_topk_support(vals, K):
+    """First K of a plain Python sort on (|v| bits descending, index ascending)."""
+    def key(l):
+        bits = struct.unpack("<I", struct.pack("<f", vals[l]))[0] & 0x7FFFFFFF
+        return (-bits, l)
+    return sorted(sorted(range(len(vals)), key=key)[:K])
+
+
+TINY = [
+    [3.0, -1.0, 2.0, -3.0, 0.5],
+    [1.0, 1.0, 1.0, 1.0],
+    [0.0, -0.0, 0.0, 5.0, -0.0],
+    [-2.0, 2.0, -2.0, 2.0, 1e-40, -1e-40, 0.0],
+    [7.0],
+    [1e-45, 0.0, -1e-45, 1.1754942e-38],
+    [float("inf"), 1.0, -float("inf"), 3.0],
+]
+
+
+@pytest.mark.parametrize("vals", TINY)
+def test_topk_matches_brute_force(vals):
+    v = np.array(vals, dtype=np.float32)
+    for K in range(1, len(vals) + 1):
+        got = O.topk_support(v, K).tolist()
+        assert got == brute_topk_support(vals, K), (vals, K)
+        c = O.topk(v, K)
+        mask = np.zeros(len(vals), bool)
+        mask[got] = True
+        assert np.array_equal(c[mask].view(np.uint32), v[mask].view(np.uint32))
+        assert np.all(c[~mask] == 0)
+
+
+def test_topk_random_brute_force_with_duplicates():
+    rng = np.random.default_rng(11)
+    for trial in range(40):
+        d = int(rng.integers(1, 60))
+        v = rng.integers(-4, 5, size=d).astype(np.float32) * np.float32(0.25)
+        K = int(rng.integers(1, d + 1))
+        assert O.topk_support(v, K).tolist() == brute_topk_support(v.tolist(), K)
+
+
+def test_topk_tie_prefers_lower_index_and_K_exceeding_nonzeros():
+    v = np.array([0, 2, 0, -2, 0, 2], dtype=np.float32)
+    assert O.topk_support(v, 2).tolist() == [1, 3]
+    assert O.topk_support(v, 4).tolist() == [0, 1, 3, 5]      # zeros by ascending index
+    assert O.topk_support(v, 6).tolist() == [0, 1, 2, 3, 4, 5]
+
+
+def test_topk_contractive_inequality_and_equality_case():
+    # Definition 1 with alpha = K/d; equality when all magnitudes coincide.
+    rng = np.random.default_rng(5)
+    for d in (7, 64, 1000):
+        v = rng.standard_normal(d).astype(np.float32)
+        S = O.sum_squares(v)
+        for K in (1, 2, d // 2 + 1, d):
+            err = O.sum_sq_diff(v, O.topk(v, K))
+            assert err <= (1 - K / d) * S * (1 + 1e-12)
+        c = np.float32(1.5)
+        w = np.where(rng.random(d) < 0.5, c, -c).astype(np.float32)
+        for K in (1, d // 3 + 1, d):
+            assert O.sum_sq_diff(w, O.topk(w, K)) == (d - K) * float(c) ** 2
+
+
+def test_topk_levels_nested_and_errors_monotone():
+    rng = np.random.default_rng(6)
+    v = rng.standard_t(3, size=500).astype(np.float32)
+    Ks = [1, 5, 50, 200, 500]
+    sup = [set(O.topk_support(v, K).tolist()) for K in Ks]
+    err = [O.sum_sq_diff(v, O.topk(v, K)) for K in Ks]
+    for a, b in zip(sup, sup[1:]):
+        assert a < b
+    assert all(e0 >= e1 for e0, e1 in zip(err, err[1:]))
+    assert err[-1] == 0.0
+
+
+def test_sum_squares_matches_exact_sum():
+    rng = np.random.default_rng(7)
+    a = (rng.standard_normal(20000) * 10.0 ** rng.uniform(-6, 6, 20000)).astype(np.float32)
+    exact = math.fsum(float(x) * float(x) for x in a)
+    assert O.sum_squares(a) == exact
+
+
+# ---------------------------------------------------------------- Philox
+def philox_ref(ctr, key):
+    """Independent plain-integer Philox4x32-10."""
+    c = list(ctr)
+    k = list(key)
+    for r in range(10):
+        p0 = 0xD2511F53 * c[0]
+        p1 = 0xCD9E8D57 * c[2]
+        c = [(p1 >> 32) ^ c[1] ^ k[0], p1 & 0xFFFFFFFF, (p0 >> 32) ^ c[3] ^ k[1], p0 & 0xFFFFFFFF]
+        k = [(k[0] + 0x9E3779B9) & 0xFFFFFFFF, (k[1] + 0xBB67AE85) & 0xFFFFFFFF]
+    return c
+
+
+def test_philox_known_answers():
+    with open(os.path.join(GOLD, "philox4x32_10_kat.txt")) as f:
+        rows = [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 2
+    for row in rows:
+        w = [int(t, 16) for t in row]
+        out = O.philox4x32_10([w[0]], [w[1]], [w[2]], [w[3]], w[4], w[5])
+        assert [int(o[0]) for o in out] == w[6:10]
+        assert philox_ref(w[0:4], w[4:6]) == w[6:10]
+
+
+def test_philox_vectorised_matches_integer_reference():
+    rng = np.random.default_rng(3)
+    C = rng.integers(0, 2 ** 32, size=(50, 4), dtype=np.uint64)
+    for k in [(0, 0), (123, 456), (0xFFFFFFFF, 0xDEADBEEF)]:
+        out = O.philox4x32_10(C[:, 0], C[:, 1], C[:, 2], C[:, 3], k[0], k[1])
+        for r in range(50):
+            assert [int(o[r]) for o in out] == philox_ref([int(x) for x in C[r]], k)
+
+
+def test_dither_uniform_layout_and_range():
+    d, seed, node, step = 37, (7 << 32) | 9, 5, 11
+    u = O.dither_uniforms(d, seed, node, step)
+    assert u.shape == (d,) and np.all(u >= 0) and np.all(u < 1)
+    for l in (0, 1, 6, 35, 36):
+        w = philox_ref([l // 4, node, step, 0], [9, 7])[l % 4]
+        assert u[l] == (w >> 8) * 2.0 ** -24
+    big = O.dither_uniforms(1 << 16, 1, 0, 0)
+    cnt, _ = np.histogram(big, bins=16, range=(0, 1))
+    chi2 = np.sum((cnt - 4096.0) ** 2 / 4096.0)
+    assert chi2 < 50.0                      # 15 degrees of freedom
+
+
+# ---------------------------------------------------------------- quantiser
+def test_quantizer_structure():
+    rng = np.random.default_rng(8)
+    d = 513
+    v = rng.standard_normal(d).astype(np.float32)
+    for b in (2, 4, 8, 16):
+        s = 2 ** (b - 1) - 1
+        u = O.dither_uniforms(d, 42, 3, 2)
+        c, codes, scale = O.quantize(v, b, u)
+        assert np.all(np.abs(codes) <= s)
+        assert np.all((codes == 0) | (np.sign(codes) == np.sign(v)))
+        l = int(np.argmax(np.abs(v)))
+        assert abs(codes[l]) == s           # the max coordinate sits on the top level
+        w = O.quant_omega(d, b)
+        assert abs(float(c[l]) - float(v[l]) / (1 + w)) <= 2e-7 * abs(float(v[l]))
+        # decoded value is sign * fl(|code| * scale)
+        dec = np.copysign((np.abs(codes).astype(np.float32) * np.float32(scale)), v)
+        assert np.array_equal(dec.view(np.uint32)[codes != 0], c.view(np.uint32)[codes != 0])
+        # every coordinate lands on one of the two neighbouring levels
+        r = np.abs(v.astype(np.float64)) / np.abs(v).max() * s
+        assert np.all(np.abs(np.abs(codes) - r) < 1 + 1e-5)
+    z = np.zeros(9, dtype=np.float32)
+    c, codes, scale = O.quantize(z, 4, O.dither_uniforms(9, 1, 0, 0))
+    assert not c.any() and not codes.any() and scale == 0
+
+
+def test_quantizer_unbiased_after_rescaling_and_contractive_in_expectation():
+    rng = np.random.default_rng(9)
+    d, b = 64, 4
+    v = rng.standard_normal(d).astype(np.float32)
+    w = O.quant_omega(d, b)
+    trials = 4000
+    acc = np.zeros(d)
+    sq = 0.0
+    for t in range(trials):
+        c, _, _ = O.quantize(v, b, O.dither_uniforms(d, 77, 1, t))
+        acc += c.astype(np.float64)
+        sq += O.sum_sq_diff(v, c)
+    mean = acc / trials * (1 + w)
+    s = 2 ** (b - 1) - 1
+    delta = np.abs(v).max() / s
+    assert np.all(np.abs(mean - v) < 5 * (delta / 2) / math.sqrt(trials) + 1e-6)   # CLT band
+    expected = O.quant_expected_sqerr(v, b)
+    assert abs(sq / trials - expected) < 0.05 * expected
+    S = O.sum_squares(v)
+    assert expected <= (1 - O.quant_alpha(d, b)) * S * (1 + 1e-9)                # Definition 1
+
+
+@pytest.mark.parametrize("d,b", [(16, 2), (1000, 2), (1000, 4), (1 << 16, 8), (1 << 20, 2)])
+def test_quantizer_expected_error_bound_any_shape(d, b):
+    rng = np.random.default_rng(d + b)
+    v = (rng.standard_t(3, size=d) * 3).astype(np.float32)
+    assert O.quant_expected_sqerr(v, b) <= (1 - O.quant_alpha(d, b)) * O.sum_squares(v) * (1 + 1e-9)
+
+
+def test_level_order_check():
+    d = 1 << 20
+    lv = [(O.QUANT, 2), (O.TOPK, 1049), (O.QUANT, 4), (O.TOPK, 10486), (O.TOPK, 104858), (O.QUANT, 8)]
+    assert O.check_levels(lv, d)
+    assert not O.check_levels(lv[::-1], d)
