@@ -1,0 +1,206 @@
+/*
+ * adacgd.h -- C ABI of the AdaCGD engine for one MI355X (gfx950).
+ *
+ * The library runs, entirely on the device, the iteration of "DCGD with master
+ * compression" (Algorithm 1) in its three-point-compressor form (Algorithm 2,
+ * 3PC-BD) for n simulated workers, with the AdaCGD compressor of Section 4.3 on
+ * both sides:
+ *
+ *     x^{t+1}     = x^t - gamma g^t
+ *     g~_i^{t+1}  = C^AC_{g~_i^t, grad f_i(x^t)}( grad f_i(x^{t+1}) )      i = 1..n
+ *     g~^{t+1}    = (1/n) sum_i g~_i^{t+1}      (kept incrementally from the n messages)
+ *     g^{t+1}     = C^AC_{g^t, g~^t}( g~^{t+1} )                           (master)
+ *
+ * where C^AC_{h,y}(x) returns h if ||x-h||^2 <= zeta ||x-y||^2, otherwise
+ * h + C_j(x-h) (the EF21 form, Eq. (7)) for the first level j < m whose realised
+ * error ||x-h-C_j(x-h)||^2 <= zeta ||x-y||^2 (the trigger, Eq. (10)), otherwise
+ * level m.  Levels are Top-K sparsifiers (Section 2.1; ties: larger |value|
+ * first, then lower index) and b-bit stochastic quantisers.
+ *
+ * Conventions
+ *  - Every function returns an adacgd_status; 0 is success.  Nothing aborts,
+ *    prints or throws.  On failure adacgd_last_error() gives a message.
+ *  - "device" pointers are HIP device addresses on the current device, "host"
+ *    pointers are ordinary process memory.  All vectors are fp32, row-major,
+ *    contiguous.  Reductions are accumulated in fp64.
+ *  - The library allocates no device memory: the caller passes one workspace of
+ *    adacgd_workspace_bytes() bytes (256-byte aligned) that the context owns
+ *    until adacgd_destroy(); everything the engine stores lives there.
+ *  - All work is enqueued on the caller's stream; adacgd_step does not
+ *    synchronise.  adacgd_state synchronises the stream before copying.
+ *  - One context must not be used from two threads at once.
+ */
+#ifndef ADACGD_H
+#define ADACGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct adacgd_ctx adacgd_ctx; /* opaque, host memory owned by the library */
+
+enum adacgd_status {
+  ADACGD_OK = 0,
+  ADACGD_ERR_ARG = 1,    /* null pointer, size out of range, non-finite scalar       */
+  ADACGD_ERR_LEVELS = 2, /* level set not ordered by contraction parameter           */
+  ADACGD_ERR_ALLOC = 3,  /* workspace missing, misaligned or too small               */
+  ADACGD_ERR_DEVICE = 4, /* a HIP call failed                                        */
+  ADACGD_ERR_STATE = 5,  /* call not valid for this context's mode                   */
+  ADACGD_ERR_FIELD = 6   /* unknown field or wrong destination size; nothing written */
+};
+
+/* One compression level.  The AdaCGD definition orders levels from strongest to
+ * weakest compression, alpha_1 <= ... <= alpha_m.  alpha = K/d for Top-K;
+ * alpha = 1/(1+omega), omega = min(d/(4 s^2), sqrt(d)/s), s = 2^(b-1)-1 for b bits. */
+enum adacgd_level_kind { ADACGD_TOPK = 0, ADACGD_QUANT = 1 };
+typedef struct {
+  int32_t kind;  /* adacgd_level_kind                                   */
+  int32_t pad;   /* set to 0                                            */
+  int64_t param; /* TOPK: K in [1,d] (K = d is the identity); QUANT: b in [2,16] */
+} adacgd_level;
+
+#define ADACGD_MAX_LEVELS 16
+
+/* Where grad f_i(x^{t+1}) comes from. */
+enum adacgd_grad_mode {
+  ADACGD_GRAD_LOGISTIC = 0, /* engine computes the gradient of the Section 6 objective:
+                               f_i(x) = (1/N_i) sum_l log(1+exp(-y_l a_l^T x)) + lambda sum_j x_j^2/(1+x_j^2) */
+  ADACGD_GRAD_EXTERNAL = 1, /* caller passes grad f_i(x^{t+1}) to adacgd_step                         */
+  ADACGD_DIFF_EXTERNAL = 2  /* caller passes x - h (the compressor's argument) and ||x-y||^2 directly  */
+};
+
+/* g~_i^0 ("known by nodes" in Algorithm 1's input line; the paper leaves it free). */
+enum adacgd_init_mode {
+  ADACGD_INIT_FULLGRAD = 0, /* g~_i^0 = grad f_i(x^0)  */
+  ADACGD_INIT_ZERO = 1      /* g~_i^0 = 0              */
+};
+
+enum adacgd_flags {
+  ADACGD_FLAG_ANY_LEVEL_ORDER = 1, /* accept level sets not sorted by alpha (Lemma 2 holds for any order) */
+  ADACGD_FLAG_RETAIN_EXT = 2,      /* GRAD_EXTERNAL: keep the caller's last gradient array as y for the
+                                      next step instead of copying it; the caller must leave that array
+                                      untouched until the next adacgd_step call has completed            */
+  ADACGD_FLAG_KERNEL_TIMING = 4    /* record HIP events around every kernel (see ADACGD_F_KERNEL_MS)    */
+};
+
+typedef struct {
+  int64_t n;                    /* workers, 1 <= n <= 65535                                   */
+  int64_t d;                    /* dimension, 1 <= d < 2^31                                   */
+  int32_t grad_mode;            /* adacgd_grad_mode                                           */
+  int32_t init_mode;            /* adacgd_init_mode (DIFF_EXTERNAL requires INIT_ZERO)        */
+  const float* A;               /* LOGISTIC: device [sum N_i x d] features; BORROWED for the context's life */
+  const float* labels;          /* LOGISTIC: device [sum N_i], each -1 or +1; BORROWED       */
+  const int64_t* shard_offsets; /* LOGISTIC: host [n+1], rows of worker i are [off[i],off[i+1]); copied */
+  const float* x0;              /* device [d] starting point; copied                          */
+  const float* grad0;           /* GRAD_EXTERNAL: device [n x d] grad f_i(x^0); copied        */
+  float lambda;                 /* regulariser weight                                         */
+  float gamma;                  /* stepsize, finite                                           */
+  const adacgd_level* worker_levels; /* host [m_worker]; copied                               */
+  int32_t m_worker;             /* 1..ADACGD_MAX_LEVELS                                       */
+  float zeta_worker;            /* trigger constant, finite, >= 0                             */
+  const adacgd_level* master_levels; /* host [m_master]; copied                               */
+  int32_t m_master;             /* 0 = identity master (g = g~); else 1..ADACGD_MAX_LEVELS    */
+  float zeta_master;
+  uint64_t seed;                /* Philox key of the quantiser's dither                       */
+  uint32_t flags;               /* adacgd_flags                                               */
+  uint32_t pad;                 /* set to 0                                                   */
+  void* stream;                 /* hipStream_t; BORROWED                                      */
+  void* workspace;              /* device, 256-byte aligned; owned by the context until destroy */
+  int64_t workspace_bytes;
+} adacgd_config;
+
+/* Device bytes adacgd_init needs for this configuration (workspace and stream
+ * fields are ignored).  Validates the configuration the way adacgd_init does. */
+int adacgd_workspace_bytes(const adacgd_config* cfg, int64_t* bytes);
+
+/* Input line of Algorithm 1: builds the state x^0, g~_i^0, g~^0 = (1/n) sum g~_i^0,
+ * g^0 = g~^0, and y_i = grad f_i(x^0).  On success *out is a new context. */
+int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out);
+
+/* Runs nsteps iterations of Algorithm 2 (all of: iterate update, local gradients,
+ * worker compression with level choice, server aggregation, master compression).
+ *   LOGISTIC      ext = ext_D = NULL.
+ *   GRAD_EXTERNAL ext = device [nsteps x n x d], one gradient array per step; ext_D = NULL.
+ *   DIFF_EXTERNAL ext = device [nsteps x n x d] difference vectors v_i, ext_D = device
+ *                 [nsteps x n] fp64 values of ||x-y||^2; g~_i accumulates C(v_i).
+ * ext must be 16-byte aligned.  Arrays passed in must stay valid until the
+ * enqueued work has completed. */
+int adacgd_step(adacgd_ctx* ctx, const float* ext, const double* ext_D, int32_t nsteps);
+
+/* Fields of adacgd_state.  Sizes in elements; W = worker side, M = master side. */
+enum adacgd_field {
+  ADACGD_F_X = 0,            /* float  [d]     x^t                                            */
+  ADACGD_F_G = 1,            /* float  [d]     g^t                                            */
+  ADACGD_F_GTILDE = 2,       /* float  [d]     g~^t                                           */
+  ADACGD_F_GTILDE_PREV = 3,  /* float  [d]     g~^{t-1}                                       */
+  ADACGD_F_GI = 4,           /* float  [n x d] g~_i^t                                         */
+  ADACGD_F_PREV_GRAD = 5,    /* float  [n x d] grad f_i(x^t)  (not in DIFF_EXTERNAL)          */
+  ADACGD_F_LEVEL = 6,        /* int32  [n]     level of the last step: 0 = skip, 1..m         */
+  ADACGD_F_SQNORM = 7,       /* double [n]     ||x-h||^2 of the last step                     */
+  ADACGD_F_D = 8,            /* double [n]     ||x-y||^2 of the last step                     */
+  ADACGD_F_ERR = 9,          /* double [n x m_worker] realised error of every level           */
+  ADACGD_F_MSG_COUNT = 10,   /* int64  [n]     entries of each worker's last Top-K message    */
+  ADACGD_F_MSG_IDX = 11,     /* int32  [sum counts] coordinates, ascending per worker, packed */
+  ADACGD_F_MSG_VAL = 12,     /* float  [sum counts] values, packed in the same order          */
+  ADACGD_F_M_LEVEL = 13,     /* int32  [1]                                                    */
+  ADACGD_F_M_SQNORM = 14,    /* double [1]                                                    */
+  ADACGD_F_M_D = 15,         /* double [1]                                                    */
+  ADACGD_F_M_ERR = 16,       /* double [m_master]                                             */
+  ADACGD_F_M_MSG_COUNT = 17, /* int64  [1]                                                    */
+  ADACGD_F_M_MSG_IDX = 18,   /* int32  [count]                                                */
+  ADACGD_F_M_MSG_VAL = 19,   /* float  [count]                                                */
+  ADACGD_F_STEP = 20,        /* int64  [1]     iterations done                                */
+  ADACGD_F_LEVEL_HIST = 21,  /* uint64 [m_worker+1] cumulative count of each worker level     */
+  ADACGD_F_M_LEVEL_HIST = 22,/* uint64 [m_master+1]                                           */
+  ADACGD_F_COMM = 23,        /* uint64 [4] cumulative values_up, bits_up, values_down, bits_down:
+                                a Top-K message costs K (32 + ceil(log2 d)) bits, a b-bit message
+                                d b + 32, plus ceil(log2(m+1)) bits for the level id; the master's
+                                message is counted once per worker                             */
+  ADACGD_F_QCODES = 24,      /* int16  [n x d] signed codes of the last quantised messages (rows of
+                                workers that chose another level are unspecified)             */
+  ADACGD_F_QSCALE = 25,      /* float  [n]     scale c of the last quantised message          */
+  ADACGD_F_KERNEL_MS = 26,   /* double [2 x ADACGD_NUM_KERNELS] per kernel: summed milliseconds, then
+                                launch counts, since init or the last query (query resets)    */
+  ADACGD_F_GRAD = 27         /* float  [n x d] same as PREV_GRAD (the gradients of the last step) */
+};
+
+/* Kernel slots of ADACGD_F_KERNEL_MS. */
+enum adacgd_kernel {
+  ADACGD_K_XUPDATE = 0,
+  ADACGD_K_GRAD_MARGIN = 1,
+  ADACGD_K_GRAD_COLS = 2,
+  ADACGD_K_W_SCAN = 3,    /* worker: differences, norms, first-digit histogram */
+  ADACGD_K_W_FILTER = 4,  /* worker: candidate extraction, low-band energy, quantiser errors */
+  ADACGD_K_W_REFINE = 5,
+  ADACGD_K_W_TALLY = 6,   /* band energies, level choice */
+  ADACGD_K_W_COMPACT = 7, /* message + estimator update */
+  ADACGD_K_W_QAPPLY = 8,
+  ADACGD_K_AGGREGATE = 9,
+  ADACGD_K_M_SCAN = 10,
+  ADACGD_K_M_FILTER = 11,
+  ADACGD_K_M_REFINE = 12,
+  ADACGD_K_M_TALLY = 13,
+  ADACGD_K_M_COMPACT = 14,
+  ADACGD_K_M_QAPPLY = 15,
+  ADACGD_NUM_KERNELS = 16
+};
+
+/* Copies one field to dst (host memory, or device memory if dst_on_device != 0)
+ * after synchronising the context's stream.  dst_bytes must equal the field's
+ * size exactly, else ADACGD_ERR_FIELD and nothing is written. */
+int adacgd_state(adacgd_ctx* ctx, int32_t field, void* dst, int64_t dst_bytes, int32_t dst_on_device);
+
+/* Synchronises the stream and frees the context (the workspace returns to the
+ * caller).  NULL is accepted. */
+int adacgd_destroy(adacgd_ctx* ctx);
+
+/* Message of the last failure on this context, or, for ctx == NULL, of the
+ * calling thread's last failed adacgd_init / adacgd_workspace_bytes. */
+const char* adacgd_last_error(const adacgd_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADACGD_H */

@@ -236,7 +236,13 @@ def adacgd_compress(h, y, x, levels, zeta, *, seed=0, node=0, step=0, D_given=No
     d = h.shape[0]
     v = np.asarray(v_given, dtype=dt) if v_given is not None else (x - h).astype(dt)
     S = sum_squares(v)
-    D = float(D_given) if D_given is not None else sum_squares((x - y).astype(dt))
+    same_terms = False        # x - h and x - y are the same vector: S and D are the same sum
+    if D_given is not None:
+        D = float(D_given)
+    else:
+        w = (x - y).astype(dt)
+        D = sum_squares(w)
+        same_terms = bool(np.array_equal(v, w))
     tau = float(np.float64(dt.type(zeta))) * D          # zeta is held in the storage dtype
     m = len(levels)
 
@@ -260,10 +266,16 @@ def adacgd_compress(h, y, x, levels, zeta, *, seed=0, node=0, step=0, D_given=No
     margins = []
 
     def holds(lhs):
-        margins.append(abs(lhs - tau) / max(tau, 1e-300))
+        # relative distance from equality; 0 == 0 is exact on any summation order (every term is zero)
+        margins.append(float("inf") if lhs == 0.0 and tau == 0.0 else abs(lhs - tau) / max(tau, 1e-300))
         return lhs <= tau
 
-    if holds(S):
+    if same_terms and tau == D:
+        margins.append(float("inf"))      # S == D term by term: the comparison is S <= S
+        first = True
+    else:
+        first = holds(S)
+    if first:
         level = 0
     else:
         level = m

@@ -1,0 +1,132 @@
+// Internal interfaces of the AdaCGD engine: device-side data layout of one
+// "node set" (the n workers, or the single master) and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace adacgd {
+
+// Tiling of a length-d vector.  A tile is the unit of candidate grouping:
+// candidates of one tile are stored contiguously and in ascending coordinate.
+constexpr int kBlock = 256;             // threads per block (4 wavefronts of 64)
+constexpr int kIter = 8;                // 16-byte loads per thread per tile
+constexpr int kTile = kIter * kBlock * 4;   // 8192 coordinates
+constexpr int kWaveTile = kTile / 4;    // contiguous share of one wavefront
+
+// Radix digits of the 31-bit magnitude key (bit pattern of |v|), most significant first.
+constexpr int kShift0 = 19, kBins0 = 4096;  // sign-less exponent + 4 mantissa bits
+constexpr int kShift1 = 9, kBins1 = 1024;
+constexpr int kBins2 = 512;
+
+constexpr int kMaxLevels = 16;
+
+enum { kTopK = 0, kQuant = 1 };
+
+// The ordered level set of one side, in the form the kernels use.
+struct LevelTable {
+  int m;                      // levels in cascade order (strongest compression first)
+  int kind[kMaxLevels];       // kTopK / kQuant
+  int ref[kMaxLevels];        // kTopK: slot index into K[]; kQuant: index into qs[]
+  int p;                      // distinct Top-K sizes ("slots")
+  uint32_t K[kMaxLevels];     // ascending
+  int nq;                     // quantiser levels
+  int qbits[kMaxLevels];
+  float qs[kMaxLevels];       // s = 2^(b-1) - 1 magnitude levels
+  double qdenom[kMaxLevels];  // s (1 + omega)
+  double zeta;                // trigger constant, the fp32 argument widened
+};
+
+// Device arrays of one side.  nn nodes, each with a length-d vector.
+struct NodeSet {
+  int nn;
+  int64_t d;
+  int tiles;        // ceil(d / kTile)
+  int G;            // blocks per node of the streaming kernels (scan, filter)
+  int G2;           // blocks per node of the candidate kernels (4 groups per block at a time)
+  uint32_t Kcap;    // message capacity per node = largest Top-K size (0 if none)
+  LevelTable lv;
+
+  uint32_t* hist0;      // [nn][kBins0]           first-digit counts; zero between launches
+  uint32_t* ref1;       // [nn][p][kBins1]        second-digit counts inside each slot's bin
+  uint32_t* ref2;       // [nn][p][kBins2]        third digit
+  uint32_t* prefix;     // [nn][p]                known high bits of slot threshold T_s (12, 22, 31 bits)
+  uint32_t* rank;       // [nn][p]                rank of the K_s-th element inside the prefix
+  uint32_t* eqcnt;      // [nn][p]                count of keys equal to T_s
+  uint32_t* bmin;       // [nn]                   lowest first-digit bin that holds candidates
+  uint32_t* done;       // [nn]                   arrival counter of the last-block epilogues
+  uint32_t* cursor;     // [nn]                   candidates reserved so far
+  uint32_t* kmax;       // [nn]                   running max magnitude key of the current scan; zero between launches
+  uint32_t* amax;       // [nn]                   max magnitude key of the last scan (quantiser scale a)
+  double* partS;        // [nn][G]
+  double* partD;        // [nn][G]
+  double* partEb;       // [nn][G]
+  double* partQ;        // [nn][G][nq]
+  double* partStrict;   // [nn][G2][p]
+  double* S;            // [nn]  ||x-h||^2
+  double* D;            // [nn]  ||x-y||^2
+  double* Eb;           // [nn]  energy below the candidate bins
+  double* qerr;         // [nn][nq]
+  double* err;          // [nn][m]
+  uint32_t* grp_start;  // [nn][tiles]  offset of the tile's candidates in the node's list
+  uint32_t* grp_count;  // [nn][tiles]
+  uint32_t* cnt_gt;     // [nn][p][tiles]  candidates with key > T_s
+  uint32_t* cnt_eq;     // [nn][p][tiles]  candidates with key == T_s
+  uint32_t* out_off;    // [nn][tiles+1]   message offset of the tile for the chosen level
+  uint32_t* eq_before;  // [nn][tiles]     ties in earlier tiles
+  uint2* cand;          // [nn][d]         (coordinate, value bits), grouped by tile
+  int32_t* level;       // [nn]   0 = skip
+  int32_t* sel_slot;    // [nn]   slot of the chosen Top-K level, -1 otherwise
+  int32_t* sel_q;       // [nn]   quantiser index of the chosen level, -1 otherwise
+  uint32_t* sel_T;      // [nn]
+  uint32_t* sel_r;      // [nn]
+  uint32_t* msg_count;  // [nn]
+  int32_t* msg_idx;     // [nn][Kcap]
+  float* msg_val;       // [nn][Kcap]
+  unsigned long long* level_hist;  // [m+1]
+  int16_t* qcodes;      // [nn][d] (only with quantiser levels)
+  float* qscale;        // [nn]
+};
+
+// Operands of one application of the compressor C_{h,y}(x) to every node of a set.
+struct PassArgs {
+  const float* x;      // [nn][d]  new point; in difference mode the difference vector itself
+  float* h;            // [nn][d]  stored estimator, updated in place
+  const float* y;      // [nn][d]  previous point (unused in difference mode)
+  float* ycopy;        // optional [nn][d]: receives a copy of x
+  const double* extD;  // difference mode: [nn] given ||x-y||^2
+  int diff;            // 1 = difference mode
+  uint64_t seed;       // Philox key
+  uint32_t step;       // Philox counter word 2
+  uint32_t node_flag;  // OR-ed into counter word 1 (0 for workers, 2^31 for the master)
+};
+
+struct LogisticData {
+  const float* A;
+  const float* labels;
+  const int64_t* offsets;  // device [n+1]
+  const int32_t* row_node; // device [rows]
+  int64_t rows;
+  int64_t max_rows;        // largest shard
+  double lambda;
+  double* margins;         // [rows]  s_l = -y_l / (1 + exp(y_l a_l^T x)) / N_i
+  double* part;            // [n][row_chunks][d] when row_chunks > 1
+  int row_chunks;
+};
+
+// launchers (each enqueues on the stream and returns the launch status)
+hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st);
+hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st);
+hipError_t launch_refine(const NodeSet& ns, hipStream_t st);
+hipError_t launch_tally(const NodeSet& ns, hipStream_t st);
+hipError_t launch_compact(const NodeSet& ns, const PassArgs& a, hipStream_t st);
+hipError_t launch_qapply(const NodeSet& ns, const PassArgs& a, hipStream_t st);
+
+hipError_t launch_xupdate(float* x, const float* g, double gamma, int64_t d, hipStream_t st);
+hipError_t launch_mean(const float* gi, float* out0, float* out1, float* out2, int n, int64_t d, hipStream_t st);
+hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_new, hipStream_t st);
+hipError_t launch_fill_u32(uint32_t* p, uint32_t v, size_t count, hipStream_t st);
+hipError_t launch_copy_f32(float* dst, const float* src, size_t count, hipStream_t st);
+hipError_t launch_grad_margins(const LogisticData& ld, const float* x, int64_t d, hipStream_t st);
+hipError_t launch_grad_cols(const LogisticData& ld, const float* x, float* grads, int n, int64_t d, hipStream_t st);
+
+}  // namespace adacgd

@@ -1,0 +1,700 @@
+// Host side of the AdaCGD engine: configuration checks, workspace layout, the
+// kernel sequence of one iteration of Algorithm 2, and the C ABI of adacgd.h.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/adacgd.h"
+#include "engine.h"
+
+using namespace adacgd;
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+void set_err(char* buf, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void set_err(char* buf, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, 256, fmt, ap);
+  va_end(ap);
+}
+
+// bump allocator over the caller's workspace; with base == nullptr it only measures
+struct Carver {
+  char* base;
+  size_t off = 0;
+  template <typename T>
+  T* take(size_t count) {
+    off = (off + 255) & ~size_t(255);
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+double level_alpha(const adacgd_level& lv, int64_t d) {
+  if (lv.kind == ADACGD_TOPK) return (double)lv.param / (double)d;
+  const double s = (double)((1 << (lv.param - 1)) - 1);
+  const double w = std::fmin((double)d / (4.0 * s * s), std::sqrt((double)d) / s);
+  return 1.0 / (1.0 + w);
+}
+
+int build_levels(const adacgd_level* in, int m, float zeta, int64_t d, uint32_t flags, LevelTable* lt, char* err) {
+  std::memset(lt, 0, sizeof(*lt));
+  if (m < 0 || m > ADACGD_MAX_LEVELS) { set_err(err, "level count %d out of range", m); return ADACGD_ERR_ARG; }
+  if (m > 0 && !in) { set_err(err, "level array is null"); return ADACGD_ERR_ARG; }
+  if (!std::isfinite(zeta) || zeta < 0.f) { set_err(err, "zeta must be finite and >= 0"); return ADACGD_ERR_ARG; }
+  lt->m = m;
+  lt->zeta = (double)zeta;
+  for (int j = 0; j < m; ++j) {
+    if (in[j].kind == ADACGD_TOPK) {
+      if (in[j].param < 1 || in[j].param > d) {
+        set_err(err, "level %d: Top-K needs 1 <= K <= d, got %lld", j + 1, (long long)in[j].param);
+        return ADACGD_ERR_ARG;
+      }
+    } else if (in[j].kind == ADACGD_QUANT) {
+      if (in[j].param < 2 || in[j].param > 16) {
+        set_err(err, "level %d: quantiser needs 2 <= b <= 16, got %lld", j + 1, (long long)in[j].param);
+        return ADACGD_ERR_ARG;
+      }
+    } else {
+      set_err(err, "level %d: unknown kind %d", j + 1, in[j].kind);
+      return ADACGD_ERR_ARG;
+    }
+    if (j > 0 && !(flags & ADACGD_FLAG_ANY_LEVEL_ORDER) && level_alpha(in[j - 1], d) > level_alpha(in[j], d)) {
+      set_err(err, "levels %d and %d are not ordered by contraction parameter", j, j + 1);
+      return ADACGD_ERR_LEVELS;
+    }
+  }
+  // distinct Top-K sizes ascending -> slots
+  std::vector<uint32_t> ks;
+  for (int j = 0; j < m; ++j)
+    if (in[j].kind == ADACGD_TOPK) ks.push_back((uint32_t)in[j].param);
+  std::sort(ks.begin(), ks.end());
+  ks.erase(std::unique(ks.begin(), ks.end()), ks.end());
+  lt->p = (int)ks.size();
+  for (int s = 0; s < lt->p; ++s) lt->K[s] = ks[s];
+  for (int j = 0; j < m; ++j) {
+    lt->kind[j] = in[j].kind == ADACGD_TOPK ? kTopK : kQuant;
+    if (in[j].kind == ADACGD_TOPK) {
+      lt->ref[j] = (int)(std::lower_bound(ks.begin(), ks.end(), (uint32_t)in[j].param) - ks.begin());
+    } else {
+      const int b = (int)in[j].param;
+      int q = -1;
+      for (int i = 0; i < lt->nq; ++i)
+        if (lt->qbits[i] == b) q = i;
+      if (q < 0) {
+        q = lt->nq++;
+        const double s = (double)((1 << (b - 1)) - 1);
+        const double w = std::fmin((double)d / (4.0 * s * s), std::sqrt((double)d) / s);
+        lt->qbits[q] = b;
+        lt->qs[q] = (float)s;
+        lt->qdenom[q] = s * (1.0 + w);
+      }
+      lt->ref[j] = q;
+    }
+  }
+  return ADACGD_OK;
+}
+
+void carve_nodeset(Carver& c, NodeSet& ns) {
+  const size_t nn = ns.nn, p = ns.lv.p, nq = ns.lv.nq, m = ns.lv.m, tiles = ns.tiles;
+  ns.hist0 = c.take<uint32_t>(nn * kBins0);
+  ns.ref1 = c.take<uint32_t>(nn * p * kBins1);
+  ns.ref2 = c.take<uint32_t>(nn * p * kBins2);
+  ns.done = c.take<uint32_t>(nn);
+  ns.kmax = c.take<uint32_t>(nn);
+  ns.level_hist = c.take<unsigned long long>(m + 1);
+  // everything up to here must start at zero
+  ns.prefix = c.take<uint32_t>(nn * p);
+  ns.rank = c.take<uint32_t>(nn * p);
+  ns.eqcnt = c.take<uint32_t>(nn * p);
+  ns.bmin = c.take<uint32_t>(nn);
+  ns.amax = c.take<uint32_t>(nn);
+  ns.cursor = c.take<uint32_t>(nn);
+  ns.partS = c.take<double>(nn * ns.G);
+  ns.partD = c.take<double>(nn * ns.G);
+  ns.partEb = c.take<double>(nn * ns.G);
+  ns.partQ = c.take<double>(nn * ns.G * nq);
+  ns.partStrict = c.take<double>(nn * ns.G2 * p);
+  ns.S = c.take<double>(nn);
+  ns.D = c.take<double>(nn);
+  ns.Eb = c.take<double>(nn);
+  ns.qerr = c.take<double>(nn * nq);
+  ns.err = c.take<double>(nn * m);
+  ns.grp_start = c.take<uint32_t>(nn * tiles);
+  ns.grp_count = c.take<uint32_t>(nn * tiles);
+  ns.cnt_gt = c.take<uint32_t>(nn * p * tiles);
+  ns.cnt_eq = c.take<uint32_t>(nn * p * tiles);
+  ns.out_off = c.take<uint32_t>(nn * (tiles + 1));
+  ns.eq_before = c.take<uint32_t>(nn * tiles);
+  ns.cand = p ? c.take<uint2>(nn * (size_t)ns.d) : nullptr;
+  ns.level = c.take<int32_t>(nn);
+  ns.sel_slot = c.take<int32_t>(nn);
+  ns.sel_q = c.take<int32_t>(nn);
+  ns.sel_T = c.take<uint32_t>(nn);
+  ns.sel_r = c.take<uint32_t>(nn);
+  ns.msg_count = c.take<uint32_t>(nn);
+  ns.msg_idx = c.take<int32_t>(nn * (size_t)ns.Kcap);
+  ns.msg_val = c.take<float>(nn * (size_t)ns.Kcap);
+  ns.qcodes = nq ? c.take<int16_t>(nn * (size_t)ns.d) : nullptr;
+  ns.qscale = c.take<float>(nn);
+}
+
+void shape_nodeset(NodeSet& ns, int nn, int64_t d) {
+  ns.nn = nn;
+  ns.d = d;
+  ns.tiles = (int)((d + kTile - 1) / kTile);
+  const int want = (2560 + nn - 1) / nn;
+  ns.G = ns.tiles < want ? ns.tiles : want;
+  if (ns.G < 1) ns.G = 1;
+  const int g2 = (ns.tiles + 3) / 4;
+  ns.G2 = g2 < 512 ? g2 : 512;
+  ns.Kcap = ns.lv.p ? ns.lv.K[ns.lv.p - 1] : 0;
+}
+
+}  // namespace
+
+struct adacgd_ctx {
+  int64_t n, d;
+  int grad_mode;
+  uint32_t flags;
+  double gamma;
+  uint64_t seed;
+  hipStream_t st;
+  char* ws_base;
+  NodeSet W, M;
+  bool has_master;
+  float* x;
+  float* g_own;     // master estimator g when the master compresses
+  float* gt[2];     // g~^t and g~^{t-1}; cur indexes g~^t
+  int cur;
+  float* gi;        // [n][d] worker estimators
+  float* yb[2];     // [n][d] gradient buffers
+  int ycur;         // yb[ycur] holds grad f_i(x^t) unless y_ext is set
+  const float* y_ext;
+  LogisticData ld;
+  int64_t step;
+  uint64_t w_zero_bytes, m_zero_bytes;
+  char err[256];
+  // kernel timing
+  bool timing;
+  struct Span { int slot; hipEvent_t a, b; };
+  std::vector<Span> spans;
+  std::vector<hipEvent_t> pool;
+  double ms_sum[ADACGD_NUM_KERNELS];
+  double ms_cnt[ADACGD_NUM_KERNELS];
+
+  const float* g() const { return has_master ? g_own : gt[cur]; }
+  const float* ycurp() const { return y_ext ? y_ext : yb[ycur]; }
+};
+
+namespace {
+
+int validate(const adacgd_config* cfg, LevelTable* wl, LevelTable* ml, char* err) {
+  if (!cfg) { set_err(err, "config is null"); return ADACGD_ERR_ARG; }
+  if (cfg->n < 1 || cfg->n > 65535) { set_err(err, "n must be in [1, 65535]"); return ADACGD_ERR_ARG; }
+  if (cfg->d < 1 || cfg->d >= (int64_t(1) << 31)) { set_err(err, "d must be in [1, 2^31)"); return ADACGD_ERR_ARG; }
+  if (cfg->grad_mode < 0 || cfg->grad_mode > 2) { set_err(err, "unknown grad_mode"); return ADACGD_ERR_ARG; }
+  if (cfg->init_mode < 0 || cfg->init_mode > 1) { set_err(err, "unknown init_mode"); return ADACGD_ERR_ARG; }
+  if (cfg->grad_mode == ADACGD_DIFF_EXTERNAL && cfg->init_mode != ADACGD_INIT_ZERO) {
+    set_err(err, "DIFF_EXTERNAL requires INIT_ZERO");
+    return ADACGD_ERR_ARG;
+  }
+  if (!std::isfinite(cfg->gamma)) { set_err(err, "gamma must be finite"); return ADACGD_ERR_ARG; }
+  if (cfg->m_worker < 1) { set_err(err, "at least one worker level is required"); return ADACGD_ERR_ARG; }
+  int rc = build_levels(cfg->worker_levels, cfg->m_worker, cfg->zeta_worker, cfg->d, cfg->flags, wl, err);
+  if (rc) return rc;
+  rc = build_levels(cfg->master_levels, cfg->m_master, cfg->zeta_master, cfg->d, cfg->flags, ml, err);
+  if (rc) return rc;
+  if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC) {
+    if (!cfg->shard_offsets) { set_err(err, "shard_offsets is null"); return ADACGD_ERR_ARG; }
+    if (!std::isfinite(cfg->lambda)) { set_err(err, "lambda must be finite"); return ADACGD_ERR_ARG; }
+    if (cfg->shard_offsets[0] != 0) { set_err(err, "shard_offsets[0] must be 0"); return ADACGD_ERR_ARG; }
+    for (int64_t i = 0; i < cfg->n; ++i)
+      if (cfg->shard_offsets[i + 1] <= cfg->shard_offsets[i]) {
+        set_err(err, "worker %lld has an empty shard", (long long)i);
+        return ADACGD_ERR_ARG;
+      }
+  }
+  return ADACGD_OK;
+}
+
+struct Layout {
+  float *x, *g_own, *gt0, *gt1, *gi, *yb0, *yb1;
+  int64_t* offsets;
+  int32_t* row_node;
+  double* margins;
+  double* part;
+  size_t w_zero, m_zero;
+};
+
+size_t carve_all(char* base, const adacgd_config* cfg, NodeSet& W, NodeSet& M, LogisticData& ld, Layout& L) {
+  Carver c{base};
+  const size_t n = cfg->n, d = cfg->d;
+  const size_t w0 = c.off;
+  carve_nodeset(c, W);
+  // the arrays that must be zero come first in carve_nodeset: up to and including level_hist
+  L.w_zero = base ? (size_t)((char*)W.prefix - (char*)W.hist0) : 0;
+  (void)w0;
+  if (M.lv.m > 0) {
+    carve_nodeset(c, M);
+    L.m_zero = base ? (size_t)((char*)M.prefix - (char*)M.hist0) : 0;
+  }
+  L.x = c.take<float>(d);
+  L.g_own = M.lv.m > 0 ? c.take<float>(d) : nullptr;
+  L.gt0 = c.take<float>(d);
+  L.gt1 = c.take<float>(d);
+  L.gi = c.take<float>(n * d);
+  if (cfg->grad_mode != ADACGD_DIFF_EXTERNAL) {
+    L.yb0 = c.take<float>(n * d);
+    const bool second = cfg->grad_mode == ADACGD_GRAD_LOGISTIC || !(cfg->flags & ADACGD_FLAG_RETAIN_EXT);
+    L.yb1 = second ? c.take<float>(n * d) : nullptr;
+  } else {
+    L.yb0 = L.yb1 = nullptr;
+  }
+  if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC) {
+    const size_t rows = cfg->shard_offsets[n];
+    L.offsets = c.take<int64_t>(n + 1);
+    L.row_node = c.take<int32_t>(rows);
+    L.margins = c.take<double>(rows);
+    L.part = ld.row_chunks > 1 ? c.take<double>(n * ld.row_chunks * d) : nullptr;
+  } else {
+    L.offsets = nullptr; L.row_node = nullptr; L.margins = nullptr; L.part = nullptr;
+  }
+  return (c.off + 255) & ~size_t(255);
+}
+
+void shape_logistic(const adacgd_config* cfg, LogisticData& ld) {
+  std::memset(&ld, 0, sizeof(ld));
+  if (cfg->grad_mode != ADACGD_GRAD_LOGISTIC) return;
+  ld.rows = cfg->shard_offsets[cfg->n];
+  int64_t mx = 0;
+  for (int64_t i = 0; i < cfg->n; ++i) mx = std::max<int64_t>(mx, cfg->shard_offsets[i + 1] - cfg->shard_offsets[i]);
+  ld.max_rows = mx;
+  int64_t chunks = (mx + 63) / 64;      // about 64 rows per block ...
+  if (chunks > 64) chunks = 64;         // ... but a bounded number of partial sums
+  ld.row_chunks = (int)chunks;
+  ld.lambda = (double)cfg->lambda;
+}
+
+#define HIPCHK(ctx, call)                                                            \
+  do {                                                                               \
+    hipError_t e_ = (call);                                                          \
+    if (e_ != hipSuccess) {                                                          \
+      set_err((ctx)->err, "%s failed: %s", #call, hipGetErrorString(e_));            \
+      return ADACGD_ERR_DEVICE;                                                      \
+    }                                                                                \
+  } while (0)
+
+template <typename F>
+int timed(adacgd_ctx* c, int slot, F&& f) {
+  hipEvent_t a = nullptr, b = nullptr;
+  if (c->timing) {
+    for (hipEvent_t* e : {&a, &b}) {
+      if (!c->pool.empty()) { *e = c->pool.back(); c->pool.pop_back(); }
+      else HIPCHK(c, hipEventCreate(e));
+    }
+    HIPCHK(c, hipEventRecord(a, c->st));
+  }
+  hipError_t e = f();
+  if (e != hipSuccess) {
+    set_err(c->err, "kernel launch (slot %d) failed: %s", slot, hipGetErrorString(e));
+    return ADACGD_ERR_DEVICE;
+  }
+  if (c->timing) {
+    HIPCHK(c, hipEventRecord(b, c->st));
+    c->spans.push_back({slot, a, b});
+  }
+  return ADACGD_OK;
+}
+
+int drain_spans(adacgd_ctx* c) {
+  for (auto& s : c->spans) {
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, s.a, s.b));
+    c->ms_sum[s.slot] += ms;
+    c->ms_cnt[s.slot] += 1.0;
+    c->pool.push_back(s.a);
+    c->pool.push_back(s.b);
+  }
+  c->spans.clear();
+  return ADACGD_OK;
+}
+
+// one application of the AdaCGD compressor to every node of a set
+int compress(adacgd_ctx* c, NodeSet& ns, const PassArgs& a, int slot0) {
+  int rc;
+  if ((rc = timed(c, slot0 + 0, [&] { return launch_scan(ns, a, c->st); }))) return rc;
+  if ((rc = timed(c, slot0 + 1, [&] { return launch_filter(ns, a, c->st); }))) return rc;
+  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 2, [&] { return launch_refine(ns, c->st); }))) return rc;
+  if ((rc = timed(c, slot0 + 3, [&] { return launch_tally(ns, c->st); }))) return rc;
+  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 4, [&] { return launch_compact(ns, a, c->st); }))) return rc;
+  if (ns.lv.nq > 0 && (rc = timed(c, slot0 + 5, [&] { return launch_qapply(ns, a, c->st); }))) return rc;
+  return ADACGD_OK;
+}
+
+int gradients(adacgd_ctx* c, float* out) {
+  int rc;
+  if ((rc = timed(c, ADACGD_K_GRAD_MARGIN, [&] { return launch_grad_margins(c->ld, c->x, c->d, c->st); }))) return rc;
+  return timed(c, ADACGD_K_GRAD_COLS, [&] { return launch_grad_cols(c->ld, c->x, out, (int)c->n, c->d, c->st); });
+}
+
+int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
+  int rc;
+  // x^{t+1} = x^t - gamma g^t
+  if ((rc = timed(c, ADACGD_K_XUPDATE, [&] { return launch_xupdate(c->x, c->g(), c->gamma, c->d, c->st); })))
+    return rc;
+  PassArgs a{};
+  a.h = c->gi;
+  a.seed = c->seed;
+  a.step = (uint32_t)c->step;
+  a.node_flag = 0;
+  if (c->grad_mode == ADACGD_GRAD_LOGISTIC) {
+    float* fresh = c->yb[c->ycur ^ 1];
+    if ((rc = gradients(c, fresh))) return rc;
+    a.x = fresh;
+    a.y = c->yb[c->ycur];
+  } else if (c->grad_mode == ADACGD_GRAD_EXTERNAL) {
+    a.x = ext;
+    a.y = c->ycurp();
+    a.ycopy = (c->flags & ADACGD_FLAG_RETAIN_EXT) ? nullptr : c->yb[c->ycur ^ 1];
+  } else {
+    a.x = ext;
+    a.diff = 1;
+    a.extD = extD;
+  }
+  // g~_i^{t+1} = C^AC_{g~_i^t, grad f_i(x^t)}(grad f_i(x^{t+1}))
+  if ((rc = compress(c, c->W, a, ADACGD_K_W_SCAN))) return rc;
+  if (c->grad_mode == ADACGD_GRAD_LOGISTIC) {
+    c->ycur ^= 1;
+  } else if (c->grad_mode == ADACGD_GRAD_EXTERNAL) {
+    if (c->flags & ADACGD_FLAG_RETAIN_EXT) c->y_ext = ext;
+    else c->ycur ^= 1;
+  }
+  // g~^{t+1} = g~^t + (1/n) sum_i messages
+  float* gt_old = c->gt[c->cur];
+  float* gt_new = c->gt[c->cur ^ 1];
+  if ((rc = timed(c, ADACGD_K_AGGREGATE, [&] { return launch_aggregate(c->W, gt_old, gt_new, c->st); }))) return rc;
+  c->cur ^= 1;
+  // g^{t+1} = C^AC_{g^t, g~^t}(g~^{t+1})
+  if (c->has_master) {
+    PassArgs m{};
+    m.x = gt_new;
+    m.h = c->g_own;
+    m.y = gt_old;
+    m.seed = c->seed;
+    m.step = (uint32_t)c->step;
+    m.node_flag = 0x80000000u;
+    if ((rc = compress(c, c->M, m, ADACGD_K_M_SCAN))) return rc;
+  }
+  c->step += 1;
+  return ADACGD_OK;
+}
+
+uint64_t ceil_log2(uint64_t v) {
+  uint64_t b = 0;
+  while ((uint64_t(1) << b) < v) ++b;
+  return b;
+}
+
+void comm_of(const NodeSet& ns, const unsigned long long* hist, uint64_t copies, uint64_t* values, uint64_t* bits) {
+  const uint64_t idb = std::max<uint64_t>(1, ceil_log2((uint64_t)ns.lv.m + 1));
+  const uint64_t ib = std::max<uint64_t>(1, ceil_log2((uint64_t)ns.d));
+  *values = 0;
+  *bits = 0;
+  for (int j = 0; j <= ns.lv.m; ++j) {
+    uint64_t v = 0, b = idb;
+    if (j > 0) {
+      if (ns.lv.kind[j - 1] == kTopK) {
+        v = ns.lv.K[ns.lv.ref[j - 1]];
+        b += v * (32 + ib);
+      } else {
+        v = (uint64_t)ns.d;
+        b += (uint64_t)ns.d * ns.lv.qbits[ns.lv.ref[j - 1]] + 32;
+      }
+    }
+    *values += hist[j] * v * copies;
+    *bits += hist[j] * b * copies;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int adacgd_workspace_bytes(const adacgd_config* cfg, int64_t* bytes) {
+  LevelTable wl, ml;
+  int rc = validate(cfg, &wl, &ml, g_err);
+  if (rc) return rc;
+  if (!bytes) { set_err(g_err, "bytes is null"); return ADACGD_ERR_ARG; }
+  NodeSet W{}, M{};
+  W.lv = wl; M.lv = ml;
+  shape_nodeset(W, (int)cfg->n, cfg->d);
+  shape_nodeset(M, 1, cfg->d);
+  LogisticData ld;
+  shape_logistic(cfg, ld);
+  Layout L{};
+  *bytes = (int64_t)carve_all(nullptr, cfg, W, M, ld, L);
+  return ADACGD_OK;
+}
+
+int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
+  LevelTable wl, ml;
+  int rc = validate(cfg, &wl, &ml, g_err);
+  if (rc) return rc;
+  if (!out) { set_err(g_err, "out is null"); return ADACGD_ERR_ARG; }
+  *out = nullptr;
+  if (!cfg->x0) { set_err(g_err, "x0 is null"); return ADACGD_ERR_ARG; }
+  if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC && (!cfg->A || !cfg->labels)) {
+    set_err(g_err, "A / labels is null");
+    return ADACGD_ERR_ARG;
+  }
+  if (cfg->grad_mode == ADACGD_GRAD_EXTERNAL && !cfg->grad0) {
+    set_err(g_err, "grad0 is required in GRAD_EXTERNAL mode");
+    return ADACGD_ERR_ARG;
+  }
+  if (!cfg->workspace || (reinterpret_cast<uintptr_t>(cfg->workspace) & 255u)) {
+    set_err(g_err, "workspace is null or not 256-byte aligned");
+    return ADACGD_ERR_ALLOC;
+  }
+  adacgd_ctx* c = new (std::nothrow) adacgd_ctx();
+  if (!c) { set_err(g_err, "out of host memory"); return ADACGD_ERR_ALLOC; }
+  c->n = cfg->n; c->d = cfg->d; c->grad_mode = cfg->grad_mode; c->flags = cfg->flags;
+  c->gamma = (double)cfg->gamma; c->seed = cfg->seed; c->st = (hipStream_t)cfg->stream;
+  c->ws_base = (char*)cfg->workspace;
+  c->has_master = cfg->m_master > 0;
+  c->timing = (cfg->flags & ADACGD_FLAG_KERNEL_TIMING) != 0;
+  c->step = 0; c->cur = 0; c->ycur = 0; c->y_ext = nullptr; c->err[0] = 0;
+  std::memset(c->ms_sum, 0, sizeof(c->ms_sum));
+  std::memset(c->ms_cnt, 0, sizeof(c->ms_cnt));
+  c->W = NodeSet{}; c->M = NodeSet{};
+  c->W.lv = wl; c->M.lv = ml;
+  shape_nodeset(c->W, (int)cfg->n, cfg->d);
+  shape_nodeset(c->M, 1, cfg->d);
+  shape_logistic(cfg, c->ld);
+  Layout L{};
+  const size_t need = carve_all(c->ws_base, cfg, c->W, c->M, c->ld, L);
+  if ((int64_t)need > cfg->workspace_bytes) {
+    set_err(g_err, "workspace too small: need %zu bytes, got %lld", need, (long long)cfg->workspace_bytes);
+    delete c;
+    return ADACGD_ERR_ALLOC;
+  }
+  c->x = L.x; c->g_own = L.g_own; c->gt[0] = L.gt0; c->gt[1] = L.gt1; c->gi = L.gi;
+  c->yb[0] = L.yb0; c->yb[1] = L.yb1;
+  c->ld.A = cfg->A; c->ld.labels = cfg->labels; c->ld.offsets = L.offsets; c->ld.row_node = L.row_node;
+  c->ld.margins = L.margins; c->ld.part = L.part;
+
+  auto fail = [&](int code) { std::memcpy(g_err, c->err, sizeof(g_err)); delete c; return code; };
+#define INITCHK(call)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (call);                                                                 \
+    if (e_ != hipSuccess) {                                                                 \
+      set_err(c->err, "%s failed: %s", #call, hipGetErrorString(e_));                       \
+      return fail(ADACGD_ERR_DEVICE);                                                       \
+    }                                                                                       \
+  } while (0)
+
+  const size_t nd = (size_t)c->n * (size_t)c->d;
+  INITCHK(launch_fill_u32((uint32_t*)c->W.hist0, 0u, L.w_zero / 4, c->st));
+  if (c->has_master) INITCHK(launch_fill_u32((uint32_t*)c->M.hist0, 0u, L.m_zero / 4, c->st));
+  INITCHK(launch_copy_f32(c->x, cfg->x0, (size_t)c->d, c->st));
+  if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC) {
+    std::vector<int32_t> rn((size_t)c->ld.rows);
+    for (int64_t i = 0; i < c->n; ++i)
+      for (int64_t l = cfg->shard_offsets[i]; l < cfg->shard_offsets[i + 1]; ++l) rn[(size_t)l] = (int32_t)i;
+    INITCHK(hipMemcpyAsync(L.offsets, cfg->shard_offsets, (size_t)(c->n + 1) * sizeof(int64_t), hipMemcpyHostToDevice,
+                           c->st));
+    INITCHK(hipMemcpyAsync(L.row_node, rn.data(), rn.size() * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+    INITCHK(hipStreamSynchronize(c->st));   // rn goes out of scope
+    INITCHK(launch_grad_margins(c->ld, c->x, c->d, c->st));
+    INITCHK(launch_grad_cols(c->ld, c->x, c->yb[0], (int)c->n, c->d, c->st));
+  } else if (cfg->grad_mode == ADACGD_GRAD_EXTERNAL) {
+    INITCHK(launch_copy_f32(c->yb[0], cfg->grad0, nd, c->st));
+  }
+  if (cfg->init_mode == ADACGD_INIT_FULLGRAD) INITCHK(launch_copy_f32(c->gi, c->yb[0], nd, c->st));
+  else INITCHK(launch_fill_u32((uint32_t*)c->gi, 0u, nd, c->st));
+  INITCHK(launch_mean(c->gi, c->gt[0], c->gt[1], c->g_own, (int)c->n, c->d, c->st));
+  // message tables start empty
+  INITCHK(launch_fill_u32((uint32_t*)c->W.sel_slot, 0xFFFFFFFFu, (size_t)c->n, c->st));
+  INITCHK(launch_fill_u32((uint32_t*)c->W.sel_q, 0xFFFFFFFFu, (size_t)c->n, c->st));
+  INITCHK(launch_fill_u32(c->W.msg_count, 0u, (size_t)c->n, c->st));
+  INITCHK(launch_fill_u32((uint32_t*)c->W.level, 0u, (size_t)c->n, c->st));
+  if (c->has_master) {
+    INITCHK(launch_fill_u32((uint32_t*)c->M.sel_slot, 0xFFFFFFFFu, 1, c->st));
+    INITCHK(launch_fill_u32((uint32_t*)c->M.sel_q, 0xFFFFFFFFu, 1, c->st));
+    INITCHK(launch_fill_u32(c->M.msg_count, 0u, 1, c->st));
+    INITCHK(launch_fill_u32((uint32_t*)c->M.level, 0u, 1, c->st));
+  }
+#undef INITCHK
+  *out = c;
+  return ADACGD_OK;
+}
+
+int adacgd_step(adacgd_ctx* c, const float* ext, const double* ext_D, int32_t nsteps) {
+  if (!c) return ADACGD_ERR_ARG;
+  if (nsteps < 0) { set_err(c->err, "nsteps < 0"); return ADACGD_ERR_ARG; }
+  if (c->grad_mode == ADACGD_GRAD_LOGISTIC) {
+    if (ext || ext_D) { set_err(c->err, "LOGISTIC mode takes no external arrays"); return ADACGD_ERR_STATE; }
+  } else {
+    if (!ext) { set_err(c->err, "ext is null"); return ADACGD_ERR_ARG; }
+    if (reinterpret_cast<uintptr_t>(ext) & 15u) { set_err(c->err, "ext is not 16-byte aligned"); return ADACGD_ERR_ARG; }
+    if (c->grad_mode == ADACGD_DIFF_EXTERNAL && !ext_D) { set_err(c->err, "ext_D is null"); return ADACGD_ERR_ARG; }
+    if (c->grad_mode == ADACGD_GRAD_EXTERNAL && ext_D) {
+      set_err(c->err, "ext_D is only used in DIFF_EXTERNAL mode");
+      return ADACGD_ERR_STATE;
+    }
+  }
+  const size_t nd = (size_t)c->n * (size_t)c->d;
+  for (int32_t s = 0; s < nsteps; ++s) {
+    int rc = one_step(c, ext ? ext + (size_t)s * nd : nullptr, ext_D ? ext_D + (size_t)s * c->n : nullptr);
+    if (rc) return rc;
+  }
+  return ADACGD_OK;
+}
+
+int adacgd_state(adacgd_ctx* c, int32_t field, void* dst, int64_t dst_bytes, int32_t dst_on_device) {
+  if (!c) return ADACGD_ERR_ARG;
+  if (!dst && dst_bytes != 0) { set_err(c->err, "dst is null"); return ADACGD_ERR_ARG; }
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  const int64_t n = c->n, d = c->d;
+  const hipMemcpyKind kind = dst_on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
+  auto copy = [&](const void* src, int64_t bytes) -> int {
+    if (bytes != dst_bytes) {
+      set_err(c->err, "field %d holds %lld bytes, destination has %lld", field, (long long)bytes, (long long)dst_bytes);
+      return ADACGD_ERR_FIELD;
+    }
+    if (bytes == 0) return ADACGD_OK;
+    if (!src) { set_err(c->err, "field %d is not kept in this mode", field); return ADACGD_ERR_STATE; }
+    HIPCHK(c, hipMemcpyAsync(dst, src, (size_t)bytes, kind, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    return ADACGD_OK;
+  };
+  auto host_out = [&](const void* src, int64_t bytes) -> int {
+    if (bytes != dst_bytes) {
+      set_err(c->err, "field %d holds %lld bytes, destination has %lld", field, (long long)bytes, (long long)dst_bytes);
+      return ADACGD_ERR_FIELD;
+    }
+    if (dst_on_device) {
+      HIPCHK(c, hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyHostToDevice, c->st));
+      HIPCHK(c, hipStreamSynchronize(c->st));
+    } else {
+      std::memcpy(dst, src, (size_t)bytes);
+    }
+    return ADACGD_OK;
+  };
+  auto packed = [&](const NodeSet& ns, const void* base, size_t elt, bool count_only) -> int {
+    std::vector<uint32_t> cnt((size_t)ns.nn);
+    HIPCHK(c, hipMemcpyAsync(cnt.data(), ns.msg_count, cnt.size() * 4, hipMemcpyDeviceToHost, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    if (count_only) {
+      std::vector<int64_t> c64(cnt.begin(), cnt.end());
+      return host_out(c64.data(), (int64_t)c64.size() * 8);
+    }
+    int64_t total = 0;
+    for (uint32_t v : cnt) total += v;
+    if (total * (int64_t)elt != dst_bytes) {
+      set_err(c->err, "field %d holds %lld bytes, destination has %lld", field, (long long)(total * elt),
+              (long long)dst_bytes);
+      return ADACGD_ERR_FIELD;
+    }
+    size_t off = 0;
+    for (int i = 0; i < ns.nn; ++i) {
+      if (!cnt[i]) continue;
+      HIPCHK(c, hipMemcpyAsync((char*)dst + off, (const char*)base + (size_t)i * ns.Kcap * elt, cnt[i] * elt, kind,
+                               c->st));
+      off += cnt[i] * elt;
+    }
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    return ADACGD_OK;
+  };
+  const NodeSet& W = c->W;
+  const NodeSet& M = c->M;
+  const bool hm = c->has_master;
+  switch (field) {
+    case ADACGD_F_X: return copy(c->x, d * 4);
+    case ADACGD_F_G: return copy(c->g(), d * 4);
+    case ADACGD_F_GTILDE: return copy(c->gt[c->cur], d * 4);
+    case ADACGD_F_GTILDE_PREV: return copy(c->gt[c->cur ^ 1], d * 4);
+    case ADACGD_F_GI: return copy(c->gi, n * d * 4);
+    case ADACGD_F_PREV_GRAD:
+    case ADACGD_F_GRAD:
+      return copy(c->grad_mode == ADACGD_DIFF_EXTERNAL ? nullptr : c->ycurp(), n * d * 4);
+    case ADACGD_F_LEVEL: return copy(W.level, n * 4);
+    case ADACGD_F_SQNORM: return copy(W.S, n * 8);
+    case ADACGD_F_D: return copy(W.D, n * 8);
+    case ADACGD_F_ERR: return copy(W.err, n * W.lv.m * 8);
+    case ADACGD_F_MSG_COUNT: return packed(W, nullptr, 0, true);
+    case ADACGD_F_MSG_IDX: return packed(W, W.msg_idx, 4, false);
+    case ADACGD_F_MSG_VAL: return packed(W, W.msg_val, 4, false);
+    case ADACGD_F_M_LEVEL: return hm ? copy(M.level, 4) : copy(nullptr, 4);
+    case ADACGD_F_M_SQNORM: return hm ? copy(M.S, 8) : copy(nullptr, 8);
+    case ADACGD_F_M_D: return hm ? copy(M.D, 8) : copy(nullptr, 8);
+    case ADACGD_F_M_ERR: return hm ? copy(M.err, (int64_t)M.lv.m * 8) : copy(nullptr, 0);
+    case ADACGD_F_M_MSG_COUNT:
+      if (!hm) { set_err(c->err, "no master compressor"); return ADACGD_ERR_STATE; }
+      return packed(M, nullptr, 0, true);
+    case ADACGD_F_M_MSG_IDX:
+      if (!hm) { set_err(c->err, "no master compressor"); return ADACGD_ERR_STATE; }
+      return packed(M, M.msg_idx, 4, false);
+    case ADACGD_F_M_MSG_VAL:
+      if (!hm) { set_err(c->err, "no master compressor"); return ADACGD_ERR_STATE; }
+      return packed(M, M.msg_val, 4, false);
+    case ADACGD_F_STEP: return host_out(&c->step, 8);
+    case ADACGD_F_LEVEL_HIST: return copy(W.level_hist, (int64_t)(W.lv.m + 1) * 8);
+    case ADACGD_F_M_LEVEL_HIST: return hm ? copy(M.level_hist, (int64_t)(M.lv.m + 1) * 8) : copy(nullptr, 8);
+    case ADACGD_F_COMM: {
+      uint64_t o[4] = {0, 0, 0, 0};
+      std::vector<unsigned long long> hw(W.lv.m + 1), hmv(M.lv.m + 1);
+      HIPCHK(c, hipMemcpyAsync(hw.data(), W.level_hist, hw.size() * 8, hipMemcpyDeviceToHost, c->st));
+      if (hm) HIPCHK(c, hipMemcpyAsync(hmv.data(), M.level_hist, hmv.size() * 8, hipMemcpyDeviceToHost, c->st));
+      HIPCHK(c, hipStreamSynchronize(c->st));
+      comm_of(W, hw.data(), 1, &o[0], &o[1]);
+      if (hm) {
+        comm_of(M, hmv.data(), (uint64_t)n, &o[2], &o[3]);
+      } else {                      // identity master: the dense g~ goes to every worker each step
+        o[2] = (uint64_t)c->step * (uint64_t)d * (uint64_t)n;
+        o[3] = o[2] * 32;
+      }
+      return host_out(o, 32);
+    }
+    case ADACGD_F_QCODES: return copy(W.qcodes, n * d * 2);
+    case ADACGD_F_QSCALE: return copy(W.qscale, n * 4);
+    case ADACGD_F_KERNEL_MS: {
+      int rc = drain_spans(c);
+      if (rc) return rc;
+      double o[2 * ADACGD_NUM_KERNELS];
+      for (int k = 0; k < ADACGD_NUM_KERNELS; ++k) { o[k] = c->ms_sum[k]; o[ADACGD_NUM_KERNELS + k] = c->ms_cnt[k]; }
+      rc = host_out(o, sizeof(o));
+      if (rc == ADACGD_OK) {
+        std::memset(c->ms_sum, 0, sizeof(c->ms_sum));
+        std::memset(c->ms_cnt, 0, sizeof(c->ms_cnt));
+      }
+      return rc;
+    }
+    default:
+      set_err(c->err, "unknown field %d", field);
+      return ADACGD_ERR_FIELD;
+  }
+}
+
+int adacgd_destroy(adacgd_ctx* c) {
+  if (!c) return ADACGD_OK;
+  hipError_t e = hipStreamSynchronize(c->st);
+  for (auto& s : c->spans) { hipEventDestroy(s.a); hipEventDestroy(s.b); }
+  for (auto ev : c->pool) hipEventDestroy(ev);
+  delete c;
+  return e == hipSuccess ? ADACGD_OK : ADACGD_ERR_DEVICE;
+}
+
+const char* adacgd_last_error(const adacgd_ctx* c) { return c ? c->err : g_err; }
+
+}  // extern "C"

@@ -1,0 +1,809 @@
+// Worker / master compression step of AdaCGD (Section 4.3) for a set of nodes:
+// multi-level exact Top-K selection by radix select on the magnitude key, the
+// realised error of every level (left side of the trigger, Eq. (10)), the level
+// cascade of the AdaCGD definition, and the EF21 update h <- h + C_j(x - h) (Eq. (7))
+// with the sparse message.
+//
+// Kernel sequence per node set (every kernel ends with a "last block of the node"
+// epilogue that finishes the node's small serial work, so no extra launches):
+//   scan    : v = x - h, S = ||v||^2, D = ||x - y||^2, first-digit histogram
+//             epilogue: bin and in-bin rank of each Top-K size, candidate cut-off bin
+//   filter  : re-forms v, sums the energy below the cut-off, writes candidates
+//             (coordinate, value) grouped by tile in coordinate order, second-digit
+//             histograms, realised quantiser errors
+//             epilogue: second digit of each threshold
+//   refine  : third-digit histograms over the candidates; epilogue: exact thresholds
+//             T_s, ties to take r_s, tie counts
+//   tally   : per tile counts of keys > T_s and == T_s, energy strictly below T_s
+//             epilogue: err of every level, the cascade, message offsets per tile
+//   compact : writes the chosen level's message in ascending coordinate and updates h
+#include "devutil.h"
+#include "engine.h"
+
+namespace adacgd {
+
+// ---------------------------------------------------------------------------
+// element mapping of a tile: wavefront w owns coordinates [w*2048, (w+1)*2048) of the
+// tile.  Vector path (d % 4 == 0): iteration k, lane l holds 4 consecutive coordinates
+// starting at w*2048 + k*256 + 4l.  Scalar path: component c of iteration k is
+// coordinate w*2048 + k*256 + 64c + l.
+// ---------------------------------------------------------------------------
+template <bool VEC>
+__device__ __forceinline__ int64_t comp0(int64_t base, int w, int lane, int k) {
+  return VEC ? base + w * kWaveTile + k * 256 + lane * 4 : base + w * kWaveTile + k * 256 + lane;
+}
+template <bool VEC>
+__device__ __forceinline__ int64_t comp_index(int64_t l0, int c) {
+  return VEC ? l0 + c : l0 + 64 * c;
+}
+template <bool VEC>
+__device__ __forceinline__ void load4(const float* __restrict__ p, int64_t l0, int64_t d, float (&o)[4]) {
+  if (VEC) {
+    if (l0 < d) {
+      const float4 q = *reinterpret_cast<const float4*>(p + l0);
+      o[0] = q.x; o[1] = q.y; o[2] = q.z; o[3] = q.w;
+    } else {
+      o[0] = o[1] = o[2] = o[3] = 0.f;
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) o[c] = (l0 + 64 * c < d) ? p[l0 + 64 * c] : 0.f;
+  }
+}
+template <bool VEC>
+__device__ __forceinline__ void store4(float* __restrict__ p, int64_t l0, int64_t d, const float (&o)[4]) {
+  if (VEC) {
+    if (l0 < d) *reinterpret_cast<float4*>(p + l0) = make_float4(o[0], o[1], o[2], o[3]);
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (l0 + 64 * c < d) p[l0 + 64 * c] = o[c];
+  }
+}
+
+// Walks a histogram of this launch from its top bin down and finds, for each of nr
+// ranks, the bin where the running count reaches the rank.  Zeroes the histogram.
+template <int NB>
+__device__ void locate(uint32_t* hist, int nr, const uint32_t* rank, uint32_t* out_bin, uint32_t* out_rank,
+                       uint32_t* out_cnt, uint32_t* lds4) {
+  constexpr int PER = NB / kBlock;
+  uint32_t loc[PER];
+  uint32_t sum = 0;
+  const int top = NB - 1 - (int)threadIdx.x * PER;
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    loc[q] = ld_coherent(&hist[top - q]);
+    hist[top - q] = 0;
+    sum += loc[q];
+  }
+  uint32_t total;
+  uint32_t cum = block_excl_scan(sum, lds4, &total);
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    const uint32_t c = loc[q];
+    if (c) {
+      for (int r = 0; r < nr; ++r) {
+        const uint32_t rk = rank[r];
+        if (cum < rk && rk <= cum + c) {
+          out_bin[r] = (uint32_t)(top - q);
+          out_rank[r] = rk - cum;
+          out_cnt[r] = c;
+        }
+      }
+    }
+    cum += c;
+  }
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// scan
+// ---------------------------------------------------------------------------
+template <bool DIFF, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
+  __shared__ uint32_t hist[kBins0];
+  __shared__ double red[4];
+  __shared__ uint32_t lds4[4];
+  __shared__ int s_flag;
+  __shared__ uint32_t s_rank[kMaxLevels], s_bin[kMaxLevels], s_rk[kMaxLevels], s_cnt[kMaxLevels];
+
+  const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int64_t d = ns.d;
+  const size_t row = (size_t)node * (size_t)d;
+  const float* __restrict__ x = a.x + row;
+  const float* __restrict__ h = a.h + row;
+  const float* __restrict__ y = DIFF ? nullptr : a.y + row;
+  float* __restrict__ yc = a.ycopy ? a.ycopy + row : nullptr;
+
+  for (int b = tid; b < kBins0; b += kBlock) hist[b] = 0;
+  __syncthreads();
+
+  double S = 0.0, D = 0.0;
+  uint32_t kmax = 0;
+  for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
+    const int64_t base = (int64_t)t * kTile;
+#pragma unroll
+    for (int k = 0; k < kIter; ++k) {
+      const int64_t l0 = comp0<VEC>(base, w, lane, k);
+      float xv[4], hv[4], yv[4];
+      load4<VEC>(x, l0, d, xv);
+      if (!DIFF) {
+        load4<VEC>(h, l0, d, hv);
+        load4<VEC>(y, l0, d, yv);
+        if (yc) store4<VEC>(yc, l0, d, xv);
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if (comp_index<VEC>(l0, c) < d) {
+          const float v = DIFF ? xv[c] : xv[c] - hv[c];
+          const double dv = (double)v;
+          S = fma(dv, dv, S);
+          if (!DIFF) {
+            const double dw = (double)(xv[c] - yv[c]);
+            D = fma(dw, dw, D);
+          }
+          const uint32_t key = magkey(v);
+          kmax = key > kmax ? key : kmax;
+          atomicAdd(&hist[key >> kShift0], 1u);
+        }
+      }
+    }
+  }
+  S = block_sum(S, red);
+  D = block_sum(D, red);
+  if (tid == 0) {
+    ns.partS[(size_t)node * ns.G + blockIdx.x] = S;
+    ns.partD[(size_t)node * ns.G + blockIdx.x] = D;
+  }
+  if (ns.lv.nq > 0) {
+    kmax = wave_max(kmax);
+    if (lane == 0) atomicMax(&ns.kmax[node], kmax);
+  }
+  __syncthreads();
+  uint32_t* gh = ns.hist0 + (size_t)node * kBins0;
+  for (int b = tid; b < kBins0; b += kBlock) {
+    const uint32_t c = hist[b];
+    if (c) atomicAdd(&gh[b], c);
+  }
+
+  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+
+  // ---- epilogue: one block per node ----
+  const int p = ns.lv.p;
+  double s = 0.0, dd = 0.0;
+  for (int b = tid; b < (int)gridDim.x; b += kBlock) {
+    s += ld_coherent(&ns.partS[(size_t)node * ns.G + b]);
+    dd += ld_coherent(&ns.partD[(size_t)node * ns.G + b]);
+  }
+  s = block_sum(s, red);
+  dd = block_sum(dd, red);
+  if (tid < kMaxLevels) {
+    s_rank[tid] = tid < p ? ns.lv.K[tid] : 0;
+    s_bin[tid] = 0; s_rk[tid] = 1; s_cnt[tid] = 0;
+  }
+  __syncthreads();
+  locate<kBins0>(gh, p, s_rank, s_bin, s_rk, s_cnt, lds4);
+  if (tid < p) {
+    ns.prefix[node * p + tid] = s_bin[tid];
+    ns.rank[node * p + tid] = s_rk[tid];
+  }
+  if (tid == 0) {
+    ns.S[node] = s;
+    ns.D[node] = DIFF ? a.extD[node] : dd;
+    ns.bmin[node] = p > 0 ? s_bin[p - 1] : (uint32_t)kBins0;   // largest K reaches lowest
+    ns.cursor[node] = 0;
+    if (ns.lv.nq > 0) {
+      ns.amax[node] = ld_coherent(&ns.kmax[node]);
+      ns.kmax[node] = 0;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1) -> 4 words
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c0 = n0; c1 = (uint32_t)p1; c2 = n2; c3 = (uint32_t)p0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// dither u in [0,1) of coordinate l: word l%4 of the block l/4, top 24 bits
+__device__ __forceinline__ float dither_of(uint32_t word) { return (float)(word >> 8) * 5.9604644775390625e-8f; }
+
+// b-bit stochastic quantiser of one coordinate: returns the signed code xi and the decoded value.
+// a = max |v| (> 0), s = magnitude levels, c = fl(a / (s (1+omega))).
+__device__ __forceinline__ float quant_one(float v, float a, float s, float c, float u, int* code) {
+  const float av = fabsf(v);
+  const float r = (av / a) * s;       // two rounded fp32 operations
+  const float fl = floorf(r);
+  const float pfrac = r - fl;
+  const float xi = fl + ((u < pfrac) ? 1.f : 0.f);
+  const float mag = xi * c;
+  *code = (__float_as_uint(v) >> 31) ? -(int)xi : (int)xi;
+  return copysignf(mag, v);
+}
+
+// ---------------------------------------------------------------------------
+// filter
+// ---------------------------------------------------------------------------
+template <bool DIFF, bool VEC, bool QUANT>
+__global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
+  extern __shared__ uint32_t ref1[];   // [p][kBins1]
+  __shared__ double red[4];
+  __shared__ uint32_t lds4[4];
+  __shared__ uint32_t s_wtot[4];
+  __shared__ uint32_t s_start;
+  __shared__ int s_flag;
+  __shared__ uint32_t s_rank[1], s_bin[1], s_rk[1], s_cnt[1];
+
+  const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int64_t d = ns.d;
+  const int p = ns.lv.p, nq = ns.lv.nq;
+  const size_t row = (size_t)node * (size_t)d;
+  const float* __restrict__ x = a.x + row;
+  const float* __restrict__ h = a.h + row;
+  uint2* __restrict__ cand = ns.cand + row;
+
+  for (int b = tid; b < p * kBins1; b += kBlock) ref1[b] = 0;
+  const uint32_t bmin = ns.bmin[node];
+  uint32_t pre[kMaxLevels];
+#pragma unroll
+  for (int s = 0; s < kMaxLevels; ++s) pre[s] = s < p ? ns.prefix[node * p + s] : 0xFFFFFFFFu;
+  __syncthreads();
+
+  // quantiser constants of this node
+  float qa = 0.f;
+  float qc[kMaxLevels];
+  double qacc[kMaxLevels];
+  if (QUANT) {
+    qa = __uint_as_float(ns.amax[node]);
+#pragma unroll
+    for (int q = 0; q < kMaxLevels; ++q) {
+      qc[q] = (q < nq && qa > 0.f) ? (float)((double)qa / ns.lv.qdenom[q]) : 0.f;
+      qacc[q] = 0.0;
+    }
+  }
+  const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
+  const uint32_t ctr1 = (uint32_t)node | a.node_flag;
+
+  double Eb = 0.0;
+  for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
+    const int64_t base = (int64_t)t * kTile;
+    float v[kIter * 4];
+    uint32_t mask = 0;
+#pragma unroll
+    for (int k = 0; k < kIter; ++k) {
+      const int64_t l0 = comp0<VEC>(base, w, lane, k);
+      float xv[4], hv[4];
+      load4<VEC>(x, l0, d, xv);
+      if (!DIFF) load4<VEC>(h, l0, d, hv);
+      uint32_t rnd[4];
+      if (QUANT && VEC) philox4x32_10((uint32_t)(l0 >> 2), ctr1, a.step, 0u, k0, k1, rnd);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float vv = DIFF ? xv[c] : xv[c] - hv[c];
+        v[k * 4 + c] = vv;
+        const int64_t l = comp_index<VEC>(l0, c);
+        if (l < d) {
+          const uint32_t key = magkey(vv);
+          const uint32_t bin = key >> kShift0;
+          const double dv = (double)vv;
+          if (bin >= bmin) {
+            mask |= 1u << (k * 4 + c);
+#pragma unroll
+            for (int s = 0; s < kMaxLevels; ++s)
+              if (s < p && bin == pre[s]) atomicAdd(&ref1[s * kBins1 + ((key >> kShift1) & (kBins1 - 1))], 1u);
+          } else {
+            Eb = fma(dv, dv, Eb);
+          }
+          if (QUANT) {
+            uint32_t word;
+            if (VEC) {
+              word = rnd[c];
+            } else {
+              uint32_t r4[4];
+              philox4x32_10((uint32_t)(l >> 2), ctr1, a.step, 0u, k0, k1, r4);
+              word = r4[l & 3];
+            }
+            const float u = dither_of(word);
+#pragma unroll
+            for (int q = 0; q < kMaxLevels; ++q) {
+              if (q < nq) {
+                int code;
+                const float cq = qa > 0.f ? quant_one(vv, qa, ns.lv.qs[q], qc[q], u, &code) : 0.f;
+                const double e = dv - (double)cq;
+                qacc[q] = fma(e, e, qacc[q]);
+              }
+            }
+          }
+        }
+      }
+    }
+    // ---- ordered compaction of the tile's candidates ----
+    uint32_t wtot = 0;
+    if (VEC) {
+#pragma unroll
+      for (int k = 0; k < kIter; ++k) {
+        const uint32_t f = (mask >> (4 * k)) & 15u;
+        wtot += popc64(ballot(f & 1u)) + popc64(ballot(f & 2u)) + popc64(ballot(f & 4u)) + popc64(ballot(f & 8u));
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < kIter * 4; ++j) wtot += popc64(ballot((mask >> j) & 1u));
+    }
+    __syncthreads();                      // previous tile's readers of s_wtot / s_start are done
+    if (lane == 0) s_wtot[w] = wtot;
+    __syncthreads();
+    if (tid == 0) {
+      const uint32_t total = s_wtot[0] + s_wtot[1] + s_wtot[2] + s_wtot[3];
+      const uint32_t start = total ? atomicAdd(&ns.cursor[node], total) : 0u;
+      ns.grp_start[(size_t)node * ns.tiles + t] = start;
+      ns.grp_count[(size_t)node * ns.tiles + t] = total;
+      s_start = start;
+    }
+    __syncthreads();
+    if (wtot) {
+      uint32_t running = s_start;
+      for (int i = 0; i < w; ++i) running += s_wtot[i];
+      if (VEC) {
+#pragma unroll
+        for (int k = 0; k < kIter; ++k) {
+          const uint32_t f = (mask >> (4 * k)) & 15u;
+          const uint64_t b0 = ballot(f & 1u), b1 = ballot(f & 2u), b2 = ballot(f & 4u), b3 = ballot(f & 8u);
+          uint32_t pos = running + below(b0) + below(b1) + below(b2) + below(b3);
+          const int64_t l0 = comp0<VEC>(base, w, lane, k);
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if ((f >> c) & 1u) cand[pos++] = make_uint2((uint32_t)(l0 + c), fbits(v[k * 4 + c]));
+          running += popc64(b0) + popc64(b1) + popc64(b2) + popc64(b3);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < kIter * 4; ++j) {
+          const bool f = (mask >> j) & 1u;
+          const uint64_t b = ballot(f);
+          if (f) {
+            const int64_t l = comp_index<VEC>(comp0<VEC>(base, w, lane, j >> 2), j & 3);
+            cand[running + below(b)] = make_uint2((uint32_t)l, fbits(v[j]));
+          }
+          running += popc64(b);
+        }
+      }
+    }
+  }
+
+  Eb = block_sum(Eb, red);
+  if (tid == 0) ns.partEb[(size_t)node * ns.G + blockIdx.x] = Eb;
+  if (QUANT) {
+#pragma unroll
+    for (int q = 0; q < kMaxLevels; ++q) {
+      if (q < nq) {
+        const double e = block_sum(qacc[q], red);
+        if (tid == 0) ns.partQ[((size_t)node * ns.G + blockIdx.x) * nq + q] = e;
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* gref = ns.ref1 + (size_t)node * p * kBins1;
+  for (int b = tid; b < p * kBins1; b += kBlock) {
+    const uint32_t c = ref1[b];
+    if (c) atomicAdd(&gref[b], c);
+  }
+
+  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+
+  // ---- epilogue ----
+  double e = 0.0;
+  for (int b = tid; b < (int)gridDim.x; b += kBlock) e += ld_coherent(&ns.partEb[(size_t)node * ns.G + b]);
+  e = block_sum(e, red);
+  if (tid == 0) ns.Eb[node] = e;
+  if (QUANT) {
+    for (int q = 0; q < nq; ++q) {
+      double s = 0.0;
+      for (int b = tid; b < (int)gridDim.x; b += kBlock)
+        s += ld_coherent(&ns.partQ[((size_t)node * ns.G + b) * nq + q]);
+      s = block_sum(s, red);
+      if (tid == 0) ns.qerr[node * nq + q] = s;
+    }
+    if (tid == 0) ns.qscale[node] = 0.f;
+  }
+  for (int s = 0; s < p; ++s) {
+    if (tid == 0) {
+      s_rank[0] = ns.rank[node * p + s];
+      s_bin[0] = 0; s_rk[0] = 1; s_cnt[0] = 0;
+    }
+    __syncthreads();
+    locate<kBins1>(gref + (size_t)s * kBins1, 1, s_rank, s_bin, s_rk, s_cnt, lds4);
+    if (tid == 0) {
+      ns.prefix[node * p + s] = (ns.prefix[node * p + s] << 10) | s_bin[0];
+      ns.rank[node * p + s] = s_rk[0];
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// refine: third digit over the candidate lists (one wavefront per tile group)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_refine(NodeSet ns) {
+  extern __shared__ uint32_t ref2[];   // [p][kBins2]
+  __shared__ uint32_t lds4[4];
+  __shared__ int s_flag;
+  __shared__ uint32_t s_rank[1], s_bin[1], s_rk[1], s_cnt[1];
+  const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int p = ns.lv.p;
+  const size_t row = (size_t)node * (size_t)ns.d;
+  const uint2* __restrict__ cand = ns.cand + row;
+  for (int b = tid; b < p * kBins2; b += kBlock) ref2[b] = 0;
+  uint32_t pre[kMaxLevels];
+#pragma unroll
+  for (int s = 0; s < kMaxLevels; ++s) pre[s] = s < p ? ns.prefix[node * p + s] : 0xFFFFFFFFu;
+  __syncthreads();
+  for (int g = blockIdx.x * 4 + w; g < ns.tiles; g += gridDim.x * 4) {
+    const uint32_t start = ns.grp_start[(size_t)node * ns.tiles + g];
+    const uint32_t cnt = ns.grp_count[(size_t)node * ns.tiles + g];
+    for (uint32_t e = lane; e < cnt; e += 64) {
+      const uint32_t key = cand[start + e].y & 0x7FFFFFFFu;
+      const uint32_t hi = key >> kShift1;
+#pragma unroll
+      for (int s = 0; s < kMaxLevels; ++s)
+        if (s < p && hi == pre[s]) atomicAdd(&ref2[s * kBins2 + (key & (kBins2 - 1))], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t* gref = ns.ref2 + (size_t)node * p * kBins2;
+  for (int b = tid; b < p * kBins2; b += kBlock) {
+    const uint32_t c = ref2[b];
+    if (c) atomicAdd(&gref[b], c);
+  }
+  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+  for (int s = 0; s < p; ++s) {
+    if (tid == 0) {
+      s_rank[0] = ns.rank[node * p + s];
+      s_bin[0] = 0; s_rk[0] = 1; s_cnt[0] = 0;
+    }
+    __syncthreads();
+    locate<kBins2>(gref + (size_t)s * kBins2, 1, s_rank, s_bin, s_rk, s_cnt, lds4);
+    if (tid == 0) {
+      ns.prefix[node * p + s] = (ns.prefix[node * p + s] << 9) | s_bin[0];   // exact threshold key T_s
+      ns.rank[node * p + s] = s_rk[0];                                       // ties to take
+      ns.eqcnt[node * p + s] = s_cnt[0];                                     // keys equal to T_s
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// tally: counts and band energies against the exact thresholds; epilogue = level choice
+// ---------------------------------------------------------------------------
+template <int P>
+__global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
+  __shared__ double red[4];
+  __shared__ uint32_t lds4[4];
+  __shared__ int s_flag;
+  __shared__ double s_strict[kMaxLevels];
+  __shared__ int s_slot;
+  __shared__ uint32_t s_r;
+  const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int p = ns.lv.p;
+  const int tiles = ns.tiles;
+  const size_t row = (size_t)node * (size_t)ns.d;
+  const uint2* __restrict__ cand = ns.cand + row;
+  uint32_t T[P];
+  double strict[P];
+#pragma unroll
+  for (int s = 0; s < P; ++s) {
+    T[s] = s < p ? ns.prefix[node * p + s] : 0u;
+    strict[s] = 0.0;
+  }
+  for (int g = blockIdx.x * 4 + w; g < tiles; g += gridDim.x * 4) {
+    const uint32_t start = ns.grp_start[(size_t)node * tiles + g];
+    const uint32_t cnt = ns.grp_count[(size_t)node * tiles + g];
+    uint32_t cg[P], ce[P];
+#pragma unroll
+    for (int s = 0; s < P; ++s) cg[s] = ce[s] = 0;
+    for (uint32_t e0 = 0; e0 < cnt; e0 += 64) {
+      const uint32_t e = e0 + lane;
+      const bool valid = e < cnt;
+      const uint2 c = valid ? cand[start + e] : make_uint2(0u, 0u);
+      const uint32_t key = c.y & 0x7FFFFFFFu;
+      const double dv = (double)__uint_as_float(c.y);
+      const double ev = dv * dv;
+#pragma unroll
+      for (int s = 0; s < P; ++s) {
+        if (s < p) {
+          cg[s] += popc64(ballot(valid && key > T[s]));
+          ce[s] += popc64(ballot(valid && key == T[s]));
+          if (valid && key < T[s]) strict[s] += ev;
+        }
+      }
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int s = 0; s < P; ++s) {
+        if (s < p) {
+          ns.cnt_gt[((size_t)node * p + s) * tiles + g] = cg[s];
+          ns.cnt_eq[((size_t)node * p + s) * tiles + g] = ce[s];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < P; ++s) {
+    if (s < p) {
+      const double e = block_sum(strict[s], red);
+      if (tid == 0) ns.partStrict[((size_t)node * ns.G2 + blockIdx.x) * p + s] = e;
+    }
+  }
+  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+
+  // ---- epilogue: realised errors, the AdaCGD cascade, message layout ----
+  for (int s = 0; s < p; ++s) {
+    double e = 0.0;
+    for (int b = tid; b < (int)gridDim.x; b += kBlock)
+      e += ld_coherent(&ns.partStrict[((size_t)node * ns.G2 + b) * p + s]);
+    e = block_sum(e, red);
+    if (tid == 0) s_strict[s] = e;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const LevelTable& lv = ns.lv;
+    const double S = ns.S[node], D = ns.D[node], Eb = ns.Eb[node];
+    const double tau = lv.zeta * D;
+    double err[kMaxLevels];
+    for (int j = 0; j < lv.m; ++j) {
+      if (lv.kind[j] == kTopK) {
+        const int s = lv.ref[j];
+        const double tv = (double)__uint_as_float(ns.prefix[node * p + s]);
+        const double left = (double)(ns.eqcnt[node * p + s] - ns.rank[node * p + s]);   // ties not taken
+        err[j] = Eb + s_strict[s] + left * (tv * tv);
+      } else {
+        err[j] = ns.qerr[node * lv.nq + lv.ref[j]];
+      }
+      ns.err[node * lv.m + j] = err[j];
+    }
+    int jstar;
+    if (S <= tau) {
+      jstar = 0;                                   // keep h: communication skipped
+    } else {
+      jstar = lv.m;
+      for (int j = 1; j < lv.m; ++j)
+        if (err[j - 1] <= tau) { jstar = j; break; }
+    }
+    ns.level[node] = jstar;
+    atomicAdd(&ns.level_hist[jstar], 1ull);
+    int slot = -1, q = -1;
+    if (jstar > 0) {
+      if (lv.kind[jstar - 1] == kTopK) slot = lv.ref[jstar - 1];
+      else q = lv.ref[jstar - 1];
+    }
+    ns.sel_slot[node] = slot;
+    ns.sel_q[node] = q;
+    ns.msg_count[node] = slot >= 0 ? lv.K[slot] : 0u;
+    if (slot >= 0) {
+      ns.sel_T[node] = ns.prefix[node * p + slot];
+      ns.sel_r[node] = ns.rank[node * p + slot];
+      s_r = ns.rank[node * p + slot];
+    }
+    s_slot = slot;
+  }
+  __syncthreads();
+  const int slot = s_slot;
+  if (slot < 0) return;
+  const uint32_t r = s_r;
+  const uint32_t* cgt = ns.cnt_gt + ((size_t)node * p + slot) * tiles;
+  const uint32_t* ceq = ns.cnt_eq + ((size_t)node * p + slot) * tiles;
+  uint32_t* out_off = ns.out_off + (size_t)node * (tiles + 1);
+  uint32_t* eq_before = ns.eq_before + (size_t)node * tiles;
+  const int per = (tiles + kBlock - 1) / kBlock;
+  const int g0 = tid * per, g1 = min(tiles, g0 + per);
+  uint32_t eqs = 0;
+  for (int g = g0; g < g1; ++g) eqs += ld_coherent(&ceq[g]);
+  uint32_t tot;
+  uint32_t eqb = block_excl_scan(eqs, lds4, &tot);
+  uint32_t outs = 0, eqrun = eqb;
+  for (int g = g0; g < g1; ++g) {
+    const uint32_t ce = ld_coherent(&ceq[g]);
+    const uint32_t take = eqrun >= r ? 0u : min(ce, r - eqrun);
+    outs += ld_coherent(&cgt[g]) + take;
+    eqrun += ce;
+  }
+  uint32_t outb = block_excl_scan(outs, lds4, &tot);
+  eqrun = eqb;
+  for (int g = g0; g < g1; ++g) {
+    const uint32_t ce = ld_coherent(&ceq[g]);
+    const uint32_t take = eqrun >= r ? 0u : min(ce, r - eqrun);
+    out_off[g] = outb;
+    eq_before[g] = eqrun;
+    outb += ld_coherent(&cgt[g]) + take;
+    eqrun += ce;
+  }
+  if (tid == 0) out_off[tiles] = tot;
+}
+
+// ---------------------------------------------------------------------------
+// compact: message of the chosen Top-K level, h <- h + C_j(v)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_compact(NodeSet ns, PassArgs a) {
+  const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  if (ns.sel_slot[node] < 0) return;
+  const uint32_t T = ns.sel_T[node], r = ns.sel_r[node];
+  const int tiles = ns.tiles;
+  const size_t row = (size_t)node * (size_t)ns.d;
+  const uint2* __restrict__ cand = ns.cand + row;
+  float* __restrict__ h = a.h + row;
+  int32_t* __restrict__ midx = ns.msg_idx + (size_t)node * ns.Kcap;
+  float* __restrict__ mval = ns.msg_val + (size_t)node * ns.Kcap;
+  for (int g = blockIdx.x * 4 + w; g < tiles; g += gridDim.x * 4) {
+    const uint32_t start = ns.grp_start[(size_t)node * tiles + g];
+    const uint32_t cnt = ns.grp_count[(size_t)node * tiles + g];
+    uint32_t out = ns.out_off[(size_t)node * (tiles + 1) + g];
+    uint32_t eqb = ns.eq_before[(size_t)node * tiles + g];
+    for (uint32_t e0 = 0; e0 < cnt; e0 += 64) {
+      const uint32_t e = e0 + lane;
+      const bool valid = e < cnt;
+      const uint2 c = valid ? cand[start + e] : make_uint2(0u, 0u);
+      const uint32_t key = c.y & 0x7FFFFFFFu;
+      const bool eq = valid && key == T;
+      const uint64_t beq = ballot(eq);
+      const bool take = valid && (key > T || (eq && eqb + below(beq) < r));
+      const uint64_t bt = ballot(take);
+      if (take) {
+        const uint32_t pos = out + below(bt);
+        const float val = __uint_as_float(c.y);
+        midx[pos] = (int32_t)c.x;
+        mval[pos] = val;
+        h[c.x] = h[c.x] + val;
+      }
+      eqb += popc64(beq);
+      out += popc64(bt);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// qapply: dense update h <- h + C_b(v) and codes, for nodes whose chosen level is a quantiser
+// ---------------------------------------------------------------------------
+template <bool DIFF, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_qapply(NodeSet ns, PassArgs a) {
+  const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int q = ns.sel_q[node];
+  if (q < 0) return;
+  const int64_t d = ns.d;
+  const size_t row = (size_t)node * (size_t)d;
+  const float* __restrict__ x = a.x + row;
+  float* __restrict__ h = a.h + row;
+  int16_t* __restrict__ codes = ns.qcodes + row;
+  const float qa = __uint_as_float(ns.amax[node]);
+  const float qs = ns.lv.qs[q];
+  const float qc = qa > 0.f ? (float)((double)qa / ns.lv.qdenom[q]) : 0.f;
+  if (blockIdx.x == 0 && tid == 0) ns.qscale[node] = qc;
+  const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
+  const uint32_t ctr1 = (uint32_t)node | a.node_flag;
+  for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
+    const int64_t base = (int64_t)t * kTile;
+#pragma unroll
+    for (int k = 0; k < kIter; ++k) {
+      const int64_t l0 = comp0<VEC>(base, w, lane, k);
+      float xv[4], hv[4];
+      load4<VEC>(x, l0, d, xv);
+      load4<VEC>(h, l0, d, hv);
+      uint32_t rnd[4];
+      if (VEC) philox4x32_10((uint32_t)(l0 >> 2), ctr1, a.step, 0u, k0, k1, rnd);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int64_t l = comp_index<VEC>(l0, c);
+        if (l < d) {
+          const float vv = DIFF ? xv[c] : xv[c] - hv[c];
+          uint32_t word;
+          if (VEC) {
+            word = rnd[c];
+          } else {
+            uint32_t r4[4];
+            philox4x32_10((uint32_t)(l >> 2), ctr1, a.step, 0u, k0, k1, r4);
+            word = r4[l & 3];
+          }
+          int code = 0;
+          const float cq = qa > 0.f ? quant_one(vv, qa, qs, qc, dither_of(word), &code) : 0.f;
+          h[l] = hv[c] + cq;
+          codes[l] = (int16_t)code;
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+static inline bool vec_ok(const NodeSet& ns, const PassArgs& a) {
+  auto al = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+  return (ns.d % 4 == 0) && al(a.x) && al(a.h) && (a.diff || al(a.y)) && (!a.ycopy || al(a.ycopy));
+}
+
+hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  const dim3 grid(ns.G, ns.nn), block(kBlock);
+  const bool v = vec_ok(ns, a);
+  if (a.diff) {
+    if (v) hipLaunchKernelGGL((k_scan<true, true>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_scan<true, false>), grid, block, 0, st, ns, a);
+  } else {
+    if (v) hipLaunchKernelGGL((k_scan<false, true>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_scan<false, false>), grid, block, 0, st, ns, a);
+  }
+  return hipGetLastError();
+}
+
+template <bool DIFF, bool VEC>
+static void launch_filter_q(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+  const dim3 grid(ns.G, ns.nn), block(kBlock);
+  const size_t lds = (size_t)ns.lv.p * kBins1 * sizeof(uint32_t);
+  if (ns.lv.nq > 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, true>), grid, block, lds, st, ns, a);
+  else hipLaunchKernelGGL((k_filter<DIFF, VEC, false>), grid, block, lds, st, ns, a);
+}
+
+hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  const bool v = vec_ok(ns, a);
+  if (a.diff) {
+    if (v) launch_filter_q<true, true>(ns, a, st);
+    else launch_filter_q<true, false>(ns, a, st);
+  } else {
+    if (v) launch_filter_q<false, true>(ns, a, st);
+    else launch_filter_q<false, false>(ns, a, st);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_refine(const NodeSet& ns, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  if (ns.lv.p == 0) return hipSuccess;
+  const dim3 grid(ns.G2, ns.nn), block(kBlock);
+  hipLaunchKernelGGL(k_refine, grid, block, (size_t)ns.lv.p * kBins2 * sizeof(uint32_t), st, ns);
+  return hipGetLastError();
+}
+
+hipError_t launch_tally(const NodeSet& ns, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  const dim3 grid(ns.G2, ns.nn), block(kBlock);
+  if (ns.lv.p <= 4) hipLaunchKernelGGL((k_tally<4>), grid, block, 0, st, ns);
+  else if (ns.lv.p <= 8) hipLaunchKernelGGL((k_tally<8>), grid, block, 0, st, ns);
+  else hipLaunchKernelGGL((k_tally<16>), grid, block, 0, st, ns);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  if (ns.lv.p == 0) return hipSuccess;
+  const dim3 grid(ns.G2, ns.nn), block(kBlock);
+  hipLaunchKernelGGL(k_compact, grid, block, 0, st, ns, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_qapply(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  if (ns.lv.nq == 0) return hipSuccess;
+  const dim3 grid(ns.G, ns.nn), block(kBlock);
+  const bool v = vec_ok(ns, a);
+  if (a.diff) {
+    if (v) hipLaunchKernelGGL((k_qapply<true, true>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_qapply<true, false>), grid, block, 0, st, ns, a);
+  } else {
+    if (v) hipLaunchKernelGGL((k_qapply<false, true>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_qapply<false, false>), grid, block, 0, st, ns, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace adacgd

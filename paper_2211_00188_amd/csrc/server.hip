@@ -1,0 +1,239 @@
+// Server side and objective of the AdaCGD iteration:
+//   iterate update x <- x - gamma g                       (Algorithm 1)
+//   aggregation    g~ <- g~ + (1/n) sum_i message_i       (Algorithm 1, incremental form)
+//   local gradients of the logistic objective with the nonconvex regulariser (Section 6)
+#include "devutil.h"
+#include "engine.h"
+
+namespace adacgd {
+
+// ---------------------------------------------------------------------------
+// small dense kernels
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_xupdate(float* __restrict__ x, const float* __restrict__ g, double gamma,
+                                                     int64_t d) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < d) x[i] = (float)((double)x[i] - gamma * (double)g[i]);   // one rounding
+}
+
+// g~^0 = (1/n) sum_i g~_i^0, summed in ascending i in fp64; written to up to three vectors
+__global__ __launch_bounds__(kBlock) void k_mean(const float* __restrict__ gi, float* o0, float* o1, float* o2, int n,
+                                                  int64_t d) {
+  const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (c >= d) return;
+  double acc = 0.0;
+  for (int i = 0; i < n; ++i) acc += (double)gi[(size_t)i * d + c];
+  const float r = (float)(acc / (double)n);
+  o0[c] = r;
+  if (o1) o1[c] = r;
+  if (o2) o2[c] = r;
+}
+
+__global__ __launch_bounds__(kBlock) void k_fill_u32(uint32_t* p, uint32_t v, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < count; i += (size_t)gridDim.x * kBlock) p[i] = v;
+}
+
+__global__ __launch_bounds__(kBlock) void k_copy_f32(float* __restrict__ dst, const float* __restrict__ src,
+                                                      size_t count) {
+  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < count; i += (size_t)gridDim.x * kBlock)
+    dst[i] = src[i];
+}
+
+// ---------------------------------------------------------------------------
+// aggregation: one block per tile of the server vector.  The tile's share of every
+// worker's sorted message is a contiguous range (known from the message offsets per
+// tile), accumulated in an fp64 tile in LDS; then g~_new = fl(g~_old + acc / n).
+// Sums of fp32 values in fp64 are exact unless their exponents spread over more than
+// ~29 bits, so the result does not depend on the order of the LDS additions.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* __restrict__ gt_old,
+                                                       float* __restrict__ gt_new) {
+  extern __shared__ double acc[];   // [kTile]
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const int64_t d = ws.d;
+  const int64_t base = (int64_t)t * kTile;
+  const int tiles = ws.tiles;
+  for (int c = tid; c < kTile; c += kBlock) acc[c] = 0.0;
+  __syncthreads();
+  bool any_dense = false;
+  for (int i = 0; i < ws.nn; ++i) {
+    if (ws.sel_q && ws.sel_q[i] >= 0) any_dense = true;
+    if (ws.sel_slot[i] < 0) continue;
+    const uint32_t lo = ws.out_off[(size_t)i * (tiles + 1) + t];
+    const uint32_t hi = ws.out_off[(size_t)i * (tiles + 1) + t + 1];
+    const int32_t* __restrict__ midx = ws.msg_idx + (size_t)i * ws.Kcap;
+    const float* __restrict__ mval = ws.msg_val + (size_t)i * ws.Kcap;
+    for (uint32_t e = lo + tid; e < hi; e += kBlock)
+      unsafeAtomicAdd(&acc[midx[e] - base], (double)mval[e]);
+  }
+  __syncthreads();
+  if (any_dense) {
+    // quantised messages are dense: each thread owns its coordinates, workers in ascending order
+    for (int i = 0; i < ws.nn; ++i) {
+      if (ws.sel_q[i] < 0) continue;
+      const float sc = ws.qscale[i];
+      const int16_t* __restrict__ codes = ws.qcodes + (size_t)i * d;
+      for (int c = tid; c < kTile; c += kBlock) {
+        if (base + c < d) {
+          const int code = codes[base + c];
+          const float mag = (float)(code < 0 ? -code : code) * sc;
+          acc[c] += (double)(code < 0 ? -mag : mag);
+        }
+      }
+    }
+  }
+  const double n = (double)ws.nn;
+  for (int c = tid; c < kTile; c += kBlock)
+    if (base + c < d) gt_new[base + c] = (float)((double)gt_old[base + c] + acc[c] / n);
+}
+
+// ---------------------------------------------------------------------------
+// logistic gradient, Section 6:
+//   grad f_i(x) = -(1/N_i) sum_l y_l a_l / (1 + exp(y_l a_l^T x)) + 2 lambda x_j / (1 + x_j^2)^2
+// margins: one wavefront per sample computes a_l^T x in fp64 and s_l = -y_l/(1+exp(y_l z_l))/N_i.
+// cols   : each thread owns 4 columns and sums s_l a_l over a chunk of the shard's rows in fp64.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_grad_margins(LogisticData ld, const float* __restrict__ x, int64_t d,
+                                                          int vec) {
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t l = (int64_t)blockIdx.x * 4 + w;
+  if (l >= ld.rows) return;
+  const float* __restrict__ a = ld.A + (size_t)l * d;
+  double acc0 = 0.0, acc1 = 0.0;
+  if (vec) {
+    for (int64_t j = (int64_t)lane * 4; j < d; j += 256) {
+      const float4 av = *reinterpret_cast<const float4*>(a + j);
+      const float4 xv = *reinterpret_cast<const float4*>(x + j);
+      acc0 = fma((double)av.x, (double)xv.x, acc0);
+      acc1 = fma((double)av.y, (double)xv.y, acc1);
+      acc0 = fma((double)av.z, (double)xv.z, acc0);
+      acc1 = fma((double)av.w, (double)xv.w, acc1);
+    }
+  } else {
+    for (int64_t j = lane; j < d; j += 64) acc0 = fma((double)a[j], (double)x[j], acc0);
+  }
+  const double z = wave_sum(acc0 + acc1);
+  if (lane == 0) {
+    const int node = ld.row_node[l];
+    const double N = (double)(ld.offsets[node + 1] - ld.offsets[node]);
+    const double yl = (double)ld.labels[l];
+    ld.margins[l] = -yl / (1.0 + exp(yl * z)) / N;
+  }
+}
+
+__device__ __forceinline__ double reg_grad(double lambda, double xj) {
+  const double q = 1.0 + xj * xj;
+  return 2.0 * lambda * xj / (q * q);
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_grad_cols(LogisticData ld, const float* __restrict__ x,
+                                                       float* __restrict__ grads, int64_t d, int rows_per_chunk) {
+  const int node = blockIdx.z, rc = blockIdx.y;
+  const int64_t j0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * (VEC ? 4 : 1);
+  if (j0 >= d) return;
+  const int64_t r_begin = ld.offsets[node] + (int64_t)rc * rows_per_chunk;
+  const int64_t r_end = min(ld.offsets[node + 1], r_begin + rows_per_chunk);
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  const float* __restrict__ a = ld.A + (size_t)r_begin * d + j0;
+  for (int64_t l = r_begin; l < r_end; ++l, a += d) {
+    const double s = ld.margins[l];
+    if (VEC) {
+      const float4 av = *reinterpret_cast<const float4*>(a);
+      acc[0] = fma(s, (double)av.x, acc[0]);
+      acc[1] = fma(s, (double)av.y, acc[1]);
+      acc[2] = fma(s, (double)av.z, acc[2]);
+      acc[3] = fma(s, (double)av.w, acc[3]);
+    } else {
+      acc[0] = fma(s, (double)a[0], acc[0]);
+    }
+  }
+  if (ld.row_chunks == 1) {
+#pragma unroll
+    for (int c = 0; c < (VEC ? 4 : 1); ++c)
+      grads[(size_t)node * d + j0 + c] = (float)(acc[c] + reg_grad(ld.lambda, (double)x[j0 + c]));
+  } else {
+#pragma unroll
+    for (int c = 0; c < (VEC ? 4 : 1); ++c) ld.part[((size_t)node * ld.row_chunks + rc) * d + j0 + c] = acc[c];
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_grad_finish(LogisticData ld, const float* __restrict__ x,
+                                                         float* __restrict__ grads, int64_t d) {
+  const int node = blockIdx.y;
+  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (j >= d) return;
+  double acc = 0.0;
+  for (int rc = 0; rc < ld.row_chunks; ++rc) acc += ld.part[((size_t)node * ld.row_chunks + rc) * d + j];
+  grads[(size_t)node * d + j] = (float)(acc + reg_grad(ld.lambda, (double)x[j]));
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+static inline unsigned blocks_for(size_t count, unsigned cap = 65535u * 16u) {
+  size_t b = (count + kBlock - 1) / kBlock;
+  if (b < 1) b = 1;
+  return (unsigned)(b > cap ? cap : b);
+}
+
+hipError_t launch_xupdate(float* x, const float* g, double gamma, int64_t d, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  hipLaunchKernelGGL(k_xupdate, dim3((unsigned)((d + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, x, g, gamma, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_mean(const float* gi, float* o0, float* o1, float* o2, int n, int64_t d, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  hipLaunchKernelGGL(k_mean, dim3((unsigned)((d + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, gi, o0, o1, o2, n, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_new, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  hipLaunchKernelGGL(k_aggregate, dim3(ws.tiles), dim3(kBlock), (size_t)kTile * sizeof(double), st, ws, gt_old,
+                     gt_new);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t* p, uint32_t v, size_t count, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  if (count == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(count, 4096)), dim3(kBlock), 0, st, p, v, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_f32(float* dst, const float* src, size_t count, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  if (count == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_copy_f32, dim3(blocks_for(count, 8192)), dim3(kBlock), 0, st, dst, src, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_grad_margins(const LogisticData& ld, const float* x, int64_t d, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  const int vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(ld.A) & 15u) == 0) &&
+                  ((reinterpret_cast<uintptr_t>(x) & 15u) == 0);
+  hipLaunchKernelGGL(k_grad_margins, dim3((unsigned)((ld.rows + 3) / 4)), dim3(kBlock), 0, st, ld, x, d, vec);
+  return hipGetLastError();
+}
+
+hipError_t launch_grad_cols(const LogisticData& ld, const float* x, float* grads, int n, int64_t d, hipStream_t st) {
+  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(ld.A) & 15u) == 0);
+  const int rpc = (int)((ld.max_rows + ld.row_chunks - 1) / ld.row_chunks);
+  const int64_t cols_per_block = (int64_t)kBlock * (vec ? 4 : 1);
+  const dim3 grid((unsigned)((d + cols_per_block - 1) / cols_per_block), ld.row_chunks, n);
+  if (vec) hipLaunchKernelGGL((k_grad_cols<true>), grid, dim3(kBlock), 0, st, ld, x, grads, d, rpc);
+  else hipLaunchKernelGGL((k_grad_cols<false>), grid, dim3(kBlock), 0, st, ld, x, grads, d, rpc);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (ld.row_chunks > 1) {
+    hipLaunchKernelGGL(k_grad_finish, dim3((unsigned)((d + kBlock - 1) / kBlock), n), dim3(kBlock), 0, st, ld, x,
+                       grads, d);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace adacgd

@@ -1,0 +1,77 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad configurations with the documented codes."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2211_00188_amd import engine as E
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+pytestmark = pytest.mark.skipif(not os.path.exists(E.LIB_PATH), reason="libadacgd.so not built")
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "adacgd.h")).read()
+    declared = set(re.findall(r"^(?:int|const char\*)\s+(adacgd_\w+)\s*\(", hdr, flags=re.M))
+    assert declared == set(E.EXPORTS)
+    lib = E.load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def _cfg(**kw):
+    base = dict(n=4, d=100, worker_levels=[(E.TOPK, 1), (E.TOPK, 10)], zeta_worker=1.0,
+                master_levels=[(E.TOPK, 5)], zeta_master=0.0, grad_mode=E.GRAD_EXTERNAL)
+    base.update(kw)
+    return E.make_config(**base)
+
+
+def test_workspace_size_is_reported_and_grows_with_problem():
+    a = E.adacgd_workspace_bytes(_cfg()[0])
+    b = E.adacgd_workspace_bytes(_cfg(n=8, d=100000)[0])
+    assert 0 < a < b
+    assert a % 256 == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n=0), 1), (dict(d=0), 1), (dict(d=1 << 31), 1), (dict(n=70000), 1),
+    (dict(worker_levels=[(E.TOPK, 0)]), 1), (dict(worker_levels=[(E.TOPK, 101)]), 1),
+    (dict(worker_levels=[(E.QUANT, 1)]), 1), (dict(worker_levels=[(E.QUANT, 17)]), 1),
+    (dict(worker_levels=[]), 1), (dict(worker_levels=[(7, 3)]), 1),
+    (dict(zeta_worker=-1.0), 1), (dict(zeta_worker=float("nan")), 1), (dict(gamma=float("inf")), 1),
+    (dict(worker_levels=[(E.TOPK, 10), (E.TOPK, 1)]), 2),
+    (dict(worker_levels=[(E.TOPK, 50), (E.QUANT, 2)]), 2),
+    (dict(grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_FULLGRAD), 1),
+    (dict(grad_mode=5), 1),
+])
+def test_bad_configurations_are_rejected(kw, code):
+    with pytest.raises(E.AdaCGDError) as ei:
+        E.adacgd_workspace_bytes(_cfg(**kw)[0])
+    assert ei.value.code == code
+    assert str(ei.value)
+
+
+def test_unsorted_levels_accepted_with_flag():
+    cfg, _ = _cfg(worker_levels=[(E.TOPK, 10), (E.TOPK, 1)], flags=E.FLAG_ANY_LEVEL_ORDER)
+    assert E.adacgd_workspace_bytes(cfg) > 0
+
+
+def test_init_rejects_missing_pointers_without_touching_the_device():
+    cfg, _ = _cfg()
+    lib = E.load_library()
+    ctx = C.c_void_p(None)
+    assert lib.adacgd_init(C.byref(cfg), C.byref(ctx)) == 1      # x0 is null
+    assert b"x0" in lib.adacgd_last_error(None)
+    assert lib.adacgd_destroy(None) == 0
+    assert lib.adacgd_step(None, None, None, 1) == 1
+
+
+def test_logistic_shards_validated():
+    so = np.array([0, 10, 10, 30, 40], dtype=np.int64)
+    with pytest.raises(E.AdaCGDError) as ei:
+        E.adacgd_workspace_bytes(_cfg(grad_mode=E.GRAD_LOGISTIC, shard_offsets=so)[0])
+    assert ei.value.code == 1 and "empty shard" in str(ei.value)
