@@ -61,29 +61,40 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* lds4, 
   return base + inc - v;
 }
 
-// Loads that must observe what other blocks of the same launch wrote.
+// Data that one block writes and another block of the same launch reads goes through
+// agent-scope atomic accesses only (relaxed atomic stores, loads and read-modify-writes):
+// those are performed at the device's point of coherence, so no cache write-back or
+// invalidate is needed to make them visible -- a release/acquire fence at agent scope
+// would write back and invalidate the whole L2 of the XCD once per block.
 template <typename T>
 __device__ __forceinline__ T ld_coherent(const T* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+template <typename T>
+__device__ __forceinline__ void st_coherent(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
-// Every block of a node calls this once after its last global write.  Returns true in
+// Every block of a node calls this once after its last coherent write.  Returns true in
 // all threads of exactly one block per node: the one that arrived last.  That block may
 // then read what the others wrote (with ld_coherent) and finish the node's work; the
 // counter is back at zero when it returns.  No block ever waits for another.
+// Ordering: each wave first waits until its own vector stores and atomics have completed
+// (vmcnt reaches 0), the block barrier extends that to the whole block, and only then is
+// the arrival counted.
 __device__ __forceinline__ bool arrive_last(uint32_t* counter, uint32_t nblocks, int* lds_flag) {
-  __threadfence();
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (threadIdx.x == 0) {
-    uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     int last = (prev == nblocks - 1);
     if (last) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     *lds_flag = last;
   }
   __syncthreads();
-  const bool last = *lds_flag != 0;
-  if (last) __threadfence();
-  return last;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  return *lds_flag != 0;
 }
 
 __device__ __forceinline__ uint32_t fbits(float v) { return __float_as_uint(v); }

@@ -41,6 +41,7 @@ struct NodeSet {
   int nn;
   int64_t d;
   int tiles;        // ceil(d / kTile)
+  int groups;       // ceil(d / kWaveTile): candidate groups, one per wavefront share of a tile
   int G;            // blocks per node of the streaming kernels (scan, filter)
   int G2;           // blocks per node of the candidate kernels (4 groups per block at a time)
   uint32_t Kcap;    // message capacity per node = largest Top-K size (0 if none)
@@ -54,7 +55,6 @@ struct NodeSet {
   uint32_t* eqcnt;      // [nn][p]                count of keys equal to T_s
   uint32_t* bmin;       // [nn]                   lowest first-digit bin that holds candidates
   uint32_t* done;       // [nn]                   arrival counter of the last-block epilogues
-  uint32_t* cursor;     // [nn]                   candidates reserved so far
   uint32_t* kmax;       // [nn]                   running max magnitude key of the current scan; zero between launches
   uint32_t* amax;       // [nn]                   max magnitude key of the last scan (quantiser scale a)
   double* partS;        // [nn][G]
@@ -67,13 +67,15 @@ struct NodeSet {
   double* Eb;           // [nn]  energy below the candidate bins
   double* qerr;         // [nn][nq]
   double* err;          // [nn][m]
-  uint32_t* grp_start;  // [nn][tiles]  offset of the tile's candidates in the node's list
-  uint32_t* grp_count;  // [nn][tiles]
-  uint32_t* cnt_gt;     // [nn][p][tiles]  candidates with key > T_s
-  uint32_t* cnt_eq;     // [nn][p][tiles]  candidates with key == T_s
-  uint32_t* out_off;    // [nn][tiles+1]   message offset of the tile for the chosen level
-  uint32_t* eq_before;  // [nn][tiles]     ties in earlier tiles
-  uint2* cand;          // [nn][d]         (coordinate, value bits), grouped by tile
+  uint32_t* grp_count;  // [nn][groups]
+  uint32_t* cnt_gt;     // [nn][p][groups] candidates with key > T_s
+  uint32_t* cnt_eq;     // [nn][p][groups] candidates with key == T_s
+  uint32_t* blk_gt;     // [nn][p][G2]  per tally block: candidates with key > T_s
+  uint32_t* blk_eq;     // [nn][p][G2]  per tally block: candidates with key == T_s
+  uint32_t* blk_out;    // [nn][G2]     message offset of the block's first group, chosen level
+  uint32_t* blk_eqb;    // [nn][G2]     ties before the block's first group, chosen level
+  uint32_t* tile_off;   // [nn][tiles+1] message offset of each tile's first entry (last = total)
+  uint2* cand;          // [nn][d]  (coordinate, value bits); group g starts at g * kWaveTile
   int32_t* level;       // [nn]   0 = skip
   int32_t* sel_slot;    // [nn]   slot of the chosen Top-K level, -1 otherwise
   int32_t* sel_q;       // [nn]   quantiser index of the chosen level, -1 otherwise

@@ -106,7 +106,7 @@ int build_levels(const adacgd_level* in, int m, float zeta, int64_t d, uint32_t 
 }
 
 void carve_nodeset(Carver& c, NodeSet& ns) {
-  const size_t nn = ns.nn, p = ns.lv.p, nq = ns.lv.nq, m = ns.lv.m, tiles = ns.tiles;
+  const size_t nn = ns.nn, p = ns.lv.p, nq = ns.lv.nq, m = ns.lv.m, tiles = ns.groups;
   ns.hist0 = c.take<uint32_t>(nn * kBins0);
   ns.ref1 = c.take<uint32_t>(nn * p * kBins1);
   ns.ref2 = c.take<uint32_t>(nn * p * kBins2);
@@ -119,7 +119,6 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.eqcnt = c.take<uint32_t>(nn * p);
   ns.bmin = c.take<uint32_t>(nn);
   ns.amax = c.take<uint32_t>(nn);
-  ns.cursor = c.take<uint32_t>(nn);
   ns.partS = c.take<double>(nn * ns.G);
   ns.partD = c.take<double>(nn * ns.G);
   ns.partEb = c.take<double>(nn * ns.G);
@@ -130,12 +129,14 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.Eb = c.take<double>(nn);
   ns.qerr = c.take<double>(nn * nq);
   ns.err = c.take<double>(nn * m);
-  ns.grp_start = c.take<uint32_t>(nn * tiles);
   ns.grp_count = c.take<uint32_t>(nn * tiles);
   ns.cnt_gt = c.take<uint32_t>(nn * p * tiles);
   ns.cnt_eq = c.take<uint32_t>(nn * p * tiles);
-  ns.out_off = c.take<uint32_t>(nn * (tiles + 1));
-  ns.eq_before = c.take<uint32_t>(nn * tiles);
+  ns.blk_gt = c.take<uint32_t>(nn * p * ns.G2);
+  ns.blk_eq = c.take<uint32_t>(nn * p * ns.G2);
+  ns.blk_out = c.take<uint32_t>(nn * ns.G2);
+  ns.blk_eqb = c.take<uint32_t>(nn * ns.G2);
+  ns.tile_off = c.take<uint32_t>(nn * ((size_t)ns.tiles + 1));
   ns.cand = p ? c.take<uint2>(nn * (size_t)ns.d) : nullptr;
   ns.level = c.take<int32_t>(nn);
   ns.sel_slot = c.take<int32_t>(nn);
@@ -156,8 +157,13 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d) {
   const int want = (2560 + nn - 1) / nn;
   ns.G = ns.tiles < want ? ns.tiles : want;
   if (ns.G < 1) ns.G = 1;
-  const int g2 = (ns.tiles + 3) / 4;
-  ns.G2 = g2 < 512 ? g2 : 512;
+  ns.groups = (int)((d + kWaveTile - 1) / kWaveTile);
+  // candidate kernels: about 2048 blocks in all, each owning a contiguous range of groups
+  int g2 = (ns.groups + 3) / 4;
+  const int want2 = (2048 + nn - 1) / nn;
+  if (g2 > want2) g2 = want2;
+  const int gb = (ns.groups + g2 - 1) / g2;
+  ns.G2 = (ns.groups + gb - 1) / gb;
   ns.Kcap = ns.lv.p ? ns.lv.K[ns.lv.p - 1] : 0;
 }
 

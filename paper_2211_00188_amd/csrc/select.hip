@@ -152,8 +152,8 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
   S = block_sum(S, red);
   D = block_sum(D, red);
   if (tid == 0) {
-    ns.partS[(size_t)node * ns.G + blockIdx.x] = S;
-    ns.partD[(size_t)node * ns.G + blockIdx.x] = D;
+    st_coherent(&ns.partS[(size_t)node * ns.G + blockIdx.x], S);
+    st_coherent(&ns.partD[(size_t)node * ns.G + blockIdx.x], D);
   }
   if (ns.lv.nq > 0) {
     kmax = wave_max(kmax);
@@ -191,7 +191,6 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
     ns.S[node] = s;
     ns.D[node] = DIFF ? a.extD[node] : dd;
     ns.bmin[node] = p > 0 ? s_bin[p - 1] : (uint32_t)kBins0;   // largest K reaches lowest
-    ns.cursor[node] = 0;
     if (ns.lv.nq > 0) {
       ns.amax[node] = ld_coherent(&ns.kmax[node]);
       ns.kmax[node] = 0;
@@ -236,13 +235,11 @@ __device__ __forceinline__ float quant_one(float v, float a, float s, float c, f
 // ---------------------------------------------------------------------------
 // filter
 // ---------------------------------------------------------------------------
-template <bool DIFF, bool VEC, bool QUANT>
+template <bool DIFF, bool VEC, bool QUANT, int P>
 __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   extern __shared__ uint32_t ref1[];   // [p][kBins1]
   __shared__ double red[4];
   __shared__ uint32_t lds4[4];
-  __shared__ uint32_t s_wtot[4];
-  __shared__ uint32_t s_start;
   __shared__ int s_flag;
   __shared__ uint32_t s_rank[1], s_bin[1], s_rk[1], s_cnt[1];
 
@@ -256,9 +253,9 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
 
   for (int b = tid; b < p * kBins1; b += kBlock) ref1[b] = 0;
   const uint32_t bmin = ns.bmin[node];
-  uint32_t pre[kMaxLevels];
+  uint32_t pre[P];
 #pragma unroll
-  for (int s = 0; s < kMaxLevels; ++s) pre[s] = s < p ? ns.prefix[node * p + s] : 0xFFFFFFFFu;
+  for (int s = 0; s < P; ++s) pre[s] = s < p ? ns.prefix[node * p + s] : 0xFFFFFFFFu;
   __syncthreads();
 
   // quantiser constants of this node
@@ -301,8 +298,12 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
           if (bin >= bmin) {
             mask |= 1u << (k * 4 + c);
 #pragma unroll
-            for (int s = 0; s < kMaxLevels; ++s)
-              if (s < p && bin == pre[s]) atomicAdd(&ref1[s * kBins1 + ((key >> kShift1) & (kBins1 - 1))], 1u);
+            for (int s = 0; s < P; ++s) {
+              const bool hit = bin == pre[s];
+              if (ballot(hit) != 0) {          // wave-uniform: skip the LDS instruction when no lane hits
+                if (hit) atomicAdd(&ref1[s * kBins1 + ((key >> kShift1) & (kBins1 - 1))], 1u);
+              }
+            }
           } else {
             Eb = fma(dv, dv, Eb);
           }
@@ -341,20 +342,12 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
 #pragma unroll
       for (int j = 0; j < kIter * 4; ++j) wtot += popc64(ballot((mask >> j) & 1u));
     }
-    __syncthreads();                      // previous tile's readers of s_wtot / s_start are done
-    if (lane == 0) s_wtot[w] = wtot;
-    __syncthreads();
-    if (tid == 0) {
-      const uint32_t total = s_wtot[0] + s_wtot[1] + s_wtot[2] + s_wtot[3];
-      const uint32_t start = total ? atomicAdd(&ns.cursor[node], total) : 0u;
-      ns.grp_start[(size_t)node * ns.tiles + t] = start;
-      ns.grp_count[(size_t)node * ns.tiles + t] = total;
-      s_start = start;
-    }
-    __syncthreads();
+    // one group per wavefront, stored at the group's own fixed offset of the candidate list
+    const int grp = t * 4 + w;
+    const uint32_t start = (uint32_t)grp * kWaveTile;
+    if (lane == 0 && grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = wtot;
     if (wtot) {
-      uint32_t running = s_start;
-      for (int i = 0; i < w; ++i) running += s_wtot[i];
+      uint32_t running = start;
       if (VEC) {
 #pragma unroll
         for (int k = 0; k < kIter; ++k) {
@@ -383,13 +376,13 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   }
 
   Eb = block_sum(Eb, red);
-  if (tid == 0) ns.partEb[(size_t)node * ns.G + blockIdx.x] = Eb;
+  if (tid == 0) st_coherent(&ns.partEb[(size_t)node * ns.G + blockIdx.x], Eb);
   if (QUANT) {
 #pragma unroll
     for (int q = 0; q < kMaxLevels; ++q) {
       if (q < nq) {
         const double e = block_sum(qacc[q], red);
-        if (tid == 0) ns.partQ[((size_t)node * ns.G + blockIdx.x) * nq + q] = e;
+        if (tid == 0) st_coherent(&ns.partQ[((size_t)node * ns.G + blockIdx.x) * nq + q], e);
       }
     }
   }
@@ -435,6 +428,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
 // ---------------------------------------------------------------------------
 // refine: third digit over the candidate lists (one wavefront per tile group)
 // ---------------------------------------------------------------------------
+template <int P>
 __global__ __launch_bounds__(kBlock) void k_refine(NodeSet ns) {
   extern __shared__ uint32_t ref2[];   // [p][kBins2]
   __shared__ uint32_t lds4[4];
@@ -445,19 +439,25 @@ __global__ __launch_bounds__(kBlock) void k_refine(NodeSet ns) {
   const size_t row = (size_t)node * (size_t)ns.d;
   const uint2* __restrict__ cand = ns.cand + row;
   for (int b = tid; b < p * kBins2; b += kBlock) ref2[b] = 0;
-  uint32_t pre[kMaxLevels];
+  uint32_t pre[P];
 #pragma unroll
-  for (int s = 0; s < kMaxLevels; ++s) pre[s] = s < p ? ns.prefix[node * p + s] : 0xFFFFFFFFu;
+  for (int s = 0; s < P; ++s) pre[s] = s < p ? ns.prefix[node * p + s] : 0xFFFFFFFFu;
   __syncthreads();
-  for (int g = blockIdx.x * 4 + w; g < ns.tiles; g += gridDim.x * 4) {
-    const uint32_t start = ns.grp_start[(size_t)node * ns.tiles + g];
-    const uint32_t cnt = ns.grp_count[(size_t)node * ns.tiles + g];
-    for (uint32_t e = lane; e < cnt; e += 64) {
-      const uint32_t key = cand[start + e].y & 0x7FFFFFFFu;
+  for (int g = blockIdx.x * 4 + w; g < ns.groups; g += gridDim.x * 4) {
+    const uint32_t start = (uint32_t)g * kWaveTile;
+    const uint32_t cnt = ns.grp_count[(size_t)node * ns.groups + g];
+    for (uint32_t e0 = 0; e0 < cnt; e0 += 64) {
+      const uint32_t e = e0 + lane;
+      const bool valid = e < cnt;
+      const uint32_t key = valid ? (cand[start + e].y & 0x7FFFFFFFu) : 0u;
       const uint32_t hi = key >> kShift1;
 #pragma unroll
-      for (int s = 0; s < kMaxLevels; ++s)
-        if (s < p && hi == pre[s]) atomicAdd(&ref2[s * kBins2 + (key & (kBins2 - 1))], 1u);
+      for (int s = 0; s < P; ++s) {
+        const bool hit = valid && hi == pre[s];
+        if (ballot(hit) != 0) {
+          if (hit) atomicAdd(&ref2[s * kBins2 + (key & (kBins2 - 1))], 1u);
+        }
+      }
     }
   }
   __syncthreads();
@@ -484,31 +484,46 @@ __global__ __launch_bounds__(kBlock) void k_refine(NodeSet ns) {
 }
 
 // ---------------------------------------------------------------------------
-// tally: counts and band energies against the exact thresholds; epilogue = level choice
+// tally: counts and band energies against the exact thresholds; epilogue = level choice.
+// Block b owns the contiguous group range [b*GB, (b+1)*GB), GB = ceil(groups / G2); the
+// compact kernel uses the same mapping.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t t = __shfl_up(v, o, 64);
+    if (lane >= (uint32_t)o) v += t;
+  }
+  return v;
+}
+
 template <int P>
 __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
   __shared__ double red[4];
   __shared__ uint32_t lds4[4];
   __shared__ int s_flag;
   __shared__ double s_strict[kMaxLevels];
+  __shared__ uint32_t s_tg[4][P], s_te[4][P];
   __shared__ int s_slot;
   __shared__ uint32_t s_r;
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int p = ns.lv.p;
-  const int tiles = ns.tiles;
+  const int groups = ns.groups;
+  const int GB = (groups + ns.G2 - 1) / ns.G2;
+  const int lo = blockIdx.x * GB, hi = min(groups, lo + GB);
   const size_t row = (size_t)node * (size_t)ns.d;
   const uint2* __restrict__ cand = ns.cand + row;
-  uint32_t T[P];
+  uint32_t T[P], tg[P], te[P];
   double strict[P];
 #pragma unroll
   for (int s = 0; s < P; ++s) {
     T[s] = s < p ? ns.prefix[node * p + s] : 0u;
     strict[s] = 0.0;
+    tg[s] = te[s] = 0;
   }
-  for (int g = blockIdx.x * 4 + w; g < tiles; g += gridDim.x * 4) {
-    const uint32_t start = ns.grp_start[(size_t)node * tiles + g];
-    const uint32_t cnt = ns.grp_count[(size_t)node * tiles + g];
+  for (int g = lo + w; g < hi; g += 4) {
+    const uint32_t start = (uint32_t)g * kWaveTile;
+    const uint32_t cnt = ns.grp_count[(size_t)node * groups + g];
     uint32_t cg[P], ce[P];
 #pragma unroll
     for (int s = 0; s < P; ++s) cg[s] = ce[s] = 0;
@@ -528,26 +543,38 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
         }
       }
     }
-    if (lane == 0) {
 #pragma unroll
-      for (int s = 0; s < P; ++s) {
-        if (s < p) {
-          ns.cnt_gt[((size_t)node * p + s) * tiles + g] = cg[s];
-          ns.cnt_eq[((size_t)node * p + s) * tiles + g] = ce[s];
+    for (int s = 0; s < P; ++s) {
+      if (s < p) {
+        if (lane == 0) {
+          ns.cnt_gt[((size_t)node * p + s) * groups + g] = cg[s];
+          ns.cnt_eq[((size_t)node * p + s) * groups + g] = ce[s];
         }
+        tg[s] += cg[s];
+        te[s] += ce[s];
       }
     }
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int s = 0; s < P; ++s) { s_tg[w][s] = tg[s]; s_te[w][s] = te[s]; }
   }
 #pragma unroll
   for (int s = 0; s < P; ++s) {
     if (s < p) {
-      const double e = block_sum(strict[s], red);
-      if (tid == 0) ns.partStrict[((size_t)node * ns.G2 + blockIdx.x) * p + s] = e;
+      const double e = block_sum(strict[s], red);     // (contains the barriers that publish s_tg / s_te)
+      if (tid == 0) st_coherent(&ns.partStrict[((size_t)node * ns.G2 + blockIdx.x) * p + s], e);
     }
+  }
+  __syncthreads();
+  if (tid < p) {
+    const size_t o = ((size_t)node * p + tid) * ns.G2 + blockIdx.x;
+    st_coherent(&ns.blk_gt[o], s_tg[0][tid] + s_tg[1][tid] + s_tg[2][tid] + s_tg[3][tid]);
+    st_coherent(&ns.blk_eq[o], s_te[0][tid] + s_te[1][tid] + s_te[2][tid] + s_te[3][tid]);
   }
   if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
 
-  // ---- epilogue: realised errors, the AdaCGD cascade, message layout ----
+  // ---- epilogue: realised errors, the AdaCGD cascade, message layout per block ----
   for (int s = 0; s < p; ++s) {
     double e = 0.0;
     for (int b = tid; b < (int)gridDim.x; b += kBlock)
@@ -594,41 +621,34 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
       ns.sel_T[node] = ns.prefix[node * p + slot];
       ns.sel_r[node] = ns.rank[node * p + slot];
       s_r = ns.rank[node * p + slot];
+      ns.tile_off[(size_t)node * (ns.tiles + 1) + ns.tiles] = lv.K[slot];
     }
     s_slot = slot;
   }
   __syncthreads();
   const int slot = s_slot;
   if (slot < 0) return;
+  // ties are taken in coordinate order: block b takes clamp(r - ties before b, 0, ties in b)
   const uint32_t r = s_r;
-  const uint32_t* cgt = ns.cnt_gt + ((size_t)node * p + slot) * tiles;
-  const uint32_t* ceq = ns.cnt_eq + ((size_t)node * p + slot) * tiles;
-  uint32_t* out_off = ns.out_off + (size_t)node * (tiles + 1);
-  uint32_t* eq_before = ns.eq_before + (size_t)node * tiles;
-  const int per = (tiles + kBlock - 1) / kBlock;
-  const int g0 = tid * per, g1 = min(tiles, g0 + per);
-  uint32_t eqs = 0;
-  for (int g = g0; g < g1; ++g) eqs += ld_coherent(&ceq[g]);
-  uint32_t tot;
-  uint32_t eqb = block_excl_scan(eqs, lds4, &tot);
-  uint32_t outs = 0, eqrun = eqb;
-  for (int g = g0; g < g1; ++g) {
-    const uint32_t ce = ld_coherent(&ceq[g]);
-    const uint32_t take = eqrun >= r ? 0u : min(ce, r - eqrun);
-    outs += ld_coherent(&cgt[g]) + take;
-    eqrun += ce;
+  const uint32_t* bgt = ns.blk_gt + ((size_t)node * p + slot) * ns.G2;
+  const uint32_t* beq = ns.blk_eq + ((size_t)node * p + slot) * ns.G2;
+  uint32_t eq_carry = 0, out_carry = 0;
+  for (int b0 = 0; b0 < (int)gridDim.x; b0 += kBlock) {
+    const int b = b0 + tid;
+    const bool in = b < (int)gridDim.x;
+    const uint32_t ce = in ? ld_coherent(&beq[b]) : 0u;
+    const uint32_t cg = in ? ld_coherent(&bgt[b]) : 0u;
+    uint32_t tot_e, tot_o;
+    const uint32_t eqb = eq_carry + block_excl_scan(ce, lds4, &tot_e);
+    const uint32_t take = eqb >= r ? 0u : min(ce, r - eqb);
+    const uint32_t outb = out_carry + block_excl_scan(cg + take, lds4, &tot_o);
+    if (in) {
+      ns.blk_eqb[(size_t)node * ns.G2 + b] = eqb;
+      ns.blk_out[(size_t)node * ns.G2 + b] = outb;
+    }
+    eq_carry += tot_e;
+    out_carry += tot_o;
   }
-  uint32_t outb = block_excl_scan(outs, lds4, &tot);
-  eqrun = eqb;
-  for (int g = g0; g < g1; ++g) {
-    const uint32_t ce = ld_coherent(&ceq[g]);
-    const uint32_t take = eqrun >= r ? 0u : min(ce, r - eqrun);
-    out_off[g] = outb;
-    eq_before[g] = eqrun;
-    outb += ld_coherent(&cgt[g]) + take;
-    eqrun += ce;
-  }
-  if (tid == 0) out_off[tiles] = tot;
 }
 
 // ---------------------------------------------------------------------------
@@ -636,38 +656,63 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_compact(NodeSet ns, PassArgs a) {
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-  if (ns.sel_slot[node] < 0) return;
+  const int slot = ns.sel_slot[node];
+  if (slot < 0) return;
   const uint32_t T = ns.sel_T[node], r = ns.sel_r[node];
-  const int tiles = ns.tiles;
+  const int groups = ns.groups, p = ns.lv.p;
+  const int GB = (groups + ns.G2 - 1) / ns.G2;
+  const int lo = blockIdx.x * GB, hi = min(groups, lo + GB);
+  if (lo >= hi) return;
   const size_t row = (size_t)node * (size_t)ns.d;
   const uint2* __restrict__ cand = ns.cand + row;
   float* __restrict__ h = a.h + row;
   int32_t* __restrict__ midx = ns.msg_idx + (size_t)node * ns.Kcap;
   float* __restrict__ mval = ns.msg_val + (size_t)node * ns.Kcap;
-  for (int g = blockIdx.x * 4 + w; g < tiles; g += gridDim.x * 4) {
-    const uint32_t start = ns.grp_start[(size_t)node * tiles + g];
-    const uint32_t cnt = ns.grp_count[(size_t)node * tiles + g];
-    uint32_t out = ns.out_off[(size_t)node * (tiles + 1) + g];
-    uint32_t eqb = ns.eq_before[(size_t)node * tiles + g];
-    for (uint32_t e0 = 0; e0 < cnt; e0 += 64) {
-      const uint32_t e = e0 + lane;
-      const bool valid = e < cnt;
-      const uint2 c = valid ? cand[start + e] : make_uint2(0u, 0u);
-      const uint32_t key = c.y & 0x7FFFFFFFu;
-      const bool eq = valid && key == T;
-      const uint64_t beq = ballot(eq);
-      const bool take = valid && (key > T || (eq && eqb + below(beq) < r));
-      const uint64_t bt = ballot(take);
-      if (take) {
-        const uint32_t pos = out + below(bt);
-        const float val = __uint_as_float(c.y);
-        midx[pos] = (int32_t)c.x;
-        mval[pos] = val;
-        h[c.x] = h[c.x] + val;
+  const uint32_t* cgt = ns.cnt_gt + ((size_t)node * p + slot) * groups;
+  const uint32_t* ceq = ns.cnt_eq + ((size_t)node * p + slot) * groups;
+  uint32_t eq_base = ns.blk_eqb[(size_t)node * ns.G2 + blockIdx.x];
+  uint32_t out_base = ns.blk_out[(size_t)node * ns.G2 + blockIdx.x];
+  // every wavefront scans the block's groups 64 at a time (lane i <-> group c0 + i) to get each
+  // group's message offset and tie rank, then handles the groups with (g - lo) % 4 == w
+  for (int c0 = lo; c0 < hi; c0 += 64) {
+    const int gi = c0 + (int)lane;
+    const uint32_t ce = gi < hi ? ceq[gi] : 0u;
+    const uint32_t cg = gi < hi ? cgt[gi] : 0u;
+    const uint32_t eq_inc = wave_incl_scan(ce, lane);
+    const uint32_t eqb_l = eq_base + eq_inc - ce;
+    const uint32_t take = eqb_l >= r ? 0u : min(ce, r - eqb_l);
+    const uint32_t out_inc = wave_incl_scan(cg + take, lane);
+    const uint32_t out_l = out_base + out_inc - (cg + take);
+    const int nchunk = min(64, hi - c0);
+    for (int i = w; i < nchunk; i += 4) {
+      const int g = c0 + i;
+      uint32_t eqb = __shfl(eqb_l, i, 64);
+      uint32_t out = __shfl(out_l, i, 64);
+      if ((g & 3) == 0 && lane == 0) ns.tile_off[(size_t)node * (ns.tiles + 1) + (g >> 2)] = out;
+      const uint32_t start = (uint32_t)g * kWaveTile;
+      const uint32_t cnt = ns.grp_count[(size_t)node * groups + g];
+      for (uint32_t e0 = 0; e0 < cnt; e0 += 64) {
+        const uint32_t e = e0 + lane;
+        const bool valid = e < cnt;
+        const uint2 c = valid ? cand[start + e] : make_uint2(0u, 0u);
+        const uint32_t key = c.y & 0x7FFFFFFFu;
+        const bool eq = valid && key == T;
+        const uint64_t beq = ballot(eq);
+        const bool tk = valid && (key > T || (eq && eqb + below(beq) < r));
+        const uint64_t bt = ballot(tk);
+        if (tk) {
+          const uint32_t pos = out + below(bt);
+          const float val = __uint_as_float(c.y);
+          midx[pos] = (int32_t)c.x;
+          mval[pos] = val;
+          h[c.x] = h[c.x] + val;
+        }
+        eqb += popc64(beq);
+        out += popc64(bt);
       }
-      eqb += popc64(beq);
-      out += popc64(bt);
     }
+    eq_base += __shfl(eq_inc, 63, 64);
+    out_base += __shfl(out_inc, 63, 64);
   }
 }
 
@@ -745,12 +790,19 @@ hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <bool DIFF, bool VEC>
-static void launch_filter_q(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+template <bool DIFF, bool VEC, int P>
+static void launch_filter_p(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   const dim3 grid(ns.G, ns.nn), block(kBlock);
   const size_t lds = (size_t)ns.lv.p * kBins1 * sizeof(uint32_t);
-  if (ns.lv.nq > 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, true>), grid, block, lds, st, ns, a);
-  else hipLaunchKernelGGL((k_filter<DIFF, VEC, false>), grid, block, lds, st, ns, a);
+  if (ns.lv.nq > 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, true, P>), grid, block, lds, st, ns, a);
+  else hipLaunchKernelGGL((k_filter<DIFF, VEC, false, P>), grid, block, lds, st, ns, a);
+}
+
+template <bool DIFF, bool VEC>
+static void launch_filter_q(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+  if (ns.lv.p <= 4) launch_filter_p<DIFF, VEC, 4>(ns, a, st);
+  else if (ns.lv.p <= 8) launch_filter_p<DIFF, VEC, 8>(ns, a, st);
+  else launch_filter_p<DIFF, VEC, 16>(ns, a, st);
 }
 
 hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
@@ -770,7 +822,10 @@ hipError_t launch_refine(const NodeSet& ns, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
   if (ns.lv.p == 0) return hipSuccess;
   const dim3 grid(ns.G2, ns.nn), block(kBlock);
-  hipLaunchKernelGGL(k_refine, grid, block, (size_t)ns.lv.p * kBins2 * sizeof(uint32_t), st, ns);
+  const size_t lds = (size_t)ns.lv.p * kBins2 * sizeof(uint32_t);
+  if (ns.lv.p <= 4) hipLaunchKernelGGL((k_refine<4>), grid, block, lds, st, ns);
+  else if (ns.lv.p <= 8) hipLaunchKernelGGL((k_refine<8>), grid, block, lds, st, ns);
+  else hipLaunchKernelGGL((k_refine<16>), grid, block, lds, st, ns);
   return hipGetLastError();
 }
 

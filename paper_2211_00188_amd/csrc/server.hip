@@ -52,15 +52,14 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
   const int t = blockIdx.x, tid = threadIdx.x;
   const int64_t d = ws.d;
   const int64_t base = (int64_t)t * kTile;
-  const int tiles = ws.tiles;
   for (int c = tid; c < kTile; c += kBlock) acc[c] = 0.0;
   __syncthreads();
   bool any_dense = false;
   for (int i = 0; i < ws.nn; ++i) {
     if (ws.sel_q && ws.sel_q[i] >= 0) any_dense = true;
     if (ws.sel_slot[i] < 0) continue;
-    const uint32_t lo = ws.out_off[(size_t)i * (tiles + 1) + t];
-    const uint32_t hi = ws.out_off[(size_t)i * (tiles + 1) + t + 1];
+    const uint32_t lo = ws.tile_off[(size_t)i * (ws.tiles + 1) + t];
+    const uint32_t hi = ws.tile_off[(size_t)i * (ws.tiles + 1) + t + 1];
     const int32_t* __restrict__ midx = ws.msg_idx + (size_t)i * ws.Kcap;
     const float* __restrict__ mval = ws.msg_val + (size_t)i * ws.Kcap;
     for (uint32_t e = lo + tid; e < hi; e += kBlock)
