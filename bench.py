@@ -95,14 +95,15 @@ def main():
     # (12 B per worker-coordinate) plus the message (8 B) and estimator write (4 B) per sent entry
     sent = sum(int(hist_ev[j]) * wk.worker_levels[j - 1][1] for j in range(1, len(hist_ev)))
     alg_bytes_step = 12.0 * n * d + 12.0 * sent / args.steps
-    group = ["w_scan", "w_filter", "w_refine", "w_tally", "w_compact"]
+    group = ["w_sample", "w_scan", "w_filter", "w_refine1", "w_refine2", "w_tally", "w_compact"]
     per_kernel = {}
     for k, (ms, cnt) in kms.items():
         if cnt:
             per_kernel[k] = {"avg_ms": ms / cnt, "launches": cnt}
     group_ms = sum(per_kernel[k]["avg_ms"] for k in group if k in per_kernel)
     achieved = alg_bytes_step / (group_ms * 1e-3) / 1e9
-    dom = max(group, key=lambda k: per_kernel.get(k, {"avg_ms": 0})["avg_ms"])
+    group = [k for k in group if k in per_kernel]
+    dom = max(group, key=lambda k: per_kernel[k]["avg_ms"])
     dom_bytes = {"w_scan": 12.0 * n * d, "w_filter": 8.0 * n * d}.get(dom, 0.0)
     roofline = {
         "bound": "hbm", "kernel": "+".join(group), "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

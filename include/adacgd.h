@@ -82,7 +82,8 @@ enum adacgd_flags {
   ADACGD_FLAG_RETAIN_EXT = 2,      /* GRAD_EXTERNAL: keep the caller's last gradient array as y for the
                                       next step instead of copying it; the caller must leave that array
                                       untouched until the next adacgd_step call has completed            */
-  ADACGD_FLAG_KERNEL_TIMING = 4    /* record HIP events around every kernel (see ADACGD_F_KERNEL_MS)    */
+  ADACGD_FLAG_KERNEL_TIMING = 4,   /* record HIP events around every kernel (see ADACGD_F_KERNEL_MS)    */
+  ADACGD_FLAG_TWO_PASS = 8         /* never use the sampled one-pass selection (same results, slower)   */
 };
 
 typedef struct {
@@ -166,25 +167,31 @@ enum adacgd_field {
   ADACGD_F_GRAD = 27         /* float  [n x d] same as PREV_GRAD (the gradients of the last step) */
 };
 
-/* Kernel slots of ADACGD_F_KERNEL_MS. */
+/* Kernel slots of ADACGD_F_KERNEL_MS.  W = worker side, M = master side.  Long vectors with
+ * Top-K levels only run sample + scan (the scan also extracts the candidates) and use filter
+ * only to repair a failed estimate; otherwise scan + filter run as two passes. */
 enum adacgd_kernel {
   ADACGD_K_XUPDATE = 0,
   ADACGD_K_GRAD_MARGIN = 1,
   ADACGD_K_GRAD_COLS = 2,
-  ADACGD_K_W_SCAN = 3,    /* worker: differences, norms, first-digit histogram */
-  ADACGD_K_W_FILTER = 4,  /* worker: candidate extraction, low-band energy, quantiser errors */
-  ADACGD_K_W_REFINE = 5,
-  ADACGD_K_W_TALLY = 6,   /* band energies, level choice */
-  ADACGD_K_W_COMPACT = 7, /* message + estimator update */
-  ADACGD_K_W_QAPPLY = 8,
-  ADACGD_K_AGGREGATE = 9,
-  ADACGD_K_M_SCAN = 10,
-  ADACGD_K_M_FILTER = 11,
-  ADACGD_K_M_REFINE = 12,
-  ADACGD_K_M_TALLY = 13,
-  ADACGD_K_M_COMPACT = 14,
-  ADACGD_K_M_QAPPLY = 15,
-  ADACGD_NUM_KERNELS = 16
+  ADACGD_K_AGGREGATE = 3,
+  ADACGD_K_W_SAMPLE = 4,   /* histogram of a 1/32 sample: candidate cut-off estimate          */
+  ADACGD_K_W_SCAN = 5,     /* differences, norms, first-digit histogram (+ candidates)        */
+  ADACGD_K_W_FILTER = 6,   /* candidate extraction, low-band energy, quantiser errors         */
+  ADACGD_K_W_REFINE1 = 7,  /* second digit of the thresholds                                  */
+  ADACGD_K_W_REFINE2 = 8,  /* last digit: exact thresholds                                    */
+  ADACGD_K_W_TALLY = 9,    /* band energies, level choice                                     */
+  ADACGD_K_W_COMPACT = 10, /* message + estimator update                                      */
+  ADACGD_K_W_QAPPLY = 11,  /* dense estimator update of quantised levels                      */
+  ADACGD_K_M_SAMPLE = 12,
+  ADACGD_K_M_SCAN = 13,
+  ADACGD_K_M_FILTER = 14,
+  ADACGD_K_M_REFINE1 = 15,
+  ADACGD_K_M_REFINE2 = 16,
+  ADACGD_K_M_TALLY = 17,
+  ADACGD_K_M_COMPACT = 18,
+  ADACGD_K_M_QAPPLY = 19,
+  ADACGD_NUM_KERNELS = 20
 };
 
 /* Copies one field to dst (host memory, or device memory if dst_on_device != 0)

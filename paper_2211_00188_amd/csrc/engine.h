@@ -43,7 +43,9 @@ struct NodeSet {
   int tiles;        // ceil(d / kTile)
   int groups;       // ceil(d / kWaveTile): candidate groups, one per wavefront share of a tile
   int G;            // blocks per node of the streaming kernels (scan, filter)
-  int G2;           // blocks per node of the candidate kernels (4 groups per block at a time)
+  int G2;           // blocks per node of the candidate kernels
+  int GS;           // blocks per node of the sample kernel
+  int onepass;      // 1: sample + scanx sequence, 0: scan + filter sequence
   uint32_t Kcap;    // message capacity per node = largest Top-K size (0 if none)
   LevelTable lv;
 
@@ -54,6 +56,9 @@ struct NodeSet {
   uint32_t* rank;       // [nn][p]                rank of the K_s-th element inside the prefix
   uint32_t* eqcnt;      // [nn][p]                count of keys equal to T_s
   uint32_t* bmin;       // [nn]                   lowest first-digit bin that holds candidates
+  uint32_t* shist;      // [nn][kBins0]           first-digit counts of the sample; zero between launches
+  uint32_t* best;       // [nn]                   estimated cut-off bin from the sample
+  uint32_t* redo;       // [nn]                   1 = estimate was too high, the repair pass must run
   uint32_t* done;       // [nn]                   arrival counter of the last-block epilogues
   uint32_t* kmax;       // [nn]                   running max magnitude key of the current scan; zero between launches
   uint32_t* amax;       // [nn]                   max magnitude key of the last scan (quantiser scale a)
@@ -119,6 +124,9 @@ struct LogisticData {
 hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_refine(const NodeSet& ns, hipStream_t st);
+hipError_t launch_refine1(const NodeSet& ns, hipStream_t st);
+hipError_t launch_sample(const NodeSet& ns, const PassArgs& a, hipStream_t st);
+hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_tally(const NodeSet& ns, hipStream_t st);
 hipError_t launch_compact(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_qapply(const NodeSet& ns, const PassArgs& a, hipStream_t st);

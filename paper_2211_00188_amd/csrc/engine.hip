@@ -110,6 +110,7 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.hist0 = c.take<uint32_t>(nn * kBins0);
   ns.ref1 = c.take<uint32_t>(nn * p * kBins1);
   ns.ref2 = c.take<uint32_t>(nn * p * kBins2);
+  ns.shist = c.take<uint32_t>(ns.onepass ? nn * kBins0 : 0);
   ns.done = c.take<uint32_t>(nn);
   ns.kmax = c.take<uint32_t>(nn);
   ns.level_hist = c.take<unsigned long long>(m + 1);
@@ -119,6 +120,8 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.eqcnt = c.take<uint32_t>(nn * p);
   ns.bmin = c.take<uint32_t>(nn);
   ns.amax = c.take<uint32_t>(nn);
+  ns.best = c.take<uint32_t>(nn);
+  ns.redo = c.take<uint32_t>(nn);
   ns.partS = c.take<double>(nn * ns.G);
   ns.partD = c.take<double>(nn * ns.G);
   ns.partEb = c.take<double>(nn * ns.G);
@@ -150,7 +153,7 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.qscale = c.take<float>(nn);
 }
 
-void shape_nodeset(NodeSet& ns, int nn, int64_t d) {
+void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
   ns.nn = nn;
   ns.d = d;
   ns.tiles = (int)((d + kTile - 1) / kTile);
@@ -165,6 +168,14 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d) {
   const int gb = (ns.groups + g2 - 1) / g2;
   ns.G2 = (ns.groups + gb - 1) / gb;
   ns.Kcap = ns.lv.p ? ns.lv.K[ns.lv.p - 1] : 0;
+  // One-pass sequence: Top-K levels only, 16-byte vector path, vectors long enough for a
+  // 1/32 sample to be informative, and a candidate set that is a minor part of the vector.
+  ns.onepass = (!force_two_pass && ns.lv.nq == 0 && ns.lv.p > 0 && d % 4 == 0 && ns.tiles >= 128 &&
+                4 * (int64_t)ns.Kcap <= d) ? 1 : 0;
+  const int wants = (512 + nn - 1) / nn;         // sample kernel: about 512 blocks in all
+  const int smax = (ns.tiles + 15) / 16;         // at least 4 rounds of 4 tiles per wavefront
+  ns.GS = wants < smax ? wants : smax;
+  if (ns.GS < 1) ns.GS = 1;
 }
 
 }  // namespace
@@ -339,12 +350,19 @@ int drain_spans(adacgd_ctx* c) {
 // one application of the AdaCGD compressor to every node of a set
 int compress(adacgd_ctx* c, NodeSet& ns, const PassArgs& a, int slot0) {
   int rc;
-  if ((rc = timed(c, slot0 + 0, [&] { return launch_scan(ns, a, c->st); }))) return rc;
-  if ((rc = timed(c, slot0 + 1, [&] { return launch_filter(ns, a, c->st); }))) return rc;
-  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 2, [&] { return launch_refine(ns, c->st); }))) return rc;
-  if ((rc = timed(c, slot0 + 3, [&] { return launch_tally(ns, c->st); }))) return rc;
-  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 4, [&] { return launch_compact(ns, a, c->st); }))) return rc;
-  if (ns.lv.nq > 0 && (rc = timed(c, slot0 + 5, [&] { return launch_qapply(ns, a, c->st); }))) return rc;
+  if (ns.onepass) {
+    if ((rc = timed(c, slot0 + 0, [&] { return launch_sample(ns, a, c->st); }))) return rc;
+    if ((rc = timed(c, slot0 + 1, [&] { return launch_scanx(ns, a, c->st); }))) return rc;
+    if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->st); }))) return rc;   // repair, usually idle
+    if ((rc = timed(c, slot0 + 3, [&] { return launch_refine1(ns, c->st); }))) return rc;
+  } else {
+    if ((rc = timed(c, slot0 + 1, [&] { return launch_scan(ns, a, c->st); }))) return rc;
+    if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->st); }))) return rc;
+  }
+  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 4, [&] { return launch_refine(ns, c->st); }))) return rc;
+  if ((rc = timed(c, slot0 + 5, [&] { return launch_tally(ns, c->st); }))) return rc;
+  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 6, [&] { return launch_compact(ns, a, c->st); }))) return rc;
+  if (ns.lv.nq > 0 && (rc = timed(c, slot0 + 7, [&] { return launch_qapply(ns, a, c->st); }))) return rc;
   return ADACGD_OK;
 }
 
@@ -379,7 +397,7 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
     a.extD = extD;
   }
   // g~_i^{t+1} = C^AC_{g~_i^t, grad f_i(x^t)}(grad f_i(x^{t+1}))
-  if ((rc = compress(c, c->W, a, ADACGD_K_W_SCAN))) return rc;
+  if ((rc = compress(c, c->W, a, ADACGD_K_W_SAMPLE))) return rc;
   if (c->grad_mode == ADACGD_GRAD_LOGISTIC) {
     c->ycur ^= 1;
   } else if (c->grad_mode == ADACGD_GRAD_EXTERNAL) {
@@ -400,7 +418,7 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
     m.seed = c->seed;
     m.step = (uint32_t)c->step;
     m.node_flag = 0x80000000u;
-    if ((rc = compress(c, c->M, m, ADACGD_K_M_SCAN))) return rc;
+    if ((rc = compress(c, c->M, m, ADACGD_K_M_SAMPLE))) return rc;
   }
   c->step += 1;
   return ADACGD_OK;
@@ -444,8 +462,8 @@ int adacgd_workspace_bytes(const adacgd_config* cfg, int64_t* bytes) {
   if (!bytes) { set_err(g_err, "bytes is null"); return ADACGD_ERR_ARG; }
   NodeSet W{}, M{};
   W.lv = wl; M.lv = ml;
-  shape_nodeset(W, (int)cfg->n, cfg->d);
-  shape_nodeset(M, 1, cfg->d);
+  shape_nodeset(W, (int)cfg->n, cfg->d, (cfg->flags & ADACGD_FLAG_TWO_PASS) != 0);
+  shape_nodeset(M, 1, cfg->d, (cfg->flags & ADACGD_FLAG_TWO_PASS) != 0);
   LogisticData ld;
   shape_logistic(cfg, ld);
   Layout L{};
@@ -484,8 +502,8 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
   std::memset(c->ms_cnt, 0, sizeof(c->ms_cnt));
   c->W = NodeSet{}; c->M = NodeSet{};
   c->W.lv = wl; c->M.lv = ml;
-  shape_nodeset(c->W, (int)cfg->n, cfg->d);
-  shape_nodeset(c->M, 1, cfg->d);
+  shape_nodeset(c->W, (int)cfg->n, cfg->d, (cfg->flags & ADACGD_FLAG_TWO_PASS) != 0);
+  shape_nodeset(c->M, 1, cfg->d, (cfg->flags & ADACGD_FLAG_TWO_PASS) != 0);
   shape_logistic(cfg, c->ld);
   Layout L{};
   const size_t need = carve_all(c->ws_base, cfg, c->W, c->M, c->ld, L);

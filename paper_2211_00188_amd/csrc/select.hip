@@ -4,8 +4,19 @@
 // cascade of the AdaCGD definition, and the EF21 update h <- h + C_j(x - h) (Eq. (7))
 // with the sparse message.
 //
-// Kernel sequence per node set (every kernel ends with a "last block of the node"
-// epilogue that finishes the node's small serial work, so no extra launches):
+// Two kernel sequences per node set.  Every kernel ends with a "last block of the node"
+// epilogue that finishes the node's small serial work, so no extra launches.
+//
+// One-pass sequence (Top-K levels only, long vectors):
+//   sample  : first-digit histogram of 1/32 of the vector (one 1 KB row of every tile)
+//             epilogue: a conservative estimate b_est of the candidate cut-off bin
+//   scanx   : scan (below) fused with the candidate extraction at b_est and the energy
+//             below b_est; epilogue additionally checks, with the exact histogram, that
+//             b_est is not above the true cut-off bin, else marks the node for `filter`
+//   filter  : only for marked nodes (none in the common case)
+//   refine1, refine2, tally, compact as below
+//
+// Two-pass sequence (any level set, any length):
 //   scan    : v = x - h, S = ||v||^2, D = ||x - y||^2, first-digit histogram
 //             epilogue: bin and in-bin rank of each Top-K size, candidate cut-off bin
 //   filter  : re-forms v, sums the energy below the cut-off, writes candidates
@@ -94,6 +105,56 @@ __device__ void locate(uint32_t* hist, int nr, const uint32_t* rank, uint32_t* o
     cum += c;
   }
   __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// ordered extraction of one wavefront's flagged elements of a tile (bit j of mask <->
+// iteration j/4, component j%4) into its group's slot of the candidate list
+// ---------------------------------------------------------------------------
+template <bool VEC>
+__device__ __forceinline__ uint32_t count_flagged(uint32_t mask) {
+  uint32_t wtot = 0;
+  if (VEC) {
+#pragma unroll
+    for (int k = 0; k < kIter; ++k) {
+      const uint32_t f = (mask >> (4 * k)) & 15u;
+      wtot += popc64(ballot(f & 1u)) + popc64(ballot(f & 2u)) + popc64(ballot(f & 4u)) + popc64(ballot(f & 8u));
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < kIter * 4; ++j) wtot += popc64(ballot((mask >> j) & 1u));
+  }
+  return wtot;
+}
+
+template <bool VEC>
+__device__ __forceinline__ void emit_flagged(uint32_t mask, const float (&v)[kIter * 4], int64_t base, int w, int lane,
+                                             uint2* __restrict__ cand, uint32_t start) {
+  uint32_t running = start;
+  if (VEC) {
+#pragma unroll
+    for (int k = 0; k < kIter; ++k) {
+      const uint32_t f = (mask >> (4 * k)) & 15u;
+      const uint64_t b0 = ballot(f & 1u), b1 = ballot(f & 2u), b2 = ballot(f & 4u), b3 = ballot(f & 8u);
+      uint32_t pos = running + below(b0) + below(b1) + below(b2) + below(b3);
+      const int64_t l0 = comp0<VEC>(base, w, lane, k);
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if ((f >> c) & 1u) cand[pos++] = make_uint2((uint32_t)(l0 + c), fbits(v[k * 4 + c]));
+      running += popc64(b0) + popc64(b1) + popc64(b2) + popc64(b3);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < kIter * 4; ++j) {
+      const bool f = (mask >> j) & 1u;
+      const uint64_t b = ballot(f);
+      if (f) {
+        const int64_t l = comp_index<VEC>(comp0<VEC>(base, w, lane, j >> 2), j & 3);
+        cand[running + below(b)] = make_uint2((uint32_t)l, fbits(v[j]));
+      }
+      running += popc64(b);
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -199,6 +260,189 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// sample: tile t contributes the 256 coordinates of one of its 32 rows (row = hash of t),
+// read by one wavefront as a single 16-byte load per lane.  Epilogue: b_est = bin of the
+// sample's rank ceil(m K/d) + 6 sqrt(m K/d) + 8 from the top, K the largest Top-K size and m
+// the sample size, so that with overwhelming probability at least K coordinates of the full
+// vector lie in bins >= b_est.  scanx checks that and the repair pass covers a miss.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int sample_row(int t) { return (int)(((uint32_t)t * 2654435761u) >> 27); }
+
+template <bool DIFF>
+__global__ __launch_bounds__(kBlock) void k_sample(NodeSet ns, PassArgs a) {
+  __shared__ uint32_t hist[kBins0];
+  __shared__ uint32_t lds4[4];
+  __shared__ int s_flag;
+  __shared__ uint32_t s_rank[1], s_bin[1], s_rk[1], s_cnt[1];
+  const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int64_t d = ns.d;
+  const size_t row = (size_t)node * (size_t)d;
+  const float* __restrict__ x = a.x + row;
+  const float* __restrict__ h = a.h + row;
+  for (int b = tid; b < kBins0; b += kBlock) hist[b] = 0;
+  __syncthreads();
+  const int nw = gridDim.x * 4;
+  for (int t0 = blockIdx.x * 4 + w; t0 < ns.tiles; t0 += 4 * nw) {
+    float4 xv[4], hv[4];
+    bool ok[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {           // four tiles in flight per wavefront
+      const int t = t0 + u * nw;
+      const int64_t l0 = (int64_t)t * kTile + sample_row(t) * 256 + lane * 4;
+      ok[u] = t < ns.tiles && l0 < d;
+      if (ok[u]) {
+        xv[u] = *reinterpret_cast<const float4*>(x + l0);
+        if (!DIFF) hv[u] = *reinterpret_cast<const float4*>(h + l0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (ok[u]) {
+        const float v0 = DIFF ? xv[u].x : xv[u].x - hv[u].x, v1 = DIFF ? xv[u].y : xv[u].y - hv[u].y;
+        const float v2 = DIFF ? xv[u].z : xv[u].z - hv[u].z, v3 = DIFF ? xv[u].w : xv[u].w - hv[u].w;
+        atomicAdd(&hist[magkey(v0) >> kShift0], 1u);
+        atomicAdd(&hist[magkey(v1) >> kShift0], 1u);
+        atomicAdd(&hist[magkey(v2) >> kShift0], 1u);
+        atomicAdd(&hist[magkey(v3) >> kShift0], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = ns.shist + (size_t)node * kBins0;
+  for (int b = tid; b < kBins0; b += kBlock) {
+    const uint32_t c = hist[b];
+    if (c) atomicAdd(&gh[b], c);
+  }
+  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+  if (tid == 0) {
+    // sample size: 256 per tile, the last tile's row may be cut by d (d % 4 == 0 here)
+    const int tl = ns.tiles - 1;
+    const int64_t lrow = (int64_t)tl * kTile + sample_row(tl) * 256;
+    const int64_t last = lrow >= d ? 0 : (d - lrow < 256 ? d - lrow : 256);
+    const double m = (double)(ns.tiles - 1) * 256.0 + (double)last;
+    const double mq = m * (double)ns.lv.K[ns.lv.p - 1] / (double)d;
+    double rk = ceil(mq) + 6.0 * sqrt(mq) + 8.0;
+    if (rk > m) rk = m;
+    s_rank[0] = (uint32_t)rk;
+    s_bin[0] = 0; s_rk[0] = 1; s_cnt[0] = 0;
+  }
+  __syncthreads();
+  locate<kBins0>(gh, 1, s_rank, s_bin, s_rk, s_cnt, lds4);
+  if (tid == 0) ns.best[node] = s_bin[0];
+}
+
+// ---------------------------------------------------------------------------
+// scanx: scan fused with the candidate extraction at the estimated cut-off bin
+// (16-byte vector path only)
+// ---------------------------------------------------------------------------
+template <bool DIFF>
+__global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
+  constexpr bool VEC = true;
+  __shared__ uint32_t hist[kBins0];
+  __shared__ double red[4];
+  __shared__ uint32_t lds4[4];
+  __shared__ int s_flag;
+  __shared__ uint32_t s_rank[kMaxLevels], s_bin[kMaxLevels], s_rk[kMaxLevels], s_cnt[kMaxLevels];
+
+  const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int64_t d = ns.d;
+  const size_t row = (size_t)node * (size_t)d;
+  const float* __restrict__ x = a.x + row;
+  const float* __restrict__ h = a.h + row;
+  const float* __restrict__ y = DIFF ? nullptr : a.y + row;
+  float* __restrict__ yc = a.ycopy ? a.ycopy + row : nullptr;
+  uint2* __restrict__ cand = ns.cand + row;
+  const uint32_t best = ns.best[node];
+
+  for (int b = tid; b < kBins0; b += kBlock) hist[b] = 0;
+  __syncthreads();
+
+  double S = 0.0, D = 0.0, El = 0.0;
+  for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
+    const int64_t base = (int64_t)t * kTile;
+    float v[kIter * 4];
+    uint32_t mask = 0;
+#pragma unroll
+    for (int k = 0; k < kIter; ++k) {
+      const int64_t l0 = comp0<VEC>(base, w, lane, k);
+      float xv[4], hv[4], yv[4];
+      load4<VEC>(x, l0, d, xv);
+      if (!DIFF) {
+        load4<VEC>(h, l0, d, hv);
+        load4<VEC>(y, l0, d, yv);
+        if (yc) store4<VEC>(yc, l0, d, xv);
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float vv = DIFF ? xv[c] : xv[c] - hv[c];
+        v[k * 4 + c] = vv;
+        if (l0 < d) {
+          const double dv = (double)vv;
+          const double e = dv * dv;
+          S += e;
+          if (!DIFF) {
+            const double dw = (double)(xv[c] - yv[c]);
+            D = fma(dw, dw, D);
+          }
+          const uint32_t bin = magkey(vv) >> kShift0;
+          atomicAdd(&hist[bin], 1u);
+          if (bin >= best) mask |= 1u << (k * 4 + c);
+          else El += e;
+        }
+      }
+    }
+    const uint32_t wtot = count_flagged<VEC>(mask);
+    const int grp = t * 4 + w;
+    if (lane == 0 && grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = wtot;
+    if (wtot) emit_flagged<VEC>(mask, v, base, w, lane, cand, (uint32_t)grp * kWaveTile);
+  }
+  S = block_sum(S, red);
+  D = block_sum(D, red);
+  El = block_sum(El, red);
+  if (tid == 0) {
+    st_coherent(&ns.partS[(size_t)node * ns.G + blockIdx.x], S);
+    st_coherent(&ns.partD[(size_t)node * ns.G + blockIdx.x], D);
+    st_coherent(&ns.partEb[(size_t)node * ns.G + blockIdx.x], El);
+  }
+  __syncthreads();
+  uint32_t* gh = ns.hist0 + (size_t)node * kBins0;
+  for (int b = tid; b < kBins0; b += kBlock) {
+    const uint32_t c = hist[b];
+    if (c) atomicAdd(&gh[b], c);
+  }
+
+  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+
+  const int p = ns.lv.p;
+  double s = 0.0, dd = 0.0, el = 0.0;
+  for (int b = tid; b < (int)gridDim.x; b += kBlock) {
+    s += ld_coherent(&ns.partS[(size_t)node * ns.G + b]);
+    dd += ld_coherent(&ns.partD[(size_t)node * ns.G + b]);
+    el += ld_coherent(&ns.partEb[(size_t)node * ns.G + b]);
+  }
+  s = block_sum(s, red);
+  dd = block_sum(dd, red);
+  el = block_sum(el, red);
+  if (tid < kMaxLevels) {
+    s_rank[tid] = tid < p ? ns.lv.K[tid] : 0;
+    s_bin[tid] = 0; s_rk[tid] = 1; s_cnt[tid] = 0;
+  }
+  __syncthreads();
+  locate<kBins0>(gh, p, s_rank, s_bin, s_rk, s_cnt, lds4);
+  if (tid < p) {
+    ns.prefix[node * p + tid] = s_bin[tid];
+    ns.rank[node * p + tid] = s_rk[tid];
+  }
+  if (tid == 0) {
+    ns.S[node] = s;
+    ns.D[node] = DIFF ? a.extD[node] : dd;
+    ns.Eb[node] = el;
+    ns.bmin[node] = s_bin[p - 1];                       // true cut-off bin
+    ns.redo[node] = s_bin[p - 1] < best ? 1u : 0u;      // estimate too high: candidates are missing
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1) -> 4 words
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
@@ -235,7 +479,9 @@ __device__ __forceinline__ float quant_one(float v, float a, float s, float c, f
 // ---------------------------------------------------------------------------
 // filter
 // ---------------------------------------------------------------------------
-template <bool DIFF, bool VEC, bool QUANT, int P>
+// REF1: also builds the second-digit histograms (two-pass sequence); without it the kernel is
+// the repair pass of the one-pass sequence and touches only nodes marked in ns.redo.
+template <bool DIFF, bool VEC, bool QUANT, bool REF1, int P>
 __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   extern __shared__ uint32_t ref1[];   // [p][kBins1]
   __shared__ double red[4];
@@ -244,6 +490,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   __shared__ uint32_t s_rank[1], s_bin[1], s_rk[1], s_cnt[1];
 
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  if (!REF1 && ns.redo[node] == 0) return;
   const int64_t d = ns.d;
   const int p = ns.lv.p, nq = ns.lv.nq;
   const size_t row = (size_t)node * (size_t)d;
@@ -251,7 +498,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   const float* __restrict__ h = a.h + row;
   uint2* __restrict__ cand = ns.cand + row;
 
-  for (int b = tid; b < p * kBins1; b += kBlock) ref1[b] = 0;
+  if (REF1)
+    for (int b = tid; b < p * kBins1; b += kBlock) ref1[b] = 0;
   const uint32_t bmin = ns.bmin[node];
   uint32_t pre[P];
 #pragma unroll
@@ -297,11 +545,13 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
           const double dv = (double)vv;
           if (bin >= bmin) {
             mask |= 1u << (k * 4 + c);
+            if (REF1) {
 #pragma unroll
-            for (int s = 0; s < P; ++s) {
-              const bool hit = bin == pre[s];
-              if (ballot(hit) != 0) {          // wave-uniform: skip the LDS instruction when no lane hits
-                if (hit) atomicAdd(&ref1[s * kBins1 + ((key >> kShift1) & (kBins1 - 1))], 1u);
+              for (int s = 0; s < P; ++s) {
+                const bool hit = bin == pre[s];
+                if (ballot(hit) != 0) {          // wave-uniform: skip the LDS instruction when no lane hits
+                  if (hit) atomicAdd(&ref1[s * kBins1 + ((key >> kShift1) & (kBins1 - 1))], 1u);
+                }
               }
             }
           } else {
@@ -330,49 +580,11 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
         }
       }
     }
-    // ---- ordered compaction of the tile's candidates ----
-    uint32_t wtot = 0;
-    if (VEC) {
-#pragma unroll
-      for (int k = 0; k < kIter; ++k) {
-        const uint32_t f = (mask >> (4 * k)) & 15u;
-        wtot += popc64(ballot(f & 1u)) + popc64(ballot(f & 2u)) + popc64(ballot(f & 4u)) + popc64(ballot(f & 8u));
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < kIter * 4; ++j) wtot += popc64(ballot((mask >> j) & 1u));
-    }
-    // one group per wavefront, stored at the group's own fixed offset of the candidate list
+    // ---- ordered extraction: one group per wavefront, at the group's own fixed offset ----
+    const uint32_t wtot = count_flagged<VEC>(mask);
     const int grp = t * 4 + w;
-    const uint32_t start = (uint32_t)grp * kWaveTile;
     if (lane == 0 && grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = wtot;
-    if (wtot) {
-      uint32_t running = start;
-      if (VEC) {
-#pragma unroll
-        for (int k = 0; k < kIter; ++k) {
-          const uint32_t f = (mask >> (4 * k)) & 15u;
-          const uint64_t b0 = ballot(f & 1u), b1 = ballot(f & 2u), b2 = ballot(f & 4u), b3 = ballot(f & 8u);
-          uint32_t pos = running + below(b0) + below(b1) + below(b2) + below(b3);
-          const int64_t l0 = comp0<VEC>(base, w, lane, k);
-#pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if ((f >> c) & 1u) cand[pos++] = make_uint2((uint32_t)(l0 + c), fbits(v[k * 4 + c]));
-          running += popc64(b0) + popc64(b1) + popc64(b2) + popc64(b3);
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < kIter * 4; ++j) {
-          const bool f = (mask >> j) & 1u;
-          const uint64_t b = ballot(f);
-          if (f) {
-            const int64_t l = comp_index<VEC>(comp0<VEC>(base, w, lane, j >> 2), j & 3);
-            cand[running + below(b)] = make_uint2((uint32_t)l, fbits(v[j]));
-          }
-          running += popc64(b);
-        }
-      }
-    }
+    if (wtot) emit_flagged<VEC>(mask, v, base, w, lane, cand, (uint32_t)grp * kWaveTile);
   }
 
   Eb = block_sum(Eb, red);
@@ -388,9 +600,11 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   }
   __syncthreads();
   uint32_t* gref = ns.ref1 + (size_t)node * p * kBins1;
-  for (int b = tid; b < p * kBins1; b += kBlock) {
-    const uint32_t c = ref1[b];
-    if (c) atomicAdd(&gref[b], c);
+  if (REF1) {
+    for (int b = tid; b < p * kBins1; b += kBlock) {
+      const uint32_t c = ref1[b];
+      if (c) atomicAdd(&gref[b], c);
+    }
   }
 
   if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
@@ -410,6 +624,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
     }
     if (tid == 0) ns.qscale[node] = 0.f;
   }
+  if (!REF1) return;
   for (int s = 0; s < p; ++s) {
     if (tid == 0) {
       s_rank[0] = ns.rank[node * p + s];
@@ -426,11 +641,16 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// refine: third digit over the candidate lists (one wavefront per tile group)
+// refine: next digit of every slot's threshold over the candidate lists (one wavefront per
+// group at a time).  STAGE 1: second digit (10 bits below the 12-bit bin), used by the
+// one-pass sequence; STAGE 2: last digit (9 bits), after which T_s is exact.
 // ---------------------------------------------------------------------------
-template <int P>
+template <int P, int STAGE>
 __global__ __launch_bounds__(kBlock) void k_refine(NodeSet ns) {
-  extern __shared__ uint32_t ref2[];   // [p][kBins2]
+  constexpr int NB = STAGE == 1 ? kBins1 : kBins2;
+  constexpr int SHIFT_HI = STAGE == 1 ? kShift0 : kShift1;   // bits above this digit
+  constexpr int SHIFT_LO = STAGE == 1 ? kShift1 : 0;
+  extern __shared__ uint32_t ref[];   // [p][NB]
   __shared__ uint32_t lds4[4];
   __shared__ int s_flag;
   __shared__ uint32_t s_rank[1], s_bin[1], s_rk[1], s_cnt[1];
@@ -438,7 +658,7 @@ __global__ __launch_bounds__(kBlock) void k_refine(NodeSet ns) {
   const int p = ns.lv.p;
   const size_t row = (size_t)node * (size_t)ns.d;
   const uint2* __restrict__ cand = ns.cand + row;
-  for (int b = tid; b < p * kBins2; b += kBlock) ref2[b] = 0;
+  for (int b = tid; b < p * NB; b += kBlock) ref[b] = 0;
   uint32_t pre[P];
 #pragma unroll
   for (int s = 0; s < P; ++s) pre[s] = s < p ? ns.prefix[node * p + s] : 0xFFFFFFFFu;
@@ -450,20 +670,20 @@ __global__ __launch_bounds__(kBlock) void k_refine(NodeSet ns) {
       const uint32_t e = e0 + lane;
       const bool valid = e < cnt;
       const uint32_t key = valid ? (cand[start + e].y & 0x7FFFFFFFu) : 0u;
-      const uint32_t hi = key >> kShift1;
+      const uint32_t hi = key >> SHIFT_HI;
 #pragma unroll
       for (int s = 0; s < P; ++s) {
         const bool hit = valid && hi == pre[s];
         if (ballot(hit) != 0) {
-          if (hit) atomicAdd(&ref2[s * kBins2 + (key & (kBins2 - 1))], 1u);
+          if (hit) atomicAdd(&ref[s * NB + ((key >> SHIFT_LO) & (NB - 1))], 1u);
         }
       }
     }
   }
   __syncthreads();
-  uint32_t* gref = ns.ref2 + (size_t)node * p * kBins2;
-  for (int b = tid; b < p * kBins2; b += kBlock) {
-    const uint32_t c = ref2[b];
+  uint32_t* gref = (STAGE == 1 ? ns.ref1 : ns.ref2) + (size_t)node * p * NB;
+  for (int b = tid; b < p * NB; b += kBlock) {
+    const uint32_t c = ref[b];
     if (c) atomicAdd(&gref[b], c);
   }
   if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
@@ -473,11 +693,11 @@ __global__ __launch_bounds__(kBlock) void k_refine(NodeSet ns) {
       s_bin[0] = 0; s_rk[0] = 1; s_cnt[0] = 0;
     }
     __syncthreads();
-    locate<kBins2>(gref + (size_t)s * kBins2, 1, s_rank, s_bin, s_rk, s_cnt, lds4);
+    locate<NB>(gref + (size_t)s * NB, 1, s_rank, s_bin, s_rk, s_cnt, lds4);
     if (tid == 0) {
-      ns.prefix[node * p + s] = (ns.prefix[node * p + s] << 9) | s_bin[0];   // exact threshold key T_s
-      ns.rank[node * p + s] = s_rk[0];                                       // ties to take
-      ns.eqcnt[node * p + s] = s_cnt[0];                                     // keys equal to T_s
+      ns.prefix[node * p + s] = (ns.prefix[node * p + s] << (STAGE == 1 ? 10 : 9)) | s_bin[0];
+      ns.rank[node * p + s] = s_rk[0];       // after stage 2: ties to take
+      ns.eqcnt[node * p + s] = s_cnt[0];     // after stage 2: keys equal to the exact threshold T_s
     }
     __syncthreads();
   }
@@ -790,19 +1010,20 @@ hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <bool DIFF, bool VEC, int P>
+template <bool DIFF, bool VEC, bool REF1, int P>
 static void launch_filter_p(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   const dim3 grid(ns.G, ns.nn), block(kBlock);
-  const size_t lds = (size_t)ns.lv.p * kBins1 * sizeof(uint32_t);
-  if (ns.lv.nq > 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, true, P>), grid, block, lds, st, ns, a);
-  else hipLaunchKernelGGL((k_filter<DIFF, VEC, false, P>), grid, block, lds, st, ns, a);
+  const size_t lds = REF1 ? (size_t)ns.lv.p * kBins1 * sizeof(uint32_t) : 0;
+  if (ns.lv.nq > 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, true, REF1, P>), grid, block, lds, st, ns, a);
+  else hipLaunchKernelGGL((k_filter<DIFF, VEC, false, REF1, P>), grid, block, lds, st, ns, a);
 }
 
 template <bool DIFF, bool VEC>
 static void launch_filter_q(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
-  if (ns.lv.p <= 4) launch_filter_p<DIFF, VEC, 4>(ns, a, st);
-  else if (ns.lv.p <= 8) launch_filter_p<DIFF, VEC, 8>(ns, a, st);
-  else launch_filter_p<DIFF, VEC, 16>(ns, a, st);
+  if (ns.onepass) launch_filter_p<DIFF, VEC, false, 4>(ns, a, st);
+  else if (ns.lv.p <= 4) launch_filter_p<DIFF, VEC, true, 4>(ns, a, st);
+  else if (ns.lv.p <= 8) launch_filter_p<DIFF, VEC, true, 8>(ns, a, st);
+  else launch_filter_p<DIFF, VEC, true, 16>(ns, a, st);
 }
 
 hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
@@ -818,16 +1039,36 @@ hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_refine(const NodeSet& ns, hipStream_t st) {
-  (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
-  if (ns.lv.p == 0) return hipSuccess;
-  const dim3 grid(ns.G2, ns.nn), block(kBlock);
-  const size_t lds = (size_t)ns.lv.p * kBins2 * sizeof(uint32_t);
-  if (ns.lv.p <= 4) hipLaunchKernelGGL((k_refine<4>), grid, block, lds, st, ns);
-  else if (ns.lv.p <= 8) hipLaunchKernelGGL((k_refine<8>), grid, block, lds, st, ns);
-  else hipLaunchKernelGGL((k_refine<16>), grid, block, lds, st, ns);
+hipError_t launch_sample(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+  (void)hipGetLastError();
+  const dim3 grid(ns.GS, ns.nn), block(kBlock);
+  if (a.diff) hipLaunchKernelGGL((k_sample<true>), grid, block, 0, st, ns, a);
+  else hipLaunchKernelGGL((k_sample<false>), grid, block, 0, st, ns, a);
   return hipGetLastError();
 }
+
+hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+  (void)hipGetLastError();
+  const dim3 grid(ns.G, ns.nn), block(kBlock);
+  if (a.diff) hipLaunchKernelGGL((k_scanx<true>), grid, block, 0, st, ns, a);
+  else hipLaunchKernelGGL((k_scanx<false>), grid, block, 0, st, ns, a);
+  return hipGetLastError();
+}
+
+template <int STAGE>
+static hipError_t launch_refine_stage(const NodeSet& ns, hipStream_t st) {
+  (void)hipGetLastError();
+  if (ns.lv.p == 0) return hipSuccess;
+  const dim3 grid(ns.G2, ns.nn), block(kBlock);
+  const size_t lds = (size_t)ns.lv.p * (STAGE == 1 ? kBins1 : kBins2) * sizeof(uint32_t);
+  if (ns.lv.p <= 4) hipLaunchKernelGGL((k_refine<4, STAGE>), grid, block, lds, st, ns);
+  else if (ns.lv.p <= 8) hipLaunchKernelGGL((k_refine<8, STAGE>), grid, block, lds, st, ns);
+  else hipLaunchKernelGGL((k_refine<16, STAGE>), grid, block, lds, st, ns);
+  return hipGetLastError();
+}
+
+hipError_t launch_refine1(const NodeSet& ns, hipStream_t st) { return launch_refine_stage<1>(ns, st); }
+hipError_t launch_refine(const NodeSet& ns, hipStream_t st) { return launch_refine_stage<2>(ns, st); }
 
 hipError_t launch_tally(const NodeSet& ns, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread

@@ -19,15 +19,16 @@ LIB_PATH = os.path.join(HERE, "libadacgd.so")
 TOPK, QUANT = 0, 1
 GRAD_LOGISTIC, GRAD_EXTERNAL, DIFF_EXTERNAL = 0, 1, 2
 INIT_FULLGRAD, INIT_ZERO = 0, 1
-FLAG_ANY_LEVEL_ORDER, FLAG_RETAIN_EXT, FLAG_KERNEL_TIMING = 1, 2, 4
+FLAG_ANY_LEVEL_ORDER, FLAG_RETAIN_EXT, FLAG_KERNEL_TIMING, FLAG_TWO_PASS = 1, 2, 4, 8
 MAX_LEVELS = 16
 
 (F_X, F_G, F_GTILDE, F_GTILDE_PREV, F_GI, F_PREV_GRAD, F_LEVEL, F_SQNORM, F_D, F_ERR, F_MSG_COUNT, F_MSG_IDX,
  F_MSG_VAL, F_M_LEVEL, F_M_SQNORM, F_M_D, F_M_ERR, F_M_MSG_COUNT, F_M_MSG_IDX, F_M_MSG_VAL, F_STEP, F_LEVEL_HIST,
  F_M_LEVEL_HIST, F_COMM, F_QCODES, F_QSCALE, F_KERNEL_MS, F_GRAD) = range(28)
 
-KERNELS = ["xupdate", "grad_margin", "grad_cols", "w_scan", "w_filter", "w_refine", "w_tally", "w_compact",
-           "w_qapply", "aggregate", "m_scan", "m_filter", "m_refine", "m_tally", "m_compact", "m_qapply"]
+KERNELS = ["xupdate", "grad_margin", "grad_cols", "aggregate",
+           "w_sample", "w_scan", "w_filter", "w_refine1", "w_refine2", "w_tally", "w_compact", "w_qapply",
+           "m_sample", "m_scan", "m_filter", "m_refine1", "m_refine2", "m_tally", "m_compact", "m_qapply"]
 
 EXPORTS = ["adacgd_workspace_bytes", "adacgd_init", "adacgd_step", "adacgd_state", "adacgd_destroy",
            "adacgd_last_error"]

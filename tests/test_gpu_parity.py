@@ -376,3 +376,42 @@ def test_trajectory_with_oracle_gradients_is_bit_exact():
     assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
     assert (orc.level_hist_w > 0).sum() >= 3
     eng.close()
+
+
+def _sampled_row(t):
+    """Row (of 32 rows of 256 coordinates) of tile t that the one-pass selection samples."""
+    return ((t * 2654435761) & 0xFFFFFFFF) >> 27
+
+
+@pytest.mark.parametrize("kind", ["normal", "heavy", "ties", "adversarial", "two_pass_flag"])
+def test_long_vectors_one_pass_selection_bit_exact(kind):
+    """Vectors long enough for the sampled one-pass selection (>= 128 tiles of 8192).  The
+    'adversarial' input puts all large magnitudes exactly on the sampled rows, so the sampled
+    cut-off estimate is far too high and the repair pass must produce the same exact result."""
+    E = _eng()
+    n, d = 2, 130 * 8192 + 1284
+    rng = np.random.default_rng(77)
+    wl = [(O.TOPK, 50), (O.TOPK, 3000), (O.TOPK, d // 20)]
+    ml = [(O.TOPK, d // 100)]
+    steps = 3
+    base_kind = {"adversarial": "normal", "two_pass_flag": "normal"}.get(kind, kind)
+    grads = [make_vectors(rng, n, d, base_kind) for _ in range(steps + 1)]
+    if kind == "adversarial":
+        for g in grads[1:]:
+            for t in range((d + 8191) // 8192):
+                lo = t * 8192 + _sampled_row(t) * 256
+                g[:, lo:min(d, lo + 256)] *= np.float32(1000.0)
+    for t in range(1, steps + 1):
+        grads[t] = (grads[t - 1] * np.float32(0.5) + grads[t]).astype(np.float32)
+    x0 = np.zeros(d, dtype=np.float32)
+    zeta = 0.3
+    orc = O.AdaCGDOracle(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zeta, master_levels=ml, zeta_master=0.0)
+    orc.init(x0, grads[0], O.INIT_FULLGRAD)
+    eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zeta, master_levels=ml, zeta_master=0.0,
+                   grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=_cuda(grads[0]),
+                   flags=E.FLAG_TWO_PASS if kind == "two_pass_flag" else 0)
+    for t in range(1, steps + 1):
+        res, rm = orc.step(grads=grads[t])
+        eng.step(_cuda(grads[t]))
+        compare_step(eng, orc, res, rm, ("long", kind, t))
+    eng.close()
