@@ -95,7 +95,7 @@ def main():
     # (12 B per worker-coordinate) plus the message (8 B) and estimator write (4 B) per sent entry
     sent = sum(int(hist_ev[j]) * wk.worker_levels[j - 1][1] for j in range(1, len(hist_ev)))
     alg_bytes_step = 12.0 * n * d + 12.0 * sent / args.steps
-    group = ["w_sample", "w_scan", "w_filter", "w_refine1", "w_refine2", "w_tally", "w_compact"]
+    group = ["w_sample", "w_scan", "w_filter", "w_gather", "w_select", "w_tally", "w_compact"]
     per_kernel = {}
     for k, (ms, cnt) in kms.items():
         if cnt:

@@ -178,16 +178,16 @@ enum adacgd_kernel {
   ADACGD_K_W_SAMPLE = 4,   /* histogram of a 1/32 sample: candidate cut-off estimate          */
   ADACGD_K_W_SCAN = 5,     /* differences, norms, first-digit histogram (+ candidates)        */
   ADACGD_K_W_FILTER = 6,   /* candidate extraction, low-band energy, quantiser errors         */
-  ADACGD_K_W_REFINE1 = 7,  /* second digit of the thresholds                                  */
-  ADACGD_K_W_REFINE2 = 8,  /* last digit: exact thresholds                                    */
+  ADACGD_K_W_GATHER = 7,   /* keys inside the threshold bins -> one list per worker           */
+  ADACGD_K_W_SELECT = 8,   /* remaining digits: exact thresholds                              */
   ADACGD_K_W_TALLY = 9,    /* band energies, level choice                                     */
   ADACGD_K_W_COMPACT = 10, /* message + estimator update                                      */
   ADACGD_K_W_QAPPLY = 11,  /* dense estimator update of quantised levels                      */
   ADACGD_K_M_SAMPLE = 12,
   ADACGD_K_M_SCAN = 13,
   ADACGD_K_M_FILTER = 14,
-  ADACGD_K_M_REFINE1 = 15,
-  ADACGD_K_M_REFINE2 = 16,
+  ADACGD_K_M_GATHER = 15,
+  ADACGD_K_M_SELECT = 16,
   ADACGD_K_M_TALLY = 17,
   ADACGD_K_M_COMPACT = 18,
   ADACGD_K_M_QAPPLY = 19,

@@ -78,18 +78,35 @@ __device__ __forceinline__ void st_coherent(T* p, T v) {
 // Every block of a node calls this once after its last coherent write.  Returns true in
 // all threads of exactly one block per node: the one that arrived last.  That block may
 // then read what the others wrote (with ld_coherent) and finish the node's work; the
-// counter is back at zero when it returns.  No block ever waits for another.
+// counters are back at zero when it returns.  No block ever waits for another.
 // Ordering: each wave first waits until its own vector stores and atomics have completed
 // (vmcnt reaches 0), the block barrier extends that to the whole block, and only then is
 // the arrival counted.
-__device__ __forceinline__ bool arrive_last(uint32_t* counter, uint32_t nblocks, int* lds_flag) {
+// Arrivals are counted in two levels (kArriveFan first-level counters per node, then one
+// second-level counter) because a few thousand read-modify-writes on one address -- or on
+// one cache line -- take ~12 ns each, one after the other.  `counters` points at the node's
+// kArriveFan + 1 counters, one per kCounterStride words (= one per 64-byte line).
+constexpr int kArriveFan = 32;
+constexpr int kCounterStride = 16;
+
+__device__ __forceinline__ bool arrive_last(uint32_t* counters, uint32_t nblocks, int* lds_flag) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (threadIdx.x == 0) {
-    uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    int last = (prev == nblocks - 1);
-    if (last) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t sub = blockIdx.x % kArriveFan;
+    const uint32_t nsub = (nblocks - sub + kArriveFan - 1) / kArriveFan;     // blocks sharing this counter
+    const uint32_t nfan = nblocks < (uint32_t)kArriveFan ? nblocks : (uint32_t)kArriveFan;
+    int last = 0;
+    uint32_t prev = __hip_atomic_fetch_add(&counters[(1 + sub) * kCounterStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (prev == nsub - 1) {
+      __hip_atomic_store(&counters[(1 + sub) * kCounterStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      prev = __hip_atomic_fetch_add(&counters[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (prev == nfan - 1) {
+        __hip_atomic_store(&counters[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = 1;
+      }
+    }
     *lds_flag = last;
   }
   __syncthreads();

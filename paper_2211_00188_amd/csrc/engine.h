@@ -50,8 +50,8 @@ struct NodeSet {
   LevelTable lv;
 
   uint32_t* hist0;      // [nn][kBins0]           first-digit counts; zero between launches
-  uint32_t* ref1;       // [nn][p][kBins1]        second-digit counts inside each slot's bin
-  uint32_t* ref2;       // [nn][p][kBins2]        third digit
+  uint32_t* gcur;       // [nn]                   keys gathered so far; zero between steps
+  uint32_t* glist;      // [nn][d]                keys of the candidates inside the slots' first-digit bins
   uint32_t* prefix;     // [nn][p]                known high bits of slot threshold T_s (12, 22, 31 bits)
   uint32_t* rank;       // [nn][p]                rank of the K_s-th element inside the prefix
   uint32_t* eqcnt;      // [nn][p]                count of keys equal to T_s
@@ -59,7 +59,7 @@ struct NodeSet {
   uint32_t* shist;      // [nn][kBins0]           first-digit counts of the sample; zero between launches
   uint32_t* best;       // [nn]                   estimated cut-off bin from the sample
   uint32_t* redo;       // [nn]                   1 = estimate was too high, the repair pass must run
-  uint32_t* done;       // [nn]                   arrival counter of the last-block epilogues
+  uint32_t* done;       // [nn][kArriveFan+1]     arrival counters of the last-block epilogues
   uint32_t* kmax;       // [nn]                   running max magnitude key of the current scan; zero between launches
   uint32_t* amax;       // [nn]                   max magnitude key of the last scan (quantiser scale a)
   double* partS;        // [nn][G]
@@ -79,7 +79,7 @@ struct NodeSet {
   uint32_t* blk_eq;     // [nn][p][G2]  per tally block: candidates with key == T_s
   uint32_t* blk_out;    // [nn][G2]     message offset of the block's first group, chosen level
   uint32_t* blk_eqb;    // [nn][G2]     ties before the block's first group, chosen level
-  uint32_t* tile_off;   // [nn][tiles+1] message offset of each tile's first entry (last = total)
+  uint32_t* grp_off;    // [nn][groups+1] message offset of each group's first entry (last = total)
   uint2* cand;          // [nn][d]  (coordinate, value bits); group g starts at g * kWaveTile
   int32_t* level;       // [nn]   0 = skip
   int32_t* sel_slot;    // [nn]   slot of the chosen Top-K level, -1 otherwise
@@ -123,8 +123,8 @@ struct LogisticData {
 // launchers (each enqueues on the stream and returns the launch status)
 hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st);
-hipError_t launch_refine(const NodeSet& ns, hipStream_t st);
-hipError_t launch_refine1(const NodeSet& ns, hipStream_t st);
+hipError_t launch_gather(const NodeSet& ns, hipStream_t st);
+hipError_t launch_select(const NodeSet& ns, hipStream_t st);
 hipError_t launch_sample(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_tally(const NodeSet& ns, hipStream_t st);

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "../../include/adacgd.h"
+#include "devutil.h"
 #include "engine.h"
 
 using namespace adacgd;
@@ -108,10 +109,9 @@ int build_levels(const adacgd_level* in, int m, float zeta, int64_t d, uint32_t 
 void carve_nodeset(Carver& c, NodeSet& ns) {
   const size_t nn = ns.nn, p = ns.lv.p, nq = ns.lv.nq, m = ns.lv.m, tiles = ns.groups;
   ns.hist0 = c.take<uint32_t>(nn * kBins0);
-  ns.ref1 = c.take<uint32_t>(nn * p * kBins1);
-  ns.ref2 = c.take<uint32_t>(nn * p * kBins2);
+  ns.gcur = c.take<uint32_t>(nn * 64);   // one cursor per 256 bytes
   ns.shist = c.take<uint32_t>(ns.onepass ? nn * kBins0 : 0);
-  ns.done = c.take<uint32_t>(nn);
+  ns.done = c.take<uint32_t>(nn * (kArriveFan + 1) * kCounterStride);
   ns.kmax = c.take<uint32_t>(nn);
   ns.level_hist = c.take<unsigned long long>(m + 1);
   // everything up to here must start at zero
@@ -139,8 +139,9 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.blk_eq = c.take<uint32_t>(nn * p * ns.G2);
   ns.blk_out = c.take<uint32_t>(nn * ns.G2);
   ns.blk_eqb = c.take<uint32_t>(nn * ns.G2);
-  ns.tile_off = c.take<uint32_t>(nn * ((size_t)ns.tiles + 1));
+  ns.grp_off = c.take<uint32_t>(nn * (tiles + 1));
   ns.cand = p ? c.take<uint2>(nn * (size_t)ns.d) : nullptr;
+  ns.glist = p ? c.take<uint32_t>(nn * (size_t)ns.d) : nullptr;
   ns.level = c.take<int32_t>(nn);
   ns.sel_slot = c.take<int32_t>(nn);
   ns.sel_q = c.take<int32_t>(nn);
@@ -157,13 +158,15 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
   ns.nn = nn;
   ns.d = d;
   ns.tiles = (int)((d + kTile - 1) / kTile);
-  const int want = (2560 + nn - 1) / nn;
+  int want = (2560 + nn - 1) / nn;               // streaming kernels: about 2560 blocks in all,
+  if (want > 640) want = 640;                    // at most 640 per node (each block flushes a histogram)
   ns.G = ns.tiles < want ? ns.tiles : want;
   if (ns.G < 1) ns.G = 1;
   ns.groups = (int)((d + kWaveTile - 1) / kWaveTile);
   // candidate kernels: about 2048 blocks in all, each owning a contiguous range of groups
   int g2 = (ns.groups + 3) / 4;
-  const int want2 = (2048 + nn - 1) / nn;
+  int want2 = (2048 + nn - 1) / nn;
+  if (want2 > 512) want2 = 512;
   if (g2 > want2) g2 = want2;
   const int gb = (ns.groups + g2 - 1) / g2;
   ns.G2 = (ns.groups + gb - 1) / gb;
@@ -172,7 +175,7 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
   // 1/32 sample to be informative, and a candidate set that is a minor part of the vector.
   ns.onepass = (!force_two_pass && ns.lv.nq == 0 && ns.lv.p > 0 && d % 4 == 0 && ns.tiles >= 128 &&
                 4 * (int64_t)ns.Kcap <= d) ? 1 : 0;
-  const int wants = (512 + nn - 1) / nn;         // sample kernel: about 512 blocks in all
+  const int wants = (1024 + nn - 1) / nn;        // sample kernel: about 1024 blocks in all
   const int smax = (ns.tiles + 15) / 16;         // at least 4 rounds of 4 tiles per wavefront
   ns.GS = wants < smax ? wants : smax;
   if (ns.GS < 1) ns.GS = 1;
@@ -354,12 +357,12 @@ int compress(adacgd_ctx* c, NodeSet& ns, const PassArgs& a, int slot0) {
     if ((rc = timed(c, slot0 + 0, [&] { return launch_sample(ns, a, c->st); }))) return rc;
     if ((rc = timed(c, slot0 + 1, [&] { return launch_scanx(ns, a, c->st); }))) return rc;
     if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->st); }))) return rc;   // repair, usually idle
-    if ((rc = timed(c, slot0 + 3, [&] { return launch_refine1(ns, c->st); }))) return rc;
   } else {
     if ((rc = timed(c, slot0 + 1, [&] { return launch_scan(ns, a, c->st); }))) return rc;
     if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->st); }))) return rc;
   }
-  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 4, [&] { return launch_refine(ns, c->st); }))) return rc;
+  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 3, [&] { return launch_gather(ns, c->st); }))) return rc;
+  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 4, [&] { return launch_select(ns, c->st); }))) return rc;
   if ((rc = timed(c, slot0 + 5, [&] { return launch_tally(ns, c->st); }))) return rc;
   if (ns.lv.p > 0 && (rc = timed(c, slot0 + 6, [&] { return launch_compact(ns, a, c->st); }))) return rc;
   if (ns.lv.nq > 0 && (rc = timed(c, slot0 + 7, [&] { return launch_qapply(ns, a, c->st); }))) return rc;

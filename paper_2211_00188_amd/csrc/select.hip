@@ -108,50 +108,29 @@ __device__ void locate(uint32_t* hist, int nr, const uint32_t* rank, uint32_t* o
 }
 
 // ---------------------------------------------------------------------------
-// ordered extraction of one wavefront's flagged elements of a tile (bit j of mask <->
-// iteration j/4, component j%4) into its group's slot of the candidate list
+// ordered extraction: the wavefront appends the flagged components of one iteration (4 per
+// lane, flag bit c <-> component c) to its group's slot of the candidate list, keeping
+// coordinate order.  `running` is the number of candidates the group holds so far.
+// Must be called by all 64 lanes.
 // ---------------------------------------------------------------------------
 template <bool VEC>
-__device__ __forceinline__ uint32_t count_flagged(uint32_t mask) {
-  uint32_t wtot = 0;
-  if (VEC) {
-#pragma unroll
-    for (int k = 0; k < kIter; ++k) {
-      const uint32_t f = (mask >> (4 * k)) & 15u;
-      wtot += popc64(ballot(f & 1u)) + popc64(ballot(f & 2u)) + popc64(ballot(f & 4u)) + popc64(ballot(f & 8u));
-    }
-  } else {
-#pragma unroll
-    for (int j = 0; j < kIter * 4; ++j) wtot += popc64(ballot((mask >> j) & 1u));
-  }
-  return wtot;
-}
-
-template <bool VEC>
-__device__ __forceinline__ void emit_flagged(uint32_t mask, const float (&v)[kIter * 4], int64_t base, int w, int lane,
-                                             uint2* __restrict__ cand, uint32_t start) {
-  uint32_t running = start;
-  if (VEC) {
-#pragma unroll
-    for (int k = 0; k < kIter; ++k) {
-      const uint32_t f = (mask >> (4 * k)) & 15u;
-      const uint64_t b0 = ballot(f & 1u), b1 = ballot(f & 2u), b2 = ballot(f & 4u), b3 = ballot(f & 8u);
+__device__ __forceinline__ void emit4(uint32_t f, const float (&vv)[4], int64_t l0, uint2* __restrict__ slot,
+                                      uint32_t& running) {
+  if (VEC) {      // order: lane, then component
+    const uint64_t b0 = ballot(f & 1u), b1 = ballot(f & 2u), b2 = ballot(f & 4u), b3 = ballot(f & 8u);
+    if ((b0 | b1 | b2 | b3) != 0) {
       uint32_t pos = running + below(b0) + below(b1) + below(b2) + below(b3);
-      const int64_t l0 = comp0<VEC>(base, w, lane, k);
 #pragma unroll
       for (int c = 0; c < 4; ++c)
-        if ((f >> c) & 1u) cand[pos++] = make_uint2((uint32_t)(l0 + c), fbits(v[k * 4 + c]));
+        if ((f >> c) & 1u) slot[pos++] = make_uint2((uint32_t)(l0 + c), fbits(vv[c]));
       running += popc64(b0) + popc64(b1) + popc64(b2) + popc64(b3);
     }
-  } else {
+  } else {        // order: component, then lane
 #pragma unroll
-    for (int j = 0; j < kIter * 4; ++j) {
-      const bool f = (mask >> j) & 1u;
-      const uint64_t b = ballot(f);
-      if (f) {
-        const int64_t l = comp_index<VEC>(comp0<VEC>(base, w, lane, j >> 2), j & 3);
-        cand[running + below(b)] = make_uint2((uint32_t)l, fbits(v[j]));
-      }
+    for (int c = 0; c < 4; ++c) {
+      const bool fc = (f >> c) & 1u;
+      const uint64_t b = ballot(fc);
+      if (fc) slot[running + below(b)] = make_uint2((uint32_t)(l0 + 64 * c), fbits(vv[c]));
       running += popc64(b);
     }
   }
@@ -227,7 +206,7 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
     if (c) atomicAdd(&gh[b], c);
   }
 
-  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+  if (!arrive_last(&ns.done[(size_t)node * (kArriveFan + 1) * kCounterStride], gridDim.x, &s_flag)) return;
 
   // ---- epilogue: one block per node ----
   const int p = ns.lv.p;
@@ -313,7 +292,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(NodeSet ns, PassArgs a) {
     const uint32_t c = hist[b];
     if (c) atomicAdd(&gh[b], c);
   }
-  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+  if (!arrive_last(&ns.done[(size_t)node * (kArriveFan + 1) * kCounterStride], gridDim.x, &s_flag)) return;
   if (tid == 0) {
     // sample size: 256 per tile, the last tile's row may be cut by d (d % 4 == 0 here)
     const int tl = ns.tiles - 1;
@@ -360,41 +339,40 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
   double S = 0.0, D = 0.0, El = 0.0;
   for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
     const int64_t base = (int64_t)t * kTile;
-    float v[kIter * 4];
-    uint32_t mask = 0;
+    const int grp = t * 4 + w;
+    uint2* __restrict__ slot = cand + (size_t)grp * kWaveTile;
+    uint32_t running = 0;
 #pragma unroll
     for (int k = 0; k < kIter; ++k) {
       const int64_t l0 = comp0<VEC>(base, w, lane, k);
-      float xv[4], hv[4], yv[4];
+      float xv[4], hv[4], yv[4], vv[4];
       load4<VEC>(x, l0, d, xv);
       if (!DIFF) {
         load4<VEC>(h, l0, d, hv);
         load4<VEC>(y, l0, d, yv);
         if (yc) store4<VEC>(yc, l0, d, xv);
       }
+      uint32_t f = 0;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const float vv = DIFF ? xv[c] : xv[c] - hv[c];
-        v[k * 4 + c] = vv;
+        vv[c] = DIFF ? xv[c] : xv[c] - hv[c];
         if (l0 < d) {
-          const double dv = (double)vv;
+          const double dv = (double)vv[c];
           const double e = dv * dv;
           S += e;
           if (!DIFF) {
             const double dw = (double)(xv[c] - yv[c]);
             D = fma(dw, dw, D);
           }
-          const uint32_t bin = magkey(vv) >> kShift0;
+          const uint32_t bin = magkey(vv[c]) >> kShift0;
           atomicAdd(&hist[bin], 1u);
-          if (bin >= best) mask |= 1u << (k * 4 + c);
+          if (bin >= best) f |= 1u << c;
           else El += e;
         }
       }
+      emit4<VEC>(f, vv, l0, slot, running);
     }
-    const uint32_t wtot = count_flagged<VEC>(mask);
-    const int grp = t * 4 + w;
-    if (lane == 0 && grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = wtot;
-    if (wtot) emit_flagged<VEC>(mask, v, base, w, lane, cand, (uint32_t)grp * kWaveTile);
+    if (lane == 0 && grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = running;
   }
   S = block_sum(S, red);
   D = block_sum(D, red);
@@ -411,7 +389,7 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
     if (c) atomicAdd(&gh[b], c);
   }
 
-  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+  if (!arrive_last(&ns.done[(size_t)node * (kArriveFan + 1) * kCounterStride], gridDim.x, &s_flag)) return;
 
   const int p = ns.lv.p;
   double s = 0.0, dd = 0.0, el = 0.0;
@@ -479,32 +457,23 @@ __device__ __forceinline__ float quant_one(float v, float a, float s, float c, f
 // ---------------------------------------------------------------------------
 // filter
 // ---------------------------------------------------------------------------
-// REF1: also builds the second-digit histograms (two-pass sequence); without it the kernel is
-// the repair pass of the one-pass sequence and touches only nodes marked in ns.redo.
-template <bool DIFF, bool VEC, bool QUANT, bool REF1, int P>
+// REPAIR: the kernel is the repair pass of the one-pass sequence and touches only nodes
+// marked in ns.redo.
+template <bool DIFF, bool VEC, bool QUANT, bool REPAIR>
 __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
-  extern __shared__ uint32_t ref1[];   // [p][kBins1]
   __shared__ double red[4];
-  __shared__ uint32_t lds4[4];
   __shared__ int s_flag;
-  __shared__ uint32_t s_rank[1], s_bin[1], s_rk[1], s_cnt[1];
 
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-  if (!REF1 && ns.redo[node] == 0) return;
+  if (REPAIR && ns.redo[node] == 0) return;
   const int64_t d = ns.d;
-  const int p = ns.lv.p, nq = ns.lv.nq;
+  const int nq = ns.lv.nq;
   const size_t row = (size_t)node * (size_t)d;
   const float* __restrict__ x = a.x + row;
   const float* __restrict__ h = a.h + row;
   uint2* __restrict__ cand = ns.cand + row;
 
-  if (REF1)
-    for (int b = tid; b < p * kBins1; b += kBlock) ref1[b] = 0;
   const uint32_t bmin = ns.bmin[node];
-  uint32_t pre[P];
-#pragma unroll
-  for (int s = 0; s < P; ++s) pre[s] = s < p ? ns.prefix[node * p + s] : 0xFFFFFFFFu;
-  __syncthreads();
 
   // quantiser constants of this node
   float qa = 0.f;
@@ -524,36 +493,28 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   double Eb = 0.0;
   for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
     const int64_t base = (int64_t)t * kTile;
-    float v[kIter * 4];
-    uint32_t mask = 0;
+    const int grp = t * 4 + w;
+    uint2* __restrict__ slot = cand + (size_t)grp * kWaveTile;
+    uint32_t running = 0;
 #pragma unroll
     for (int k = 0; k < kIter; ++k) {
       const int64_t l0 = comp0<VEC>(base, w, lane, k);
-      float xv[4], hv[4];
+      float xv[4], hv[4], vv[4];
       load4<VEC>(x, l0, d, xv);
       if (!DIFF) load4<VEC>(h, l0, d, hv);
       uint32_t rnd[4];
       if (QUANT && VEC) philox4x32_10((uint32_t)(l0 >> 2), ctr1, a.step, 0u, k0, k1, rnd);
+      uint32_t f = 0;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const float vv = DIFF ? xv[c] : xv[c] - hv[c];
-        v[k * 4 + c] = vv;
+        vv[c] = DIFF ? xv[c] : xv[c] - hv[c];
         const int64_t l = comp_index<VEC>(l0, c);
         if (l < d) {
-          const uint32_t key = magkey(vv);
+          const uint32_t key = magkey(vv[c]);
           const uint32_t bin = key >> kShift0;
-          const double dv = (double)vv;
+          const double dv = (double)vv[c];
           if (bin >= bmin) {
-            mask |= 1u << (k * 4 + c);
-            if (REF1) {
-#pragma unroll
-              for (int s = 0; s < P; ++s) {
-                const bool hit = bin == pre[s];
-                if (ballot(hit) != 0) {          // wave-uniform: skip the LDS instruction when no lane hits
-                  if (hit) atomicAdd(&ref1[s * kBins1 + ((key >> kShift1) & (kBins1 - 1))], 1u);
-                }
-              }
-            }
+            f |= 1u << c;
           } else {
             Eb = fma(dv, dv, Eb);
           }
@@ -571,7 +532,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
             for (int q = 0; q < kMaxLevels; ++q) {
               if (q < nq) {
                 int code;
-                const float cq = qa > 0.f ? quant_one(vv, qa, ns.lv.qs[q], qc[q], u, &code) : 0.f;
+                const float cq = qa > 0.f ? quant_one(vv[c], qa, ns.lv.qs[q], qc[q], u, &code) : 0.f;
                 const double e = dv - (double)cq;
                 qacc[q] = fma(e, e, qacc[q]);
               }
@@ -579,12 +540,9 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
           }
         }
       }
+      emit4<VEC>(f, vv, l0, slot, running);
     }
-    // ---- ordered extraction: one group per wavefront, at the group's own fixed offset ----
-    const uint32_t wtot = count_flagged<VEC>(mask);
-    const int grp = t * 4 + w;
-    if (lane == 0 && grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = wtot;
-    if (wtot) emit_flagged<VEC>(mask, v, base, w, lane, cand, (uint32_t)grp * kWaveTile);
+    if (lane == 0 && grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = running;
   }
 
   Eb = block_sum(Eb, red);
@@ -598,16 +556,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
       }
     }
   }
-  __syncthreads();
-  uint32_t* gref = ns.ref1 + (size_t)node * p * kBins1;
-  if (REF1) {
-    for (int b = tid; b < p * kBins1; b += kBlock) {
-      const uint32_t c = ref1[b];
-      if (c) atomicAdd(&gref[b], c);
-    }
-  }
-
-  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+  if (!arrive_last(&ns.done[(size_t)node * (kArriveFan + 1) * kCounterStride], gridDim.x, &s_flag)) return;
 
   // ---- epilogue ----
   double e = 0.0;
@@ -624,82 +573,169 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
     }
     if (tid == 0) ns.qscale[node] = 0.f;
   }
-  if (!REF1) return;
-  for (int s = 0; s < p; ++s) {
-    if (tid == 0) {
-      s_rank[0] = ns.rank[node * p + s];
-      s_bin[0] = 0; s_rk[0] = 1; s_cnt[0] = 0;
-    }
-    __syncthreads();
-    locate<kBins1>(gref + (size_t)s * kBins1, 1, s_rank, s_bin, s_rk, s_cnt, lds4);
-    if (tid == 0) {
-      ns.prefix[node * p + s] = (ns.prefix[node * p + s] << 10) | s_bin[0];
-      ns.rank[node * p + s] = s_rk[0];
-    }
-    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// Visits the candidates of group g in order, 64 at a time (all lanes call f(entry, valid)).
+// The group's count and its first 256 entries are loaded together, so that a typical group
+// (a few hundred candidates) costs one memory round trip instead of one per 64 entries.
+// Entries past the count are stale data inside the group's own slot and are flagged invalid.
+// ---------------------------------------------------------------------------
+template <typename F>
+__device__ __forceinline__ void visit_group(const uint2* __restrict__ cand, const uint32_t* __restrict__ counts, int g,
+                                            int64_t d, uint32_t lane, F&& f) {
+  const uint32_t start = (uint32_t)g * kWaveTile;
+  const uint32_t slen = (uint32_t)min((int64_t)kWaveTile, d - (int64_t)start);
+  const uint32_t cnt = counts[g];
+  uint2 pre[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t e = lane + 64 * j;
+    pre[j] = e < slen ? cand[start + e] : make_uint2(0u, 0u);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (64u * j < cnt) f(pre[j], lane + 64 * j < cnt);
+  }
+  for (uint32_t e0 = 256; e0 < cnt; e0 += 64) {
+    const uint32_t e = e0 + lane;
+    const bool valid = e < cnt;
+    f(valid ? cand[start + e] : make_uint2(0u, 0u), valid);
   }
 }
 
 // ---------------------------------------------------------------------------
-// refine: next digit of every slot's threshold over the candidate lists (one wavefront per
-// group at a time).  STAGE 1: second digit (10 bits below the 12-bit bin), used by the
-// one-pass sequence; STAGE 2: last digit (9 bits), after which T_s is exact.
+// gather: the keys of all candidates that lie in some slot's first-digit bin are appended
+// to one list per node (order is irrelevant for what follows).  Each wavefront buffers up to
+// kGatherCap keys in LDS and appends them with one reservation on the node's cursor.
 // ---------------------------------------------------------------------------
-template <int P, int STAGE>
-__global__ __launch_bounds__(kBlock) void k_refine(NodeSet ns) {
-  constexpr int NB = STAGE == 1 ? kBins1 : kBins2;
-  constexpr int SHIFT_HI = STAGE == 1 ? kShift0 : kShift1;   // bits above this digit
-  constexpr int SHIFT_LO = STAGE == 1 ? kShift1 : 0;
-  extern __shared__ uint32_t ref[];   // [p][NB]
-  __shared__ uint32_t lds4[4];
-  __shared__ int s_flag;
-  __shared__ uint32_t s_rank[1], s_bin[1], s_rk[1], s_cnt[1];
-  const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+constexpr int kGatherCap = 1024;
+constexpr int kCurStride = 64;    // one cursor per 256 bytes: read-modify-writes on one cache line serialise
+
+template <int P>
+__global__ __launch_bounds__(kBlock) void k_gather(NodeSet ns) {
+  __shared__ uint32_t buf[4][kGatherCap];
+  const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6;
+  const uint32_t lane = tid & 63;
   const int p = ns.lv.p;
   const size_t row = (size_t)node * (size_t)ns.d;
   const uint2* __restrict__ cand = ns.cand + row;
-  for (int b = tid; b < p * NB; b += kBlock) ref[b] = 0;
+  uint32_t* __restrict__ list = ns.glist + row;
+  const uint32_t* __restrict__ counts = ns.grp_count + (size_t)node * ns.groups;
   uint32_t pre[P];
 #pragma unroll
   for (int s = 0; s < P; ++s) pre[s] = s < p ? ns.prefix[node * p + s] : 0xFFFFFFFFu;
-  __syncthreads();
+  __shared__ uint32_t s_held[4];
+  __shared__ uint32_t s_base;
+  uint32_t held = 0;
+  auto flush_to = [&](uint32_t base) {
+    for (uint32_t i = lane; i < held; i += 64) list[base + i] = buf[w][i];
+    held = 0;
+  };
   for (int g = blockIdx.x * 4 + w; g < ns.groups; g += gridDim.x * 4) {
-    const uint32_t start = (uint32_t)g * kWaveTile;
-    const uint32_t cnt = ns.grp_count[(size_t)node * ns.groups + g];
-    for (uint32_t e0 = 0; e0 < cnt; e0 += 64) {
-      const uint32_t e = e0 + lane;
-      const bool valid = e < cnt;
-      const uint32_t key = valid ? (cand[start + e].y & 0x7FFFFFFFu) : 0u;
-      const uint32_t hi = key >> SHIFT_HI;
+    visit_group(cand, counts, g, ns.d, lane, [&](uint2 c, bool valid) {
+      const uint32_t key = c.y & 0x7FFFFFFFu;
+      const uint32_t bin = key >> kShift0;
+      bool hit = false;
 #pragma unroll
-      for (int s = 0; s < P; ++s) {
-        const bool hit = valid && hi == pre[s];
-        if (ballot(hit) != 0) {
-          if (hit) atomicAdd(&ref[s * NB + ((key >> SHIFT_LO) & (NB - 1))], 1u);
+      for (int s = 0; s < P; ++s) hit = hit || bin == pre[s];
+      hit = hit && valid;
+      const uint64_t b = ballot(hit);
+      if (b != 0) {
+        const uint32_t nhit = popc64(b);
+        if (held + nhit > (uint32_t)kGatherCap) {       // rare: the wavefront appends on its own
+          uint32_t base = 0;
+          if (lane == 0) base = atomicAdd(&ns.gcur[(size_t)node * kCurStride], held);
+          flush_to(__builtin_amdgcn_readfirstlane(base));
         }
+        if (hit) buf[w][held + below(b)] = key;
+        held += nhit;
       }
-    }
+    });
+  }
+  // one reservation per block for what the four wavefronts still hold
+  if (lane == 0) s_held[w] = held;
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t tot = s_held[0] + s_held[1] + s_held[2] + s_held[3];
+    s_base = tot ? atomicAdd(&ns.gcur[(size_t)node * kCurStride], tot) : 0u;
   }
   __syncthreads();
-  uint32_t* gref = (STAGE == 1 ? ns.ref1 : ns.ref2) + (size_t)node * p * NB;
-  for (int b = tid; b < p * NB; b += kBlock) {
-    const uint32_t c = ref[b];
-    if (c) atomicAdd(&gref[b], c);
+  uint32_t base = s_base;
+  for (int i = 0; i < w; ++i) base += s_held[i];
+  flush_to(base);
+}
+
+// ---------------------------------------------------------------------------
+// select: one block per (slot, node) finishes the radix select of that slot's threshold on
+// the node's gathered keys: second digit (10 bits), third digit (9 bits) -> exact T_s, the
+// number of ties to take r_s, and the number of keys equal to T_s.
+// ---------------------------------------------------------------------------
+constexpr int kSelBlock = 1024;
+
+__global__ __launch_bounds__(kSelBlock) void k_select(NodeSet ns) {
+  __shared__ uint32_t hist[kBins1];
+  __shared__ uint32_t wsum16[16];
+  __shared__ uint32_t res[3];
+  const int s = blockIdx.x, node = blockIdx.y, tid = threadIdx.x;
+  const int p = ns.lv.p;
+  const uint32_t* __restrict__ list = ns.glist + (size_t)node * (size_t)ns.d;
+  const uint32_t L = ns.gcur[(size_t)node * kCurStride];
+  const uint32_t L4 = (L + 3) / 4;             // 16-byte words; the row start is 16-byte aligned (d % 4 == 0)
+  const bool vec = (ns.d % 4) == 0;
+  uint32_t prefix = ns.prefix[node * p + s];   // 12-bit bin
+  uint32_t rank = ns.rank[node * p + s];
+  for (int stage = 0; stage < 2; ++stage) {
+    const int nb = stage == 0 ? kBins1 : kBins2;
+    const int shift_hi = stage == 0 ? kShift0 : kShift1;
+    const int shift_lo = stage == 0 ? kShift1 : 0;
+    for (int b = tid; b < kBins1; b += kSelBlock) hist[b] = 0;
+    if (tid < 3) res[tid] = tid == 1 ? 1u : 0u;
+    __syncthreads();
+    auto count = [&](uint32_t key, bool ok) {
+      if (ok && (key >> shift_hi) == prefix) atomicAdd(&hist[(key >> shift_lo) & (nb - 1)], 1u);
+    };
+    if (vec) {
+      const uint4* __restrict__ l4 = reinterpret_cast<const uint4*>(list);
+      for (uint32_t i0 = 0; i0 < L4; i0 += 2 * kSelBlock) {       // two 16-byte loads in flight per thread
+        const uint32_t ia = i0 + tid, ib = i0 + kSelBlock + tid;
+        uint4 ka = make_uint4(0, 0, 0, 0), kb = make_uint4(0, 0, 0, 0);
+        if (ia < L4) ka = l4[ia];
+        if (ib < L4) kb = l4[ib];
+        count(ka.x, 4 * ia + 0 < L); count(ka.y, 4 * ia + 1 < L); count(ka.z, 4 * ia + 2 < L); count(ka.w, 4 * ia + 3 < L);
+        count(kb.x, 4 * ib + 0 < L); count(kb.y, 4 * ib + 1 < L); count(kb.z, 4 * ib + 2 < L); count(kb.w, 4 * ib + 3 < L);
+      }
+    } else {
+      for (uint32_t i = tid; i < L; i += kSelBlock) count(list[i], true);
+    }
+    __syncthreads();
+    // walk the histogram from the top: thread t owns bin nb-1-t (nb <= 1024 threads)
+    const uint32_t c = tid < nb ? hist[nb - 1 - tid] : 0u;
+    uint32_t inc = c;
+    const uint32_t lane = tid & 63, w = tid >> 6;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t t = __shfl_up(inc, o, 64);
+      if (lane >= (uint32_t)o) inc += t;
+    }
+    if (lane == 63) wsum16[w] = inc;
+    __syncthreads();
+    uint32_t cum = inc - c;
+    for (uint32_t i = 0; i < w; ++i) cum += wsum16[i];
+    if (c && cum < rank && rank <= cum + c) {
+      res[0] = nb - 1 - tid;
+      res[1] = rank - cum;
+      res[2] = c;
+    }
+    __syncthreads();
+    prefix = (prefix << (stage == 0 ? 10 : 9)) | res[0];
+    rank = res[1];
+    __syncthreads();
   }
-  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
-  for (int s = 0; s < p; ++s) {
-    if (tid == 0) {
-      s_rank[0] = ns.rank[node * p + s];
-      s_bin[0] = 0; s_rk[0] = 1; s_cnt[0] = 0;
-    }
-    __syncthreads();
-    locate<NB>(gref + (size_t)s * NB, 1, s_rank, s_bin, s_rk, s_cnt, lds4);
-    if (tid == 0) {
-      ns.prefix[node * p + s] = (ns.prefix[node * p + s] << (STAGE == 1 ? 10 : 9)) | s_bin[0];
-      ns.rank[node * p + s] = s_rk[0];       // after stage 2: ties to take
-      ns.eqcnt[node * p + s] = s_cnt[0];     // after stage 2: keys equal to the exact threshold T_s
-    }
-    __syncthreads();
+  if (tid == 0) {
+    ns.prefix[node * p + s] = prefix;   // exact threshold key T_s
+    ns.rank[node * p + s] = rank;       // ties to take
+    ns.eqcnt[node * p + s] = res[2];    // keys equal to T_s
   }
 }
 
@@ -741,16 +777,12 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
     strict[s] = 0.0;
     tg[s] = te[s] = 0;
   }
+  const uint32_t* __restrict__ counts = ns.grp_count + (size_t)node * groups;
   for (int g = lo + w; g < hi; g += 4) {
-    const uint32_t start = (uint32_t)g * kWaveTile;
-    const uint32_t cnt = ns.grp_count[(size_t)node * groups + g];
     uint32_t cg[P], ce[P];
 #pragma unroll
     for (int s = 0; s < P; ++s) cg[s] = ce[s] = 0;
-    for (uint32_t e0 = 0; e0 < cnt; e0 += 64) {
-      const uint32_t e = e0 + lane;
-      const bool valid = e < cnt;
-      const uint2 c = valid ? cand[start + e] : make_uint2(0u, 0u);
+    visit_group(cand, counts, g, ns.d, lane, [&](uint2 c, bool valid) {
       const uint32_t key = c.y & 0x7FFFFFFFu;
       const double dv = (double)__uint_as_float(c.y);
       const double ev = dv * dv;
@@ -762,7 +794,7 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
           if (valid && key < T[s]) strict[s] += ev;
         }
       }
-    }
+    });
 #pragma unroll
     for (int s = 0; s < P; ++s) {
       if (s < p) {
@@ -792,7 +824,7 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
     st_coherent(&ns.blk_gt[o], s_tg[0][tid] + s_tg[1][tid] + s_tg[2][tid] + s_tg[3][tid]);
     st_coherent(&ns.blk_eq[o], s_te[0][tid] + s_te[1][tid] + s_te[2][tid] + s_te[3][tid]);
   }
-  if (!arrive_last(&ns.done[node], gridDim.x, &s_flag)) return;
+  if (!arrive_last(&ns.done[(size_t)node * (kArriveFan + 1) * kCounterStride], gridDim.x, &s_flag)) return;
 
   // ---- epilogue: realised errors, the AdaCGD cascade, message layout per block ----
   for (int s = 0; s < p; ++s) {
@@ -829,6 +861,7 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
     }
     ns.level[node] = jstar;
     atomicAdd(&ns.level_hist[jstar], 1ull);
+    if (p > 0) ns.gcur[(size_t)node * kCurStride] = 0;
     int slot = -1, q = -1;
     if (jstar > 0) {
       if (lv.kind[jstar - 1] == kTopK) slot = lv.ref[jstar - 1];
@@ -841,7 +874,7 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
       ns.sel_T[node] = ns.prefix[node * p + slot];
       ns.sel_r[node] = ns.rank[node * p + slot];
       s_r = ns.rank[node * p + slot];
-      ns.tile_off[(size_t)node * (ns.tiles + 1) + ns.tiles] = lv.K[slot];
+      ns.grp_off[(size_t)node * (groups + 1) + groups] = lv.K[slot];
     }
     s_slot = slot;
   }
@@ -890,6 +923,7 @@ __global__ __launch_bounds__(kBlock) void k_compact(NodeSet ns, PassArgs a) {
   float* __restrict__ mval = ns.msg_val + (size_t)node * ns.Kcap;
   const uint32_t* cgt = ns.cnt_gt + ((size_t)node * p + slot) * groups;
   const uint32_t* ceq = ns.cnt_eq + ((size_t)node * p + slot) * groups;
+  const uint32_t* __restrict__ counts = ns.grp_count + (size_t)node * groups;
   uint32_t eq_base = ns.blk_eqb[(size_t)node * ns.G2 + blockIdx.x];
   uint32_t out_base = ns.blk_out[(size_t)node * ns.G2 + blockIdx.x];
   // every wavefront scans the block's groups 64 at a time (lane i <-> group c0 + i) to get each
@@ -908,13 +942,8 @@ __global__ __launch_bounds__(kBlock) void k_compact(NodeSet ns, PassArgs a) {
       const int g = c0 + i;
       uint32_t eqb = __shfl(eqb_l, i, 64);
       uint32_t out = __shfl(out_l, i, 64);
-      if ((g & 3) == 0 && lane == 0) ns.tile_off[(size_t)node * (ns.tiles + 1) + (g >> 2)] = out;
-      const uint32_t start = (uint32_t)g * kWaveTile;
-      const uint32_t cnt = ns.grp_count[(size_t)node * groups + g];
-      for (uint32_t e0 = 0; e0 < cnt; e0 += 64) {
-        const uint32_t e = e0 + lane;
-        const bool valid = e < cnt;
-        const uint2 c = valid ? cand[start + e] : make_uint2(0u, 0u);
+      if (lane == 0) ns.grp_off[(size_t)node * (groups + 1) + g] = out;
+      visit_group(cand, counts, g, ns.d, lane, [&](uint2 c, bool valid) {
         const uint32_t key = c.y & 0x7FFFFFFFu;
         const bool eq = valid && key == T;
         const uint64_t beq = ballot(eq);
@@ -929,7 +958,7 @@ __global__ __launch_bounds__(kBlock) void k_compact(NodeSet ns, PassArgs a) {
         }
         eqb += popc64(beq);
         out += popc64(bt);
-      }
+      });
     }
     eq_base += __shfl(eq_inc, 63, 64);
     out_base += __shfl(out_inc, 63, 64);
@@ -1010,20 +1039,12 @@ hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <bool DIFF, bool VEC, bool REF1, int P>
-static void launch_filter_p(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
-  const dim3 grid(ns.G, ns.nn), block(kBlock);
-  const size_t lds = REF1 ? (size_t)ns.lv.p * kBins1 * sizeof(uint32_t) : 0;
-  if (ns.lv.nq > 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, true, REF1, P>), grid, block, lds, st, ns, a);
-  else hipLaunchKernelGGL((k_filter<DIFF, VEC, false, REF1, P>), grid, block, lds, st, ns, a);
-}
-
 template <bool DIFF, bool VEC>
 static void launch_filter_q(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
-  if (ns.onepass) launch_filter_p<DIFF, VEC, false, 4>(ns, a, st);
-  else if (ns.lv.p <= 4) launch_filter_p<DIFF, VEC, true, 4>(ns, a, st);
-  else if (ns.lv.p <= 8) launch_filter_p<DIFF, VEC, true, 8>(ns, a, st);
-  else launch_filter_p<DIFF, VEC, true, 16>(ns, a, st);
+  const dim3 grid(ns.G, ns.nn), block(kBlock);
+  if (ns.onepass) hipLaunchKernelGGL((k_filter<DIFF, VEC, false, true>), grid, block, 0, st, ns, a);
+  else if (ns.lv.nq > 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, true, false>), grid, block, 0, st, ns, a);
+  else hipLaunchKernelGGL((k_filter<DIFF, VEC, false, false>), grid, block, 0, st, ns, a);
 }
 
 hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
@@ -1055,20 +1076,22 @@ hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int STAGE>
-static hipError_t launch_refine_stage(const NodeSet& ns, hipStream_t st) {
+hipError_t launch_gather(const NodeSet& ns, hipStream_t st) {
   (void)hipGetLastError();
   if (ns.lv.p == 0) return hipSuccess;
   const dim3 grid(ns.G2, ns.nn), block(kBlock);
-  const size_t lds = (size_t)ns.lv.p * (STAGE == 1 ? kBins1 : kBins2) * sizeof(uint32_t);
-  if (ns.lv.p <= 4) hipLaunchKernelGGL((k_refine<4, STAGE>), grid, block, lds, st, ns);
-  else if (ns.lv.p <= 8) hipLaunchKernelGGL((k_refine<8, STAGE>), grid, block, lds, st, ns);
-  else hipLaunchKernelGGL((k_refine<16, STAGE>), grid, block, lds, st, ns);
+  if (ns.lv.p <= 4) hipLaunchKernelGGL((k_gather<4>), grid, block, 0, st, ns);
+  else if (ns.lv.p <= 8) hipLaunchKernelGGL((k_gather<8>), grid, block, 0, st, ns);
+  else hipLaunchKernelGGL((k_gather<16>), grid, block, 0, st, ns);
   return hipGetLastError();
 }
 
-hipError_t launch_refine1(const NodeSet& ns, hipStream_t st) { return launch_refine_stage<1>(ns, st); }
-hipError_t launch_refine(const NodeSet& ns, hipStream_t st) { return launch_refine_stage<2>(ns, st); }
+hipError_t launch_select(const NodeSet& ns, hipStream_t st) {
+  (void)hipGetLastError();
+  if (ns.lv.p == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_select, dim3(ns.lv.p, ns.nn), dim3(kSelBlock), 0, st, ns);
+  return hipGetLastError();
+}
 
 hipError_t launch_tally(const NodeSet& ns, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread

@@ -40,39 +40,61 @@ __global__ __launch_bounds__(kBlock) void k_copy_f32(float* __restrict__ dst, co
 }
 
 // ---------------------------------------------------------------------------
-// aggregation: one block per tile of the server vector.  The tile's share of every
-// worker's sorted message is a contiguous range (known from the message offsets per
-// tile), accumulated in an fp64 tile in LDS; then g~_new = fl(g~_old + acc / n).
-// Sums of fp32 values in fp64 are exact unless their exponents spread over more than
-// ~29 bits, so the result does not depend on the order of the LDS additions.
+// aggregation: one block per group (2048 coordinates) of the server vector.  The group's
+// share of every worker's sorted message is a contiguous range (known from the message
+// offsets per group).  The ranges of up to 256 workers at a time are laid end to end and the
+// threads stride over that flattened list, adding into an fp64 accumulator in LDS; then
+// g~_new = fl(g~_old + acc / n).  Sums of fp32 values in fp64 are exact unless their exponents
+// spread over more than ~29 bits, so the result does not depend on the order of the additions.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* __restrict__ gt_old,
                                                        float* __restrict__ gt_new) {
-  extern __shared__ double acc[];   // [kTile]
-  const int t = blockIdx.x, tid = threadIdx.x;
+  __shared__ double acc[kWaveTile];
+  __shared__ uint32_t s_lo[kBlock], s_pre[kBlock + 1];
+  __shared__ uint32_t lds4[4];
+  __shared__ int s_dense;
+  const int g = blockIdx.x, tid = threadIdx.x;
   const int64_t d = ws.d;
-  const int64_t base = (int64_t)t * kTile;
-  for (int c = tid; c < kTile; c += kBlock) acc[c] = 0.0;
+  const int64_t base = (int64_t)g * kWaveTile;
+  for (int c = tid; c < kWaveTile; c += kBlock) acc[c] = 0.0;
+  if (tid == 0) s_dense = 0;
   __syncthreads();
-  bool any_dense = false;
-  for (int i = 0; i < ws.nn; ++i) {
-    if (ws.sel_q && ws.sel_q[i] >= 0) any_dense = true;
-    if (ws.sel_slot[i] < 0) continue;
-    const uint32_t lo = ws.tile_off[(size_t)i * (ws.tiles + 1) + t];
-    const uint32_t hi = ws.tile_off[(size_t)i * (ws.tiles + 1) + t + 1];
-    const int32_t* __restrict__ midx = ws.msg_idx + (size_t)i * ws.Kcap;
-    const float* __restrict__ mval = ws.msg_val + (size_t)i * ws.Kcap;
-    for (uint32_t e = lo + tid; e < hi; e += kBlock)
-      unsafeAtomicAdd(&acc[midx[e] - base], (double)mval[e]);
+  for (int n0 = 0; n0 < ws.nn; n0 += kBlock) {
+    const int i = n0 + tid;
+    uint32_t lo = 0, cnt = 0;
+    if (i < ws.nn) {
+      if (ws.sel_slot[i] >= 0) {
+        lo = ws.grp_off[(size_t)i * (ws.groups + 1) + g];
+        cnt = ws.grp_off[(size_t)i * (ws.groups + 1) + g + 1] - lo;
+      } else if (ws.sel_q[i] >= 0) {
+        s_dense = 1;
+      }
+    }
+    uint32_t total;
+    const uint32_t pre = block_excl_scan(cnt, lds4, &total);
+    s_lo[tid] = lo;
+    s_pre[tid] = pre;
+    if (tid == 0) s_pre[kBlock] = total;
+    __syncthreads();
+    for (uint32_t e = tid; e < total; e += kBlock) {
+      // the worker whose range holds flattened entry e: last j with s_pre[j] <= e
+      int lo_j = 0, hi_j = kBlock;
+      while (hi_j - lo_j > 1) {
+        const int mid = (lo_j + hi_j) >> 1;
+        if (s_pre[mid] <= e) lo_j = mid; else hi_j = mid;
+      }
+      const size_t off = (size_t)(n0 + lo_j) * ws.Kcap + s_lo[lo_j] + (e - s_pre[lo_j]);
+      unsafeAtomicAdd(&acc[ws.msg_idx[off] - base], (double)ws.msg_val[off]);
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  if (any_dense) {
+  if (s_dense) {
     // quantised messages are dense: each thread owns its coordinates, workers in ascending order
     for (int i = 0; i < ws.nn; ++i) {
       if (ws.sel_q[i] < 0) continue;
       const float sc = ws.qscale[i];
       const int16_t* __restrict__ codes = ws.qcodes + (size_t)i * d;
-      for (int c = tid; c < kTile; c += kBlock) {
+      for (int c = tid; c < kWaveTile; c += kBlock) {
         if (base + c < d) {
           const int code = codes[base + c];
           const float mag = (float)(code < 0 ? -code : code) * sc;
@@ -82,7 +104,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
     }
   }
   const double n = (double)ws.nn;
-  for (int c = tid; c < kTile; c += kBlock)
+  for (int c = tid; c < kWaveTile; c += kBlock)
     if (base + c < d) gt_new[base + c] = (float)((double)gt_old[base + c] + acc[c] / n);
 }
 
@@ -190,8 +212,7 @@ hipError_t launch_mean(const float* gi, float* o0, float* o1, float* o2, int n, 
 
 hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_new, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
-  hipLaunchKernelGGL(k_aggregate, dim3(ws.tiles), dim3(kBlock), (size_t)kTile * sizeof(double), st, ws, gt_old,
-                     gt_new);
+  hipLaunchKernelGGL(k_aggregate, dim3(ws.groups), dim3(kBlock), 0, st, ws, gt_old, gt_new);
   return hipGetLastError();
 }
 

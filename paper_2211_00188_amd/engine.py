@@ -27,8 +27,8 @@ MAX_LEVELS = 16
  F_M_LEVEL_HIST, F_COMM, F_QCODES, F_QSCALE, F_KERNEL_MS, F_GRAD) = range(28)
 
 KERNELS = ["xupdate", "grad_margin", "grad_cols", "aggregate",
-           "w_sample", "w_scan", "w_filter", "w_refine1", "w_refine2", "w_tally", "w_compact", "w_qapply",
-           "m_sample", "m_scan", "m_filter", "m_refine1", "m_refine2", "m_tally", "m_compact", "m_qapply"]
+           "w_sample", "w_scan", "w_filter", "w_gather", "w_select", "w_tally", "w_compact", "w_qapply",
+           "m_sample", "m_scan", "m_filter", "m_gather", "m_select", "m_tally", "m_compact", "m_qapply"]
 
 EXPORTS = ["adacgd_workspace_bytes", "adacgd_init", "adacgd_step", "adacgd_state", "adacgd_destroy",
            "adacgd_last_error"]
