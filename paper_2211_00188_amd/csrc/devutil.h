@@ -85,16 +85,17 @@ __device__ __forceinline__ void st_coherent(T* p, T v) {
 // Arrivals are counted in two levels (kArriveFan first-level counters per node, then one
 // second-level counter) because a few thousand read-modify-writes on one address -- or on
 // one cache line -- take ~12 ns each, one after the other.  `counters` points at the node's
-// kArriveFan + 1 counters, one per kCounterStride words (= one per 64-byte line).
+// kArriveFan + 1 counters, one per kCounterStride words (= one per 64-byte line); `block` is the
+// caller's index among the nblocks blocks.
 constexpr int kArriveFan = 32;
 constexpr int kCounterStride = 16;
 
-__device__ __forceinline__ bool arrive_last(uint32_t* counters, uint32_t nblocks, int* lds_flag) {
+__device__ __forceinline__ bool arrive_last(uint32_t* counters, uint32_t nblocks, uint32_t block, int* lds_flag) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (threadIdx.x == 0) {
-    const uint32_t sub = blockIdx.x % kArriveFan;
+    const uint32_t sub = block % kArriveFan;
     const uint32_t nsub = (nblocks - sub + kArriveFan - 1) / kArriveFan;     // blocks sharing this counter
     const uint32_t nfan = nblocks < (uint32_t)kArriveFan ? nblocks : (uint32_t)kArriveFan;
     int last = 0;
@@ -112,6 +113,16 @@ __device__ __forceinline__ bool arrive_last(uint32_t* counters, uint32_t nblocks
   __syncthreads();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   return *lds_flag != 0;
+}
+
+// LDS histogram increment by the lanes that call it (they may be a divergent subset).  The
+// lanes that share the first active lane's bin are counted with one atomic: vectors with many
+// equal magnitudes (zeros above all) would otherwise serialise up to 64 same-address atomics.
+__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t bin) {
+  const uint32_t first = __builtin_amdgcn_readfirstlane(bin);
+  const uint64_t same = ballot(bin == first);
+  if (bin != first) atomicAdd(&hist[bin], 1u);
+  else if (below(same) == 0) atomicAdd(&hist[first], popc64(same));
 }
 
 __device__ __forceinline__ uint32_t fbits(float v) { return __float_as_uint(v); }

@@ -44,21 +44,23 @@ struct NodeSet {
   int groups;       // ceil(d / kWaveTile): candidate groups, one per wavefront share of a tile
   int G;            // blocks per node of the streaming kernels (scan, filter)
   int G2;           // blocks per node of the candidate kernels
-  int GS;           // blocks per node of the sample kernel
+  int GZ;           // blocks per (slot, node) of the select kernels
   int onepass;      // 1: sample + scanx sequence, 0: scan + filter sequence
   uint32_t Kcap;    // message capacity per node = largest Top-K size (0 if none)
   LevelTable lv;
 
   uint32_t* hist0;      // [nn][kBins0]           first-digit counts; zero between launches
+  uint32_t* sel_hist;   // [nn][p][kBins1]        digit counts of long gathered lists; zero between launches
+  uint32_t* sel_done;   // [nn][p][kArriveFan+1]  arrival counters of the select kernels
   uint32_t* gcur;       // [nn]                   keys gathered so far; zero between steps
   uint32_t* glist;      // [nn][d]                keys of the candidates inside the slots' first-digit bins
   uint32_t* prefix;     // [nn][p]                known high bits of slot threshold T_s (12, 22, 31 bits)
   uint32_t* rank;       // [nn][p]                rank of the K_s-th element inside the prefix
   uint32_t* eqcnt;      // [nn][p]                count of keys equal to T_s
   uint32_t* bmin;       // [nn]                   lowest first-digit bin that holds candidates
-  uint32_t* shist;      // [nn][kBins0]           first-digit counts of the sample; zero between launches
-  uint32_t* best;       // [nn]                   estimated cut-off bin from the sample
-  uint32_t* redo;       // [nn]                   1 = estimate was too high, the repair pass must run
+  uint32_t* ncand;      // [nn] (one per 64 bytes) candidates found by the fused scan; zero between launches
+  uint32_t* best;       // [nn]                   candidate cut (a key) estimated from the sample
+  uint32_t* redo;       // [nn]                   1 = fewer candidates than the largest K: the repair passes run
   uint32_t* done;       // [nn][kArriveFan+1]     arrival counters of the last-block epilogues
   uint32_t* kmax;       // [nn]                   running max magnitude key of the current scan; zero between launches
   uint32_t* amax;       // [nn]                   max magnitude key of the last scan (quantiser scale a)

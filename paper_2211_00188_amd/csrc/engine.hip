@@ -110,7 +110,9 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   const size_t nn = ns.nn, p = ns.lv.p, nq = ns.lv.nq, m = ns.lv.m, tiles = ns.groups;
   ns.hist0 = c.take<uint32_t>(nn * kBins0);
   ns.gcur = c.take<uint32_t>(nn * 64);   // one cursor per 256 bytes
-  ns.shist = c.take<uint32_t>(ns.onepass ? nn * kBins0 : 0);
+  ns.sel_hist = c.take<uint32_t>(nn * p * kBins1);
+  ns.sel_done = c.take<uint32_t>(nn * p * (kArriveFan + 1) * kCounterStride);
+  ns.ncand = c.take<uint32_t>(nn * kCounterStride);
   ns.done = c.take<uint32_t>(nn * (kArriveFan + 1) * kCounterStride);
   ns.kmax = c.take<uint32_t>(nn);
   ns.level_hist = c.take<unsigned long long>(m + 1);
@@ -175,10 +177,8 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
   // 1/32 sample to be informative, and a candidate set that is a minor part of the vector.
   ns.onepass = (!force_two_pass && ns.lv.nq == 0 && ns.lv.p > 0 && d % 4 == 0 && ns.tiles >= 128 &&
                 4 * (int64_t)ns.Kcap <= d) ? 1 : 0;
-  const int wants = (1024 + nn - 1) / nn;        // sample kernel: about 1024 blocks in all
-  const int smax = (ns.tiles + 15) / 16;         // at least 4 rounds of 4 tiles per wavefront
-  ns.GS = wants < smax ? wants : smax;
-  if (ns.GS < 1) ns.GS = 1;
+  int gz = (int)((d + 65535) / 65536);           // select kernels: one block per 64 Ki coordinates, at most 128
+  ns.GZ = gz < 1 ? 1 : (gz > 128 ? 128 : gz);
 }
 
 }  // namespace
@@ -356,7 +356,9 @@ int compress(adacgd_ctx* c, NodeSet& ns, const PassArgs& a, int slot0) {
   if (ns.onepass) {
     if ((rc = timed(c, slot0 + 0, [&] { return launch_sample(ns, a, c->st); }))) return rc;
     if ((rc = timed(c, slot0 + 1, [&] { return launch_scanx(ns, a, c->st); }))) return rc;
-    if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->st); }))) return rc;   // repair, usually idle
+    // repair passes: do nothing unless the sampled cut left fewer candidates than the largest K
+    if ((rc = timed(c, slot0 + 2, [&] { return launch_scan(ns, a, c->st); }))) return rc;
+    if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->st); }))) return rc;
   } else {
     if ((rc = timed(c, slot0 + 1, [&] { return launch_scan(ns, a, c->st); }))) return rc;
     if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->st); }))) return rc;

@@ -383,7 +383,7 @@ def _sampled_row(t):
     return ((t * 2654435761) & 0xFFFFFFFF) >> 27
 
 
-@pytest.mark.parametrize("kind", ["normal", "heavy", "ties", "adversarial", "two_pass_flag"])
+@pytest.mark.parametrize("kind", ["normal", "heavy", "ties", "const", "sparse", "adversarial", "two_pass_flag"])
 def test_long_vectors_one_pass_selection_bit_exact(kind):
     """Vectors long enough for the sampled one-pass selection (>= 128 tiles of 8192).  The
     'adversarial' input puts all large magnitudes exactly on the sampled rows, so the sampled
