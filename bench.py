@@ -24,6 +24,13 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per step of the worker-side selection kernels on the default workload, from the
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/model_sized_n16_d11200000_hbm_traffic.md
+# (reads scaled by 2.0, writes by 1.0, as calibrated there).  Valid only for the default
+# arguments and for the kernels as they were when the counters were taken.
+MEASURED_TRAFFIC_BYTES = 3516.9e6
+MEASURED_TRAFFIC_KERNELS = "w_sample+w_scan+w_filter+w_gather+w_select+w_tally+w_compact"
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -35,6 +42,8 @@ def main():
     ap.add_argument("--n", type=int, default=16)
     ap.add_argument("--d", type=int, default=11_200_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="run the worker and server chains on one stream (the kernel-timing pass always does)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (all n workers are batched on it); "
@@ -86,7 +95,7 @@ def main():
         torch.cuda.empty_cache()
         return dt, hist, kms
 
-    dt, hist, _ = run(0, args.steps, args.warmup)
+    dt, hist, _ = run(0 if args.no_overlap else E.FLAG_OVERLAP, args.steps, args.warmup)
     dt_ev, hist_ev, kms = run(E.FLAG_KERNEL_TIMING, args.steps, args.warmup)
 
     steps_per_s = args.steps / dt
@@ -105,9 +114,11 @@ def main():
     group = [k for k in group if k in per_kernel]
     dom = max(group, key=lambda k: per_kernel[k]["avg_ms"])
     dom_bytes = {"w_scan": 12.0 * n * d, "w_filter": 8.0 * n * d}.get(dom, 0.0)
+    default_workload = (args.n, args.d, args.zeta, args.pool) == (16, 11_200_000, 1.0, 4)
+    traffic = MEASURED_TRAFFIC_BYTES if default_workload and "+".join(group) == MEASURED_TRAFFIC_KERNELS else None
     roofline = {
         "bound": "hbm", "kernel": "+".join(group), "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+        "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
         "algorithmic_bytes_per_step": alg_bytes_step, "avg_ms_per_step": group_ms,
         "dominant_kernel": {"name": dom, "avg_ms": per_kernel[dom]["avg_ms"],
                             "bytes_read_per_launch": dom_bytes,
@@ -140,7 +151,9 @@ def main():
                                % (n, d, [k for _, k in wk.worker_levels], wk.master_levels[0][1], wk.zeta_worker,
                                   len(pool)),
                    "level_histogram_skip_then_levels": [int(v) for v in hist],
-                   "ms_per_step_with_kernel_events": dt_ev / args.steps * 1e3},
+                   "streams": "one" if args.no_overlap else
+                   "two (worker compression of step t+1 overlaps aggregation + master compression of step t)",
+                   "ms_per_step_one_stream_with_kernel_events": dt_ev / args.steps * 1e3},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -83,7 +83,13 @@ enum adacgd_flags {
                                       next step instead of copying it; the caller must leave that array
                                       untouched until the next adacgd_step call has completed            */
   ADACGD_FLAG_KERNEL_TIMING = 4,   /* record HIP events around every kernel (see ADACGD_F_KERNEL_MS)    */
-  ADACGD_FLAG_TWO_PASS = 8         /* never use the sampled one-pass selection (same results, slower)   */
+  ADACGD_FLAG_TWO_PASS = 8,        /* never use the sampled one-pass selection (same results, slower)   */
+  ADACGD_FLAG_OVERLAP = 16         /* GRAD_EXTERNAL / DIFF_EXTERNAL: run the worker compression on a stream
+                                      of the library's own, concurrently with the previous step's
+                                      aggregation and master compression on the caller's stream (same
+                                      results).  The arrays passed to adacgd_step must then be complete
+                                      when the call is made, not merely enqueued on the caller's stream;
+                                      the caller's stream still orders after everything a step enqueues */
 };
 
 typedef struct {

@@ -189,7 +189,11 @@ struct adacgd_ctx {
   uint32_t flags;
   double gamma;
   uint64_t seed;
-  hipStream_t st;
+  hipStream_t st;        // the caller's stream
+  hipStream_t cs;        // stream the next launch goes to
+  hipStream_t wst;       // overlap mode: the library's stream for the worker chain, else null
+  hipEvent_t ev_worker, ev_agg;
+  bool agg_recorded;
   char* ws_base;
   NodeSet W, M;
   bool has_master;
@@ -323,7 +327,7 @@ int timed(adacgd_ctx* c, int slot, F&& f) {
       if (!c->pool.empty()) { *e = c->pool.back(); c->pool.pop_back(); }
       else HIPCHK(c, hipEventCreate(e));
     }
-    HIPCHK(c, hipEventRecord(a, c->st));
+    HIPCHK(c, hipEventRecord(a, c->cs));
   }
   hipError_t e = f();
   if (e != hipSuccess) {
@@ -331,7 +335,7 @@ int timed(adacgd_ctx* c, int slot, F&& f) {
     return ADACGD_ERR_DEVICE;
   }
   if (c->timing) {
-    HIPCHK(c, hipEventRecord(b, c->st));
+    HIPCHK(c, hipEventRecord(b, c->cs));
     c->spans.push_back({slot, a, b});
   }
   return ADACGD_OK;
@@ -350,37 +354,46 @@ int drain_spans(adacgd_ctx* c) {
   return ADACGD_OK;
 }
 
-// one application of the AdaCGD compressor to every node of a set
-int compress(adacgd_ctx* c, NodeSet& ns, const PassArgs& a, int slot0) {
+// One application of the AdaCGD compressor to every node of a set, on the stream c->cs.
+// `before_tally`, if set, is an event the stream waits for before the kernels that overwrite the
+// message tables (tally, compact, qapply): in overlap mode the previous step's aggregation, which
+// reads them on the other stream, must have finished.
+int compress(adacgd_ctx* c, NodeSet& ns, const PassArgs& a, int slot0, hipEvent_t before_tally) {
   int rc;
   if (ns.onepass) {
-    if ((rc = timed(c, slot0 + 0, [&] { return launch_sample(ns, a, c->st); }))) return rc;
-    if ((rc = timed(c, slot0 + 1, [&] { return launch_scanx(ns, a, c->st); }))) return rc;
+    if ((rc = timed(c, slot0 + 0, [&] { return launch_sample(ns, a, c->cs); }))) return rc;
+    if ((rc = timed(c, slot0 + 1, [&] { return launch_scanx(ns, a, c->cs); }))) return rc;
     // repair passes: do nothing unless the sampled cut left fewer candidates than the largest K
-    if ((rc = timed(c, slot0 + 2, [&] { return launch_scan(ns, a, c->st); }))) return rc;
-    if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->st); }))) return rc;
+    if ((rc = timed(c, slot0 + 2, [&] { return launch_scan(ns, a, c->cs); }))) return rc;
+    if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->cs); }))) return rc;
   } else {
-    if ((rc = timed(c, slot0 + 1, [&] { return launch_scan(ns, a, c->st); }))) return rc;
-    if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->st); }))) return rc;
+    if ((rc = timed(c, slot0 + 1, [&] { return launch_scan(ns, a, c->cs); }))) return rc;
+    if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->cs); }))) return rc;
   }
-  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 3, [&] { return launch_gather(ns, c->st); }))) return rc;
-  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 4, [&] { return launch_select(ns, c->st); }))) return rc;
-  if ((rc = timed(c, slot0 + 5, [&] { return launch_tally(ns, c->st); }))) return rc;
-  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 6, [&] { return launch_compact(ns, a, c->st); }))) return rc;
-  if (ns.lv.nq > 0 && (rc = timed(c, slot0 + 7, [&] { return launch_qapply(ns, a, c->st); }))) return rc;
+  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 3, [&] { return launch_gather(ns, c->cs); }))) return rc;
+  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 4, [&] { return launch_select(ns, c->cs); }))) return rc;
+  if (before_tally) HIPCHK(c, hipStreamWaitEvent(c->cs, before_tally, 0));
+  if ((rc = timed(c, slot0 + 5, [&] { return launch_tally(ns, c->cs); }))) return rc;
+  if (ns.lv.p > 0 && (rc = timed(c, slot0 + 6, [&] { return launch_compact(ns, a, c->cs); }))) return rc;
+  if (ns.lv.nq > 0 && (rc = timed(c, slot0 + 7, [&] { return launch_qapply(ns, a, c->cs); }))) return rc;
   return ADACGD_OK;
 }
 
 int gradients(adacgd_ctx* c, float* out) {
   int rc;
-  if ((rc = timed(c, ADACGD_K_GRAD_MARGIN, [&] { return launch_grad_margins(c->ld, c->x, c->d, c->st); }))) return rc;
-  return timed(c, ADACGD_K_GRAD_COLS, [&] { return launch_grad_cols(c->ld, c->x, out, (int)c->n, c->d, c->st); });
+  if ((rc = timed(c, ADACGD_K_GRAD_MARGIN, [&] { return launch_grad_margins(c->ld, c->x, c->d, c->cs); }))) return rc;
+  return timed(c, ADACGD_K_GRAD_COLS, [&] { return launch_grad_cols(c->ld, c->x, out, (int)c->n, c->d, c->cs); });
 }
 
 int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
   int rc;
+  // Overlap mode: the worker chain runs on the library's own stream, the server chain (iterate
+  // update, aggregation, master compression) on the caller's; the worker chain of step t+1 does not
+  // depend on the server chain of step t (gradients are supplied), so the two run concurrently.
+  const bool ov = c->wst != nullptr;
+  c->cs = c->st;
   // x^{t+1} = x^t - gamma g^t
-  if ((rc = timed(c, ADACGD_K_XUPDATE, [&] { return launch_xupdate(c->x, c->g(), c->gamma, c->d, c->st); })))
+  if ((rc = timed(c, ADACGD_K_XUPDATE, [&] { return launch_xupdate(c->x, c->g(), c->gamma, c->d, c->cs); })))
     return rc;
   PassArgs a{};
   a.h = c->gi;
@@ -402,7 +415,13 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
     a.extD = extD;
   }
   // g~_i^{t+1} = C^AC_{g~_i^t, grad f_i(x^t)}(grad f_i(x^{t+1}))
-  if ((rc = compress(c, c->W, a, ADACGD_K_W_SAMPLE))) return rc;
+  if (ov) c->cs = c->wst;
+  if ((rc = compress(c, c->W, a, ADACGD_K_W_SAMPLE, ov && c->agg_recorded ? c->ev_agg : nullptr))) return rc;
+  if (ov) {
+    HIPCHK(c, hipEventRecord(c->ev_worker, c->wst));
+    c->cs = c->st;
+    HIPCHK(c, hipStreamWaitEvent(c->st, c->ev_worker, 0));
+  }
   if (c->grad_mode == ADACGD_GRAD_LOGISTIC) {
     c->ycur ^= 1;
   } else if (c->grad_mode == ADACGD_GRAD_EXTERNAL) {
@@ -412,7 +431,11 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
   // g~^{t+1} = g~^t + (1/n) sum_i messages
   float* gt_old = c->gt[c->cur];
   float* gt_new = c->gt[c->cur ^ 1];
-  if ((rc = timed(c, ADACGD_K_AGGREGATE, [&] { return launch_aggregate(c->W, gt_old, gt_new, c->st); }))) return rc;
+  if ((rc = timed(c, ADACGD_K_AGGREGATE, [&] { return launch_aggregate(c->W, gt_old, gt_new, c->cs); }))) return rc;
+  if (ov) {
+    HIPCHK(c, hipEventRecord(c->ev_agg, c->st));
+    c->agg_recorded = true;
+  }
   c->cur ^= 1;
   // g^{t+1} = C^AC_{g^t, g~^t}(g~^{t+1})
   if (c->has_master) {
@@ -423,7 +446,7 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
     m.seed = c->seed;
     m.step = (uint32_t)c->step;
     m.node_flag = 0x80000000u;
-    if ((rc = compress(c, c->M, m, ADACGD_K_M_SAMPLE))) return rc;
+    if ((rc = compress(c, c->M, m, ADACGD_K_M_SAMPLE, nullptr))) return rc;
   }
   c->step += 1;
   return ADACGD_OK;
@@ -503,6 +526,7 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
   c->has_master = cfg->m_master > 0;
   c->timing = (cfg->flags & ADACGD_FLAG_KERNEL_TIMING) != 0;
   c->step = 0; c->cur = 0; c->ycur = 0; c->y_ext = nullptr; c->err[0] = 0;
+  c->cs = c->st; c->wst = nullptr; c->ev_worker = nullptr; c->ev_agg = nullptr; c->agg_recorded = false;
   std::memset(c->ms_sum, 0, sizeof(c->ms_sum));
   std::memset(c->ms_cnt, 0, sizeof(c->ms_cnt));
   c->W = NodeSet{}; c->M = NodeSet{};
@@ -563,6 +587,12 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
     INITCHK(launch_fill_u32(c->M.msg_count, 0u, 1, c->st));
     INITCHK(launch_fill_u32((uint32_t*)c->M.level, 0u, 1, c->st));
   }
+  if ((cfg->flags & ADACGD_FLAG_OVERLAP) && cfg->grad_mode != ADACGD_GRAD_LOGISTIC) {
+    INITCHK(hipStreamSynchronize(c->st));     // the worker stream starts from a finished initial state
+    INITCHK(hipStreamCreateWithFlags(&c->wst, hipStreamNonBlocking));
+    INITCHK(hipEventCreateWithFlags(&c->ev_worker, hipEventDisableTiming));
+    INITCHK(hipEventCreateWithFlags(&c->ev_agg, hipEventDisableTiming));
+  }
 #undef INITCHK
   *out = c;
   return ADACGD_OK;
@@ -593,6 +623,7 @@ int adacgd_step(adacgd_ctx* c, const float* ext, const double* ext_D, int32_t ns
 int adacgd_state(adacgd_ctx* c, int32_t field, void* dst, int64_t dst_bytes, int32_t dst_on_device) {
   if (!c) return ADACGD_ERR_ARG;
   if (!dst && dst_bytes != 0) { set_err(c->err, "dst is null"); return ADACGD_ERR_ARG; }
+  if (c->wst) HIPCHK(c, hipStreamSynchronize(c->wst));
   HIPCHK(c, hipStreamSynchronize(c->st));
   const int64_t n = c->n, d = c->d;
   const hipMemcpyKind kind = dst_on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
@@ -717,6 +748,12 @@ int adacgd_state(adacgd_ctx* c, int32_t field, void* dst, int64_t dst_bytes, int
 
 int adacgd_destroy(adacgd_ctx* c) {
   if (!c) return ADACGD_OK;
+  if (c->wst) {
+    (void)hipStreamSynchronize(c->wst);
+    (void)hipStreamDestroy(c->wst);
+    (void)hipEventDestroy(c->ev_worker);
+    (void)hipEventDestroy(c->ev_agg);
+  }
   hipError_t e = hipStreamSynchronize(c->st);
   for (auto& s : c->spans) { hipEventDestroy(s.a); hipEventDestroy(s.b); }
   for (auto ev : c->pool) hipEventDestroy(ev);

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(HERE, "libadacgd.so")
 TOPK, QUANT = 0, 1
 GRAD_LOGISTIC, GRAD_EXTERNAL, DIFF_EXTERNAL = 0, 1, 2
 INIT_FULLGRAD, INIT_ZERO = 0, 1
-FLAG_ANY_LEVEL_ORDER, FLAG_RETAIN_EXT, FLAG_KERNEL_TIMING, FLAG_TWO_PASS = 1, 2, 4, 8
+FLAG_ANY_LEVEL_ORDER, FLAG_RETAIN_EXT, FLAG_KERNEL_TIMING, FLAG_TWO_PASS, FLAG_OVERLAP = 1, 2, 4, 8, 16
 MAX_LEVELS = 16
 
 (F_X, F_G, F_GTILDE, F_GTILDE_PREV, F_GI, F_PREV_GRAD, F_LEVEL, F_SQNORM, F_D, F_ERR, F_MSG_COUNT, F_MSG_IDX,

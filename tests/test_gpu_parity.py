@@ -415,3 +415,58 @@ def test_long_vectors_one_pass_selection_bit_exact(kind):
         eng.step(_cuda(grads[t]))
         compare_step(eng, orc, res, rm, ("long", kind, t))
     eng.close()
+
+
+@pytest.mark.parametrize("mode", ["grad", "diff"])
+def test_overlap_mode_gives_identical_results(mode):
+    """Worker compression on the library's own stream, overlapped with the previous step's
+    server work: every state vector and message must equal the single-stream run bit for bit,
+    and the oracle, over enough steps for the two chains to interleave."""
+    E = _eng()
+    import torch
+    n, d = 4, 140 * 8192 + 64
+    rng = np.random.default_rng(123)
+    wl = [(O.TOPK, 100), (O.TOPK, 5000), (O.TOPK, d // 25)]
+    ml = [(O.TOPK, d // 100)]
+    steps = 6
+    x0 = _cuda(np.zeros(d, dtype=np.float32))
+    if mode == "grad":
+        host = [rng.standard_normal((n, d)).astype(np.float32)]
+        for t in range(steps):
+            host.append((0.9 * host[-1] + 0.45 * rng.standard_normal((n, d))).astype(np.float32))
+        arrs = [_cuda(h) for h in host]
+    else:
+        host = [(rng.standard_t(4, size=(n, d)) * 0.1).astype(np.float32) for _ in range(steps + 1)]
+        arrs = [_cuda(h) for h in host]
+        Ds = [_cuda((np.sum(h.astype(np.float64) ** 2, axis=1) * rng.uniform(0.05, 2.0, n))) for h in host]
+    torch.cuda.synchronize()
+    outs = []
+    for flags in (0, E.FLAG_OVERLAP):
+        if mode == "grad":
+            eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=0.4, master_levels=ml,
+                           grad_mode=E.GRAD_EXTERNAL, x0=x0, grad0=arrs[0], flags=flags | E.FLAG_RETAIN_EXT)
+        else:
+            eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0, master_levels=ml,
+                           grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_ZERO, x0=x0, flags=flags)
+        levels = []
+        for t in range(1, steps + 1):
+            if mode == "grad":
+                eng.step(arrs[t])
+            else:
+                eng.step(arrs[t], Ds[t])
+            if t in (3, steps):
+                levels.append(eng.state(E.F_LEVEL).tolist())
+        outs.append((levels, eng.state(E.F_X), eng.state(E.F_G), eng.state(E.F_GTILDE), eng.state(E.F_GI),
+                     eng.state(E.F_MSG_IDX), eng.state(E.F_MSG_VAL), eng.state(E.F_LEVEL_HIST)))
+        eng.close()
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1:], outs[1][1:]):
+        assert np.array_equal(np.ascontiguousarray(a).view(np.uint8), np.ascontiguousarray(b).view(np.uint8))
+    if mode == "grad":
+        orc = O.AdaCGDOracle(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=0.4, master_levels=ml)
+        orc.init(np.zeros(d, dtype=np.float32), host[0], O.INIT_FULLGRAD)
+        for t in range(1, steps + 1):
+            orc.step(grads=host[t])
+        assert np.array_equal(bits(outs[1][1]), bits(orc.x))
+        assert np.array_equal(bits(outs[1][4]), bits(orc.gi))
+        assert outs[1][7].tolist() == orc.level_hist_w.tolist()
