@@ -32,6 +32,64 @@ MEASURED_TRAFFIC_BYTES = 3516.9e6
 MEASURED_TRAFFIC_KERNELS = "w_sample+w_scan+w_filter+w_gather+w_select+w_tally+w_compact"
 
 
+def _timed_steps(eng, E, torch, step_fn, warmup, steps):
+    for t in range(warmup):
+        step_fn(t)
+    torch.cuda.synchronize()
+    eng.kernel_ms()
+    h0 = eng.state(E.F_LEVEL_HIST).astype(np.int64)
+    t0 = time.perf_counter()
+    for t in range(warmup, warmup + steps):
+        step_fn(t)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    hist = eng.state(E.F_LEVEL_HIST).astype(np.int64) - h0
+    kms = {k: round(ms / cnt, 5) for k, (ms, cnt) in eng.kernel_ms().items() if cnt}
+    return dt, hist, kms
+
+
+def extra_kernel_stress(E, W, torch, steps=50, warmup=4):
+    """Secondary workload: heavy-tailed difference vectors, mixed Top-K / b-bit level set (n=32, d=2^20)."""
+    wk = W.kernel_stress()
+    pool = [W.kernel_stress_diffs(wk, t) for t in range(4)]
+    dv = [(torch.from_numpy(v).cuda(), torch.from_numpy(D).cuda()) for v, D in pool]
+    x0 = torch.zeros(wk.d, dtype=torch.float32, device="cuda")
+    eng = E.AdaCGD(n=wk.n, d=wk.d, gamma=0.1, worker_levels=wk.worker_levels, zeta_worker=wk.zeta_worker,
+                   master_levels=wk.master_levels, zeta_master=0.0, grad_mode=E.DIFF_EXTERNAL,
+                   init_mode=E.INIT_ZERO, x0=x0, seed=wk.seed, flags=E.FLAG_KERNEL_TIMING)
+    dt, hist, kms = _timed_steps(eng, E, torch, lambda t: eng.step(*dv[t % 4]), warmup, steps)
+    eng.close()
+    return {"workload": "kernel stress: n=%d, d=%d, difference vectors exp(N(0,1)) * t3, levels %s, master Top-%d"
+                        % (wk.n, wk.d, wk.worker_levels, wk.master_levels[0][1]),
+            "steps": steps, "ms_per_step": dt / steps * 1e3, "floats_per_sec": wk.n * wk.d * steps / dt,
+            "level_histogram_skip_then_levels": [int(v) for v in hist], "kernels_avg_ms": kms,
+            "note": "one stream, HIP events around every kernel"}
+
+
+def extra_federated(E, W, torch, n, steps=10, warmup=2):
+    """Secondary workload: logistic-regression shards (engine computes the gradients), d=65536, 32 samples each."""
+    wl = W.federated(n=n)
+    A, labels = torch.from_numpy(wl.A).cuda(), torch.from_numpy(wl.labels).cuda()
+    x0 = torch.zeros(wl.d, dtype=torch.float32, device="cuda")
+    eng = E.AdaCGD(n=wl.n, d=wl.d, gamma=wl.gamma, lam=wl.lam, worker_levels=wl.worker_levels,
+                   zeta_worker=wl.zeta_worker, master_levels=wl.master_levels, zeta_master=wl.zeta_master,
+                   grad_mode=E.GRAD_LOGISTIC, A=A, labels=labels, shard_offsets=wl.shard_offsets, x0=x0, seed=5,
+                   flags=E.FLAG_KERNEL_TIMING)
+    dt, hist, kms = _timed_steps(eng, E, torch, lambda t: eng.step(), warmup, steps)
+    eng.close()
+    a_bytes = float(wl.A.nbytes)
+    grad_ms = kms.get("grad_margin", 0.0) + kms.get("grad_cols", 0.0)
+    return {"workload": "federated logistic regression: n=%d workers (1000 in the full form), d=%d, %d samples each, "
+                        "levels %s, master Top-%d" % (wl.n, wl.d, wl.A.shape[0] // wl.n, wl.worker_levels,
+                                                      wl.master_levels[0][1]),
+            "steps": steps, "ms_per_step": dt / steps * 1e3, "floats_per_sec": wl.n * wl.d * steps / dt,
+            "level_histogram_skip_then_levels": [int(v) for v in hist], "kernels_avg_ms": kms,
+            "gradient_kernels": {"algorithmic_bytes": 2 * a_bytes, "avg_ms": grad_ms,
+                                 "GB/s": 2 * a_bytes / (grad_ms * 1e-3) / 1e9 if grad_ms else None,
+                                 "frac_of_8TBps": 2 * a_bytes / (grad_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if grad_ms else None},
+            "note": "one stream, HIP events around every kernel"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -42,6 +100,9 @@ def main():
     ap.add_argument("--n", type=int, default=16)
     ap.add_argument("--d", type=int, default=11_200_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--federated-n", type=int, default=250,
+                    help="workers of the secondary federated workload (1000 in its full form)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="run the worker and server chains on one stream (the kernel-timing pass always does)")
     args = ap.parse_args()
@@ -140,6 +201,14 @@ def main():
                          % (len(sample), n, d),
                "seconds": ct}
 
+    npool = len(pool)
+    del pool, g0, x0
+    torch.cuda.empty_cache()
+    other = []
+    if not args.no_extras:
+        other.append(extra_kernel_stress(E, W, torch))
+        other.append(extra_federated(E, W, torch, args.federated_n))
+
     out = {
         "metric": "adacgd_compressed_floats_per_sec", "value": floats_per_s, "unit": "floats/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
@@ -149,13 +218,14 @@ def main():
                                "(shared AR(1) drift + 0.5 * per-worker offset), Top-K levels %s, master Top-K %d, "
                                "zeta_worker=%g, zeta_master=0, gradient pool of %d arrays"
                                % (n, d, [k for _, k in wk.worker_levels], wk.master_levels[0][1], wk.zeta_worker,
-                                  len(pool)),
+                                  npool),
                    "level_histogram_skip_then_levels": [int(v) for v in hist],
                    "streams": "one" if args.no_overlap else
                    "two (worker compression of step t+1 overlaps aggregation + master compression of step t)",
                    "ms_per_step_one_stream_with_kernel_events": dt_ev / args.steps * 1e3},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "other_workloads": other,
     }
     print(json.dumps(out))
 

@@ -94,6 +94,7 @@ struct NodeSet {
   unsigned long long* level_hist;  // [m+1]
   int16_t* qcodes;      // [nn][d] (only with quantiser levels)
   float* qscale;        // [nn]
+  double* accbuf;       // [d] fp64 sums of the sparse messages (only with quantiser levels)
 };
 
 // Operands of one application of the compressor C_{h,y}(x) to every node of a set.

@@ -154,6 +154,7 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.msg_val = c.take<float>(nn * (size_t)ns.Kcap);
   ns.qcodes = nq ? c.take<int16_t>(nn * (size_t)ns.d) : nullptr;
   ns.qscale = c.take<float>(nn);
+  ns.accbuf = nq ? c.take<double>((size_t)ns.d) : nullptr;
 }
 
 void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {

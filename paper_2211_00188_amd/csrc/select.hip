@@ -608,8 +608,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
 
 // ---------------------------------------------------------------------------
 // Visits the candidates of group g in order, 64 at a time (all lanes call f(entry, valid)).
-// The group's count and its first 256 entries are loaded together, so that a typical group
-// (a few hundred candidates) costs one memory round trip instead of one per 64 entries.
+// The group's count and its first 192 entries are loaded together, so that a typical group
+// (one or two hundred candidates) costs one memory round trip instead of one per 64 entries.
 // Entries past the count are stale data inside the group's own slot and are flagged invalid.
 // ---------------------------------------------------------------------------
 template <typename F>
@@ -618,17 +618,18 @@ __device__ __forceinline__ void visit_group(const uint2* __restrict__ cand, cons
   const uint32_t start = (uint32_t)g * kWaveTile;
   const uint32_t slen = (uint32_t)min((int64_t)kWaveTile, d - (int64_t)start);
   const uint32_t cnt = counts[g];
-  uint2 pre[4];
+  constexpr int kPre = 3;
+  uint2 pre[kPre];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < kPre; ++j) {
     const uint32_t e = lane + 64 * j;
     pre[j] = e < slen ? cand[start + e] : make_uint2(0u, 0u);
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < kPre; ++j) {
     if (64u * j < cnt) f(pre[j], lane + 64 * j < cnt);
   }
-  for (uint32_t e0 = 256; e0 < cnt; e0 += 64) {
+  for (uint32_t e0 = 64 * kPre; e0 < cnt; e0 += 64) {
     const uint32_t e = e0 + lane;
     const bool valid = e < cnt;
     f(valid ? cand[start + e] : make_uint2(0u, 0u), valid);

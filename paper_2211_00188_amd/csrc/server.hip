@@ -47,17 +47,18 @@ __global__ __launch_bounds__(kBlock) void k_copy_f32(float* __restrict__ dst, co
 // g~_new = fl(g~_old + acc / n).  Sums of fp32 values in fp64 are exact unless their exponents
 // spread over more than ~29 bits, so the result does not depend on the order of the additions.
 // ---------------------------------------------------------------------------
+// DENSE_LATER (level sets with quantisers): the fp64 sums of the sparse messages go to ws.accbuf and
+// k_aggregate_dense adds the dense messages and finishes.
+template <bool DENSE_LATER>
 __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* __restrict__ gt_old,
                                                        float* __restrict__ gt_new) {
   __shared__ double acc[kWaveTile];
   __shared__ uint32_t s_lo[kBlock], s_pre[kBlock + 1];
   __shared__ uint32_t lds4[4];
-  __shared__ int s_dense;
   const int g = blockIdx.x, tid = threadIdx.x;
   const int64_t d = ws.d;
   const int64_t base = (int64_t)g * kWaveTile;
   for (int c = tid; c < kWaveTile; c += kBlock) acc[c] = 0.0;
-  if (tid == 0) s_dense = 0;
   __syncthreads();
   for (int n0 = 0; n0 < ws.nn; n0 += kBlock) {
     const int i = n0 + tid;
@@ -66,8 +67,6 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
       if (ws.sel_slot[i] >= 0) {
         lo = ws.grp_off[(size_t)i * (ws.groups + 1) + g];
         cnt = ws.grp_off[(size_t)i * (ws.groups + 1) + g + 1] - lo;
-      } else if (ws.sel_q[i] >= 0) {
-        s_dense = 1;
       }
     }
     uint32_t total;
@@ -88,24 +87,62 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
     }
     __syncthreads();
   }
-  if (s_dense) {
-    // quantised messages are dense: each thread owns its coordinates, workers in ascending order
-    for (int i = 0; i < ws.nn; ++i) {
-      if (ws.sel_q[i] < 0) continue;
-      const float sc = ws.qscale[i];
-      const int16_t* __restrict__ codes = ws.qcodes + (size_t)i * d;
-      for (int c = tid; c < kWaveTile; c += kBlock) {
-        if (base + c < d) {
-          const int code = codes[base + c];
-          const float mag = (float)(code < 0 ? -code : code) * sc;
-          acc[c] += (double)(code < 0 ? -mag : mag);
-        }
-      }
-    }
+  if (DENSE_LATER) {
+    for (int c = tid; c < kWaveTile; c += kBlock)
+      if (base + c < d) ws.accbuf[base + c] = acc[c];
+    return;
   }
   const double n = (double)ws.nn;
   for (int c = tid; c < kWaveTile; c += kBlock)
     if (base + c < d) gt_new[base + c] = (float)((double)gt_old[base + c] + acc[c] / n);
+}
+
+// Dense (quantised) messages: a block owns 128 coordinates, each lane two of them; the four
+// wavefronts take one quarter of the workers each, in ascending order, and their partial sums are
+// combined in wavefront order: g~_new = fl(g~_old + (sparse sums + dense sums) / n).
+constexpr int kDenseCols = 128;
+__global__ __launch_bounds__(kBlock) void k_aggregate_dense(NodeSet ws, const float* __restrict__ gt_old,
+                                                             float* __restrict__ gt_new) {
+  __shared__ double part[4][kDenseCols];
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int64_t d = ws.d;
+  const int64_t c0 = (int64_t)blockIdx.x * kDenseCols + 2 * lane;
+  const bool ok0 = c0 < d, ok1 = c0 + 1 < d;
+  const int q = (ws.nn + 3) / 4;
+  const int i0 = w * q, i1 = min(ws.nn, i0 + q);
+  double a0 = 0.0, a1 = 0.0;
+  auto decode = [](int code, float sc) {
+    const float mag = (float)(code < 0 ? -code : code) * sc;
+    return (double)(code < 0 ? -mag : mag);
+  };
+  for (int i = i0; i < i1; i += 4) {          // four workers' loads in flight
+    int k0[4], k1[4];
+    float sc[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int ii = i + u;
+      const bool dense = ii < i1 && ws.sel_q[ii] >= 0;
+      sc[u] = dense ? ws.qscale[ii] : 0.f;
+      const int16_t* __restrict__ codes = ws.qcodes + (size_t)(dense ? ii : 0) * d;
+      k0[u] = (dense && ok0) ? (int)codes[c0] : 0;
+      k1[u] = (dense && ok1) ? (int)codes[c0 + 1] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      a0 += decode(k0[u], sc[u]);
+      a1 += decode(k1[u], sc[u]);
+    }
+  }
+  part[w][2 * lane] = a0;
+  part[w][2 * lane + 1] = a1;
+  __syncthreads();
+  if (tid < kDenseCols) {
+    const int64_t c = (int64_t)blockIdx.x * kDenseCols + tid;
+    if (c < d) {
+      const double tot = ws.accbuf[c] + (((part[0][tid] + part[1][tid]) + part[2][tid]) + part[3][tid]);
+      gt_new[c] = (float)((double)gt_old[c] + tot / (double)ws.nn);
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -212,7 +249,15 @@ hipError_t launch_mean(const float* gi, float* o0, float* o1, float* o2, int n, 
 
 hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_new, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
-  hipLaunchKernelGGL(k_aggregate, dim3(ws.groups), dim3(kBlock), 0, st, ws, gt_old, gt_new);
+  if (ws.lv.nq == 0) {
+    hipLaunchKernelGGL((k_aggregate<false>), dim3(ws.groups), dim3(kBlock), 0, st, ws, gt_old, gt_new);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL((k_aggregate<true>), dim3(ws.groups), dim3(kBlock), 0, st, ws, gt_old, gt_new);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_aggregate_dense, dim3((unsigned)((ws.d + kDenseCols - 1) / kDenseCols)), dim3(kBlock), 0, st, ws,
+                     gt_old, gt_new);
   return hipGetLastError();
 }
 
