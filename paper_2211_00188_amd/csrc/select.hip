@@ -4,30 +4,37 @@
 // cascade of the AdaCGD definition, and the EF21 update h <- h + C_j(x - h) (Eq. (7))
 // with the sparse message.
 //
-// Two kernel sequences per node set.  Every kernel ends with a "last block of the node"
-// epilogue that finishes the node's small serial work, so no extra launches.
+// Every vector is cut into groups of 2048 consecutive coordinates (one wavefront's share of
+// an 8192-coordinate tile).  The candidates of group g -- the coordinates that can belong to
+// the largest Top-K set -- are stored at the fixed offset g * 2048 of the node's candidate
+// list, in coordinate order, so all later stages keep that order without sorting.
+//
+// Kernel sequences per node set.  Kernels that need a reduction over the node end with a
+// "last block of the node" epilogue (an arrival counter; nobody waits), so the small serial
+// parts need no extra launches.
 //
 // One-pass sequence (Top-K levels only, long vectors):
-//   sample  : first-digit histogram of 1/32 of the vector (one 1 KB row of every tile)
-//             epilogue: a conservative estimate b_est of the candidate cut-off bin
-//   scanx   : scan (below) fused with the candidate extraction at b_est and the energy
-//             below b_est; epilogue additionally checks, with the exact histogram, that
-//             b_est is not above the true cut-off bin, else marks the node for `filter`
-//   filter  : only for marked nodes (none in the common case)
-//   refine1, refine2, tally, compact as below
-//
-// Two-pass sequence (any level set, any length):
-//   scan    : v = x - h, S = ||v||^2, D = ||x - y||^2, first-digit histogram
+//   sample  : one block per node histograms a sample of the vector and derives a
+//             conservative candidate cut (a key) for the largest Top-K size
+//   scanx   : v = x - h, S = ||v||^2, D = ||x - y||^2, candidates with key >= cut, their
+//             first-digit histogram and count, the energy below the cut
+//             epilogue: first digit (bin) and in-bin rank of each Top-K size; marks the node
+//             for repair if fewer candidates than the largest K were found
+//   scan + filter (repair variants): idle unless a node is marked; then they redo the
+//             node in two passes
+// Two-pass sequence (level sets with quantisers, short vectors):
+//   scan    : v, S, D, full first-digit histogram, max |v|
 //             epilogue: bin and in-bin rank of each Top-K size, candidate cut-off bin
-//   filter  : re-forms v, sums the energy below the cut-off, writes candidates
-//             (coordinate, value) grouped by tile in coordinate order, second-digit
-//             histograms, realised quantiser errors
-//             epilogue: second digit of each threshold
-//   refine  : third-digit histograms over the candidates; epilogue: exact thresholds
-//             T_s, ties to take r_s, tie counts
-//   tally   : per tile counts of keys > T_s and == T_s, energy strictly below T_s
-//             epilogue: err of every level, the cascade, message offsets per tile
+//   filter  : re-forms v, candidates = keys in bins >= cut-off, energy below, realised
+//             error of every quantiser level (Philox dither)
+// Then, both sequences:
+//   gather  : keys of the candidates inside some Top-K size's bin -> one list per node
+//   select  : one block per (Top-K size, node) finishes the radix select on that list:
+//             exact threshold key T_s, ties to take r_s, count of keys equal to T_s
+//   tally   : per group counts of keys > T_s and == T_s, energy strictly below T_s
+//             epilogue: err of every level, the cascade, message layout per block
 //   compact : writes the chosen level's message in ascending coordinate and updates h
+//   qapply  : dense update and codes for nodes whose chosen level is a quantiser
 #include "devutil.h"
 #include "engine.h"
 
