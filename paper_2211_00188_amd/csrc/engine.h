@@ -82,7 +82,8 @@ struct NodeSet {
   uint32_t* blk_out;    // [nn][G2]     message offset of the block's first group, chosen level
   uint32_t* blk_eqb;    // [nn][G2]     ties before the block's first group, chosen level
   uint32_t* grp_off;    // [nn][groups+1] message offset of each group's first entry (last = total)
-  uint2* cand;          // [nn][d]  (coordinate, value bits); group g starts at g * kWaveTile
+  uint32_t* cand_val;   // [nn][d]  value bits of the candidates; group g starts at g * kWaveTile
+  uint16_t* cand_off;   // [nn][d]  their coordinate offsets inside the group, same layout
   int32_t* level;       // [nn]   0 = skip
   int32_t* sel_slot;    // [nn]   slot of the chosen Top-K level, -1 otherwise
   int32_t* sel_q;       // [nn]   quantiser index of the chosen level, -1 otherwise

@@ -142,7 +142,8 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.blk_out = c.take<uint32_t>(nn * ns.G2);
   ns.blk_eqb = c.take<uint32_t>(nn * ns.G2);
   ns.grp_off = c.take<uint32_t>(nn * (tiles + 1));
-  ns.cand = p ? c.take<uint2>(nn * (size_t)ns.d) : nullptr;
+  ns.cand_val = p ? c.take<uint32_t>(nn * (size_t)ns.d) : nullptr;
+  ns.cand_off = p ? c.take<uint16_t>(nn * (size_t)ns.d) : nullptr;
   ns.glist = p ? c.take<uint32_t>(nn * (size_t)ns.d) : nullptr;
   ns.level = c.take<int32_t>(nn);
   ns.sel_slot = c.take<int32_t>(nn);
@@ -161,10 +162,6 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
   ns.nn = nn;
   ns.d = d;
   ns.tiles = (int)((d + kTile - 1) / kTile);
-  int want = (2560 + nn - 1) / nn;               // streaming kernels: about 2560 blocks in all,
-  if (want > 640) want = 640;                    // at most 640 per node (each block flushes a histogram)
-  ns.G = ns.tiles < want ? ns.tiles : want;
-  if (ns.G < 1) ns.G = 1;
   ns.groups = (int)((d + kWaveTile - 1) / kWaveTile);
   // candidate kernels: about 2048 blocks in all, each owning a contiguous range of groups
   int g2 = (ns.groups + 3) / 4;
@@ -178,8 +175,17 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
   // 1/32 sample to be informative, and a candidate set that is a minor part of the vector.
   ns.onepass = (!force_two_pass && ns.lv.nq == 0 && ns.lv.p > 0 && d % 4 == 0 && ns.tiles >= 128 &&
                 4 * (int64_t)ns.Kcap <= d) ? 1 : 0;
-  int gz = (int)((d + 65535) / 65536);           // select kernels: one block per 64 Ki coordinates, at most 128
-  ns.GZ = gz < 1 ? 1 : (gz > 128 ? 128 : gz);
+  // streaming kernels: about 5120 blocks in all for the fused scan (several short blocks per CU
+  // interleave better with kernels of another stream than few long ones), about 2560 for the
+  // two-pass scan (whose blocks each flush a full histogram); at most 640 per node
+  int want = ((ns.onepass ? 5120 : 2560) + nn - 1) / nn;
+  if (want > 640) want = 640;
+  ns.G = ns.tiles < want ? ns.tiles : want;
+  if (ns.G < 1) ns.G = 1;
+  // select kernels: up to 8 blocks per (Top-K size, node) share a long list (most lists are
+  // short and all but a few blocks exit at once, so the launch should stay small)
+  int gz = (int)((d + 262143) / 262144);
+  ns.GZ = gz < 1 ? 1 : (gz > 8 ? 8 : gz);
 }
 
 }  // namespace

@@ -35,6 +35,8 @@
 //             epilogue: err of every level, the cascade, message layout per block
 //   compact : writes the chosen level's message in ascending coordinate and updates h
 //   qapply  : dense update and codes for nodes whose chosen level is a quantiser
+#include <type_traits>
+
 #include "devutil.h"
 #include "engine.h"
 
@@ -117,22 +119,38 @@ __device__ void locate(uint32_t* hist, int nr, const uint32_t* rank, uint32_t* o
   __syncthreads();
 }
 
+// Entry e of group g's candidate slot sits at position (e + group_rot(g)) mod 2048 of the
+// slot.  Typical groups fill only the first few hundred entries; without the rotation those
+// writes would all fall on the same few address bits (slot stride 8 KB) and so on a fraction of
+// the memory channels.  Rotations are multiples of 64 entries, so 64-entry chunks stay
+// contiguous.  A trailing partial group is not rotated (its slot is shorter than 2048).
+__device__ __forceinline__ uint32_t group_rot(int g, int64_t d) {
+  if (((int64_t)g + 1) * kWaveTile > d) return 0u;
+  return (((uint32_t)g * 2654435761u) >> 21) & (uint32_t)(kWaveTile - 64);
+}
+
 // ---------------------------------------------------------------------------
 // ordered extraction: the wavefront appends the flagged components of one iteration (4 per
 // lane, flag bit c <-> component c) to its group's slot of the candidate list, keeping
-// coordinate order.  `running` is the number of candidates the group holds so far.
-// Must be called by all 64 lanes.
+// coordinate order.  A candidate is stored as its value bits (sval) and, in a separate array,
+// its 11-bit offset inside the group (soff); o0 is the offset of the lane's component 0.
+// `running` is the number of candidates the group holds so far.  Must be called by all 64 lanes.
 // ---------------------------------------------------------------------------
 template <bool VEC>
-__device__ __forceinline__ void emit4(uint32_t f, const float (&vv)[4], int64_t l0, uint2* __restrict__ slot,
-                                      uint32_t& running) {
+__device__ __forceinline__ void emit4(uint32_t f, const float (&vv)[4], uint32_t o0, uint32_t* __restrict__ sval,
+                                      uint16_t* __restrict__ soff, uint32_t rot, uint32_t& running) {
   if (VEC) {      // order: lane, then component
     const uint64_t b0 = ballot(f & 1u), b1 = ballot(f & 2u), b2 = ballot(f & 4u), b3 = ballot(f & 8u);
     if ((b0 | b1 | b2 | b3) != 0) {
       uint32_t pos = running + below(b0) + below(b1) + below(b2) + below(b3);
 #pragma unroll
       for (int c = 0; c < 4; ++c)
-        if ((f >> c) & 1u) slot[pos++] = make_uint2((uint32_t)(l0 + c), fbits(vv[c]));
+        if ((f >> c) & 1u) {
+          const uint32_t at = (pos + rot) & (uint32_t)(kWaveTile - 1);
+          sval[at] = fbits(vv[c]);
+          soff[at] = (uint16_t)(o0 + c);
+          ++pos;
+        }
       running += popc64(b0) + popc64(b1) + popc64(b2) + popc64(b3);
     }
   } else {        // order: component, then lane
@@ -140,7 +158,11 @@ __device__ __forceinline__ void emit4(uint32_t f, const float (&vv)[4], int64_t 
     for (int c = 0; c < 4; ++c) {
       const bool fc = (f >> c) & 1u;
       const uint64_t b = ballot(fc);
-      if (fc) slot[running + below(b)] = make_uint2((uint32_t)(l0 + 64 * c), fbits(vv[c]));
+      if (fc) {
+        const uint32_t at = (running + below(b) + rot) & (uint32_t)(kWaveTile - 1);
+        sval[at] = fbits(vv[c]);
+        soff[at] = (uint16_t)(o0 + 64 * c);
+      }
       running += popc64(b);
     }
   }
@@ -276,31 +298,33 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample(NodeSet ns, PassArgs a)
   if (tid < 3) res[tid] = tid == 1 ? 1u : 0u;
   __syncthreads();
   const int R = ns.tiles < kSampleRows ? ns.tiles : kSampleRows;
-  constexpr int U = kSampleRows / 16;        // rows per wavefront, all in flight at once
-  float4 xv[U], hv[U];
-  bool ok[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int r = w * U + u;
-    const int t = (int)(((int64_t)r * ns.tiles) / R);          // evenly spaced tiles
-    const int64_t l0 = (int64_t)t * kTile + sample_row(t) * 256 + lane * 4;
-    ok[u] = r < R && l0 < d;
-    if (ok[u]) {
-      xv[u] = *reinterpret_cast<const float4*>(x + l0);
-      if (!DIFF) hv[u] = *reinterpret_cast<const float4*>(h + l0);
-    }
-  }
+  constexpr int U = kSampleRows / 16;        // rows per wavefront
+  constexpr int UB = U / 2;                  // ... read in two batches of UB rows, each batch in flight at once
   uint32_t mine = 0;
+  for (int b = 0; b < 2; ++b) {
+    float4 xv[UB], hv[UB];
+    bool ok[UB];
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    if (ok[u]) {
-      const float v0 = DIFF ? xv[u].x : xv[u].x - hv[u].x, v1 = DIFF ? xv[u].y : xv[u].y - hv[u].y;
-      const float v2 = DIFF ? xv[u].z : xv[u].z - hv[u].z, v3 = DIFF ? xv[u].w : xv[u].w - hv[u].w;
-      hist_add(hist, magkey(v0) >> kSampleShift);
-      hist_add(hist, magkey(v1) >> kSampleShift);
-      hist_add(hist, magkey(v2) >> kSampleShift);
-      hist_add(hist, magkey(v3) >> kSampleShift);
-      mine += 4;
+    for (int u = 0; u < UB; ++u) {
+      const int r = w * U + b * UB + u;
+      const int t = (int)(((int64_t)r * ns.tiles) / R);          // evenly spaced tiles
+      const int64_t l0 = (int64_t)t * kTile + sample_row(t) * 256 + lane * 4;
+      ok[u] = r < R && l0 < d;
+      xv[u] = hv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (ok[u]) {
+        xv[u] = *reinterpret_cast<const float4*>(x + l0);
+        if (!DIFF) hv[u] = *reinterpret_cast<const float4*>(h + l0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      if (ok[u]) {
+        hist_add(hist, magkey(xv[u].x - hv[u].x) >> kSampleShift);
+        hist_add(hist, magkey(xv[u].y - hv[u].y) >> kSampleShift);
+        hist_add(hist, magkey(xv[u].z - hv[u].z) >> kSampleShift);
+        hist_add(hist, magkey(xv[u].w - hv[u].w) >> kSampleShift);
+        mine += 4;
+      }
     }
   }
   // sample size m
@@ -352,6 +376,9 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
   __shared__ uint32_t lds4[4];
   __shared__ int s_flag;
   __shared__ uint32_t s_rank[kMaxLevels], s_bin[kMaxLevels], s_rk[kMaxLevels], s_cnt[kMaxLevels];
+  constexpr int kStage = 512;            // staged candidates per wavefront (an iteration adds at most 256)
+  __shared__ uint32_t st_val[4][kStage];
+  __shared__ uint16_t st_off[4][kStage];
 
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int64_t d = ns.d;
@@ -360,7 +387,8 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
   const float* __restrict__ h = a.h + row;
   const float* __restrict__ y = DIFF ? nullptr : a.y + row;
   float* __restrict__ yc = a.ycopy ? a.ycopy + row : nullptr;
-  uint2* __restrict__ cand = ns.cand + row;
+  uint32_t* __restrict__ cval = ns.cand_val + row;
+  uint16_t* __restrict__ coff = ns.cand_off + row;
   const uint32_t cut = ns.best[node];
 
   for (int b = tid; b < kBins0; b += kBlock) hist[b] = 0;
@@ -371,8 +399,22 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
   for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
     const int64_t base = (int64_t)t * kTile;
     const int grp = t * 4 + w;
-    uint2* __restrict__ slot = cand + (size_t)grp * kWaveTile;
-    uint32_t running = 0;
+    uint32_t* __restrict__ sval = cval + (size_t)grp * kWaveTile;
+    uint16_t* __restrict__ soff = coff + (size_t)grp * kWaveTile;
+    const uint32_t rot = group_rot(grp, d);
+    // candidates are staged in LDS and written out at the end of the tile (earlier only when a
+    // dense group fills the stage): stores issued between the loads of a tile would make every
+    // wait for a load also wait for the stores before it
+    uint32_t held = 0, running = 0;      // the group holds running + held candidates
+    auto flush = [&]() {
+      for (uint32_t e = lane; e < held; e += 64) {
+        const uint32_t at = (running + e + rot) & (uint32_t)(kWaveTile - 1);
+        sval[at] = st_val[w][e];
+        soff[at] = st_off[w][e];
+      }
+      running += held;
+      held = 0;
+    };
 #pragma unroll
     for (int k = 0; k < kIter; ++k) {
       const int64_t l0 = comp0<VEC>(base, w, lane, k);
@@ -404,8 +446,10 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
           }
         }
       }
-      emit4<VEC>(f, vv, l0, slot, running);
+      if (held > (uint32_t)(kStage - 256)) flush();
+      emit4<VEC>(f, vv, (uint32_t)(l0 - base) - (uint32_t)w * kWaveTile, st_val[w], st_off[w], 0u, held);
     }
+    flush();
     if (lane == 0 && grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = running;
     ncand += running;
   }
@@ -509,7 +553,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   const size_t row = (size_t)node * (size_t)d;
   const float* __restrict__ x = a.x + row;
   const float* __restrict__ h = a.h + row;
-  uint2* __restrict__ cand = ns.cand + row;
+  uint32_t* __restrict__ cval = ns.cand_val + row;
+  uint16_t* __restrict__ coff = ns.cand_off + row;
 
   const uint32_t bmin = ns.bmin[node];
 
@@ -532,7 +577,9 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
     const int64_t base = (int64_t)t * kTile;
     const int grp = t * 4 + w;
-    uint2* __restrict__ slot = cand + (size_t)grp * kWaveTile;
+    uint32_t* __restrict__ sval = cval + (size_t)grp * kWaveTile;
+    uint16_t* __restrict__ soff = coff + (size_t)grp * kWaveTile;
+    const uint32_t rot = group_rot(grp, d);
     uint32_t running = 0;
 #pragma unroll
     for (int k = 0; k < kIter; ++k) {
@@ -578,7 +625,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
           }
         }
       }
-      emit4<VEC>(f, vv, l0, slot, running);
+      emit4<VEC>(f, vv, (uint32_t)(l0 - base) - (uint32_t)w * kWaveTile, sval, soff, rot, running);
     }
     if (lane == 0 && grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = running;
   }
@@ -614,32 +661,71 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// Visits the candidates of group g in order, 64 at a time (all lanes call f(entry, valid)).
-// The group's count and its first 192 entries are loaded together, so that a typical group
-// (one or two hundred candidates) costs one memory round trip instead of one per 64 entries.
-// Entries past the count are stale data inside the group's own slot and are flagged invalid.
+// Reading the candidates of a group, in order, 64 at a time.  group_load issues the loads of
+// the group's count and of its first 192 entries together, so that a typical group (one or two
+// hundred candidates) costs one memory round trip.  group_visit then calls
+// f(value bits, offset in group, valid) in all lanes for each 64 entries (offsets are read only
+// when OFF).  Entries past the count are stale data inside the group's own slot, flagged invalid.
 // ---------------------------------------------------------------------------
-template <typename F>
-__device__ __forceinline__ void visit_group(const uint2* __restrict__ cand, const uint32_t* __restrict__ counts, int g,
-                                            int64_t d, uint32_t lane, F&& f) {
-  const uint32_t start = (uint32_t)g * kWaveTile;
-  const uint32_t slen = (uint32_t)min((int64_t)kWaveTile, d - (int64_t)start);
-  const uint32_t cnt = counts[g];
-  constexpr int kPre = 3;
-  uint2 pre[kPre];
+constexpr int kPre = 3;
+struct GroupHead {
+  uint32_t start, rot, cnt;
+  uint32_t pv[kPre], po[kPre];
+};
+
+template <bool OFF>
+__device__ __forceinline__ GroupHead group_load(const uint32_t* __restrict__ cval, const uint16_t* __restrict__ coff,
+                                                const uint32_t* __restrict__ counts, int g, int64_t d, uint32_t lane) {
+  GroupHead gh;
+  gh.start = (uint32_t)g * kWaveTile;
+  gh.rot = group_rot(g, d);
+  const uint32_t slen = (uint32_t)min((int64_t)kWaveTile, d - (int64_t)gh.start);
+  gh.cnt = counts[g];
 #pragma unroll
-  for (int j = 0; j < kPre; ++j) {
+  for (int j = 0; j < kPre; ++j) {      // unconditional loads (entries past a short slot read its first one)
     const uint32_t e = lane + 64 * j;
-    pre[j] = e < slen ? cand[start + e] : make_uint2(0u, 0u);
+    const uint32_t at = gh.start + (e < slen ? ((e + gh.rot) & (uint32_t)(kWaveTile - 1)) : 0u);
+    gh.pv[j] = cval[at];
+    gh.po[j] = OFF ? (uint32_t)coff[at] : 0u;
   }
+  return gh;
+}
+
+// Calls body(head, g) for g = g0, g0 + gstep, ... < gend with the loads of the following group
+// already issued.  Two heads alternate so that no register copy (which would have to wait for
+// the loads) sits between one group and the next, and the last group has a call site of its
+// own so that no path merges with loads that may or may not have been issued.
+template <bool OFF, typename Body>
+__device__ __forceinline__ void for_groups(const uint32_t* __restrict__ cval, const uint16_t* __restrict__ coff,
+                                           const uint32_t* __restrict__ counts, int g0, int gend, int gstep, int64_t d,
+                                           uint32_t lane, Body&& body) {
+  if (g0 >= gend) return;
+  int g = g0;
+  GroupHead a = group_load<OFF>(cval, coff, counts, g, d, lane);
+  for (;;) {
+    if (g + gstep >= gend) { body(a, g); break; }
+    const GroupHead b = group_load<OFF>(cval, coff, counts, g + gstep, d, lane);
+    body(a, g);
+    g += gstep;
+    if (g + gstep >= gend) { body(b, g); break; }
+    a = group_load<OFF>(cval, coff, counts, g + gstep, d, lane);
+    body(b, g);
+    g += gstep;
+  }
+}
+
+template <bool OFF, typename F>
+__device__ __forceinline__ void group_visit(const GroupHead& gh, const uint32_t* __restrict__ cval,
+                                            const uint16_t* __restrict__ coff, uint32_t lane, F&& f) {
 #pragma unroll
   for (int j = 0; j < kPre; ++j) {
-    if (64u * j < cnt) f(pre[j], lane + 64 * j < cnt);
+    if (64u * j < gh.cnt) f(gh.pv[j], gh.po[j], lane + 64 * j < gh.cnt);
   }
-  for (uint32_t e0 = 64 * kPre; e0 < cnt; e0 += 64) {
+  for (uint32_t e0 = 64 * kPre; e0 < gh.cnt; e0 += 64) {
     const uint32_t e = e0 + lane;
-    const bool valid = e < cnt;
-    f(valid ? cand[start + e] : make_uint2(0u, 0u), valid);
+    const bool valid = e < gh.cnt;
+    const uint32_t at = gh.start + ((e + gh.rot) & (uint32_t)(kWaveTile - 1));
+    f(valid ? cval[at] : 0u, (OFF && valid) ? (uint32_t)coff[at] : 0u, valid);
   }
 }
 
@@ -658,7 +744,8 @@ __global__ __launch_bounds__(kBlock) void k_gather(NodeSet ns) {
   const uint32_t lane = tid & 63;
   const int p = ns.lv.p;
   const size_t row = (size_t)node * (size_t)ns.d;
-  const uint2* __restrict__ cand = ns.cand + row;
+  const uint32_t* __restrict__ cval = ns.cand_val + row;
+  const uint16_t* __restrict__ coff = ns.cand_off + row;
   uint32_t* __restrict__ list = ns.glist + row;
   const uint32_t* __restrict__ counts = ns.grp_count + (size_t)node * ns.groups;
   uint32_t pre[P];
@@ -671,9 +758,9 @@ __global__ __launch_bounds__(kBlock) void k_gather(NodeSet ns) {
     for (uint32_t i = lane; i < held; i += 64) list[base + i] = buf[w][i];
     held = 0;
   };
-  for (int g = blockIdx.x * 4 + w; g < ns.groups; g += gridDim.x * 4) {
-    visit_group(cand, counts, g, ns.d, lane, [&](uint2 c, bool valid) {
-      const uint32_t key = c.y & 0x7FFFFFFFu;
+  for_groups<false>(cval, coff, counts, blockIdx.x * 4 + w, ns.groups, gridDim.x * 4, ns.d, lane, [&](const GroupHead& cur, int) {
+    group_visit<false>(cur, cval, coff, lane, [&](uint32_t vbits, uint32_t, bool valid) {
+      const uint32_t key = vbits & 0x7FFFFFFFu;
       const uint32_t bin = key >> kShift0;
       bool hit = false;
 #pragma unroll
@@ -691,7 +778,7 @@ __global__ __launch_bounds__(kBlock) void k_gather(NodeSet ns) {
         held += nhit;
       }
     });
-  }
+  });
   // one reservation per block for what the four wavefronts still hold
   if (lane == 0) s_held[w] = held;
   __syncthreads();
@@ -711,7 +798,8 @@ __global__ __launch_bounds__(kBlock) void k_gather(NodeSet ns) {
 // number of ties to take r_s, and the number of keys equal to T_s.
 // ---------------------------------------------------------------------------
 constexpr int kSelBlock = 1024;
-constexpr uint32_t kSelSmall = 1u << 18;   // lists up to this length are finished by one block
+constexpr uint32_t kSelSmall = 1u << 15;   // lists up to this length are finished by one block
+constexpr int kSelUnroll = 8;
 
 // counts, into an LDS histogram, the keys of list[begin, end) whose bits above `shift_hi`
 // equal `prefix`, binned by the nb-bin digit at `shift_lo` (16-byte loads when `vec`)
@@ -724,14 +812,23 @@ __device__ __forceinline__ void select_count(const uint32_t* __restrict__ list, 
   if (vec) {        // begin is a multiple of 4 and the row start is 16-byte aligned
     const uint4* __restrict__ l4 = reinterpret_cast<const uint4*>(list);
     const uint32_t e4 = (end + 3) / 4;
-    for (uint32_t i0 = begin / 4; i0 < e4; i0 += 2 * kSelBlock) {     // two 16-byte loads in flight per thread
-      const uint32_t ia = i0 + tid, ib = i0 + kSelBlock + tid;
-      uint4 ka = make_uint4(0, 0, 0, 0), kb = make_uint4(0, 0, 0, 0);
-      if (ia < e4) ka = l4[ia];
-      if (ib < e4) kb = l4[ib];
-      count(ka.x, 4 * ia + 0 < end); count(ka.y, 4 * ia + 1 < end); count(ka.z, 4 * ia + 2 < end); count(ka.w, 4 * ia + 3 < end);
-      count(kb.x, 4 * ib + 0 < end); count(kb.y, 4 * ib + 1 < end); count(kb.z, 4 * ib + 2 < end); count(kb.w, 4 * ib + 3 < end);
-    }
+    auto sweep = [&](uint32_t i0, auto unroll) {      // unroll 16-byte loads in flight per thread
+      constexpr int U = decltype(unroll)::value;
+      uint4 k[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t i = i0 + u * kSelBlock + tid;
+        k[u] = i < e4 ? l4[i] : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t i = i0 + u * kSelBlock + tid;
+        count(k[u].x, 4 * i + 0 < end); count(k[u].y, 4 * i + 1 < end); count(k[u].z, 4 * i + 2 < end); count(k[u].w, 4 * i + 3 < end);
+      }
+    };
+    uint32_t i0 = begin / 4;
+    for (; i0 + (kSelUnroll - 2) * kSelBlock < e4; i0 += kSelUnroll * kSelBlock) sweep(i0, std::integral_constant<int, kSelUnroll>());
+    for (; i0 < e4; i0 += 2 * kSelBlock) sweep(i0, std::integral_constant<int, 2>());
   } else {
     for (uint32_t i = begin + tid; i < end; i += kSelBlock) count(list[i], true);
   }
@@ -760,11 +857,12 @@ __device__ __forceinline__ void select_walk(uint32_t c, int nb, uint32_t rank, u
   __syncthreads();
 }
 
-// Short lists (the usual case): block z = 0 of the first launch does both digits on its own and
-// the second launch has nothing to do.  Long lists (a threshold bin that holds a large part of
-// the vector, e.g. many equal magnitudes): every launch does one digit; the gridDim.z blocks of a
-// (slot, node) share the list, add their LDS histograms into a global one, and the block that
-// arrives last walks it.
+// Lists of up to kSelSmall keys: block z = 0 of the first launch does both digits on its own and
+// the second launch has nothing to do.  Longer lists (up to the whole vector when a threshold
+// bin holds most of it, e.g. many equal magnitudes): every launch does one digit; one block per
+// kSelSmall keys (at most gridDim.z) of a (slot, node) shares the list, the blocks add their LDS
+// histograms into a global one, and the block that arrives last walks it.  Blocks without a
+// share exit at once.
 template <int STAGE>
 __global__ __launch_bounds__(kSelBlock) void k_select(NodeSet ns) {
   __shared__ uint32_t hist[kBins1];
@@ -778,6 +876,9 @@ __global__ __launch_bounds__(kSelBlock) void k_select(NodeSet ns) {
   const bool vec = (ns.d % 4) == 0;
   const bool small = L <= kSelSmall;
   if (small && (STAGE == 2 || z != 0)) return;
+  // longer lists are shared by one block per kSelSmall keys, as far as the launch has blocks
+  const uint32_t zn = min((uint32_t)gridDim.z, (L + kSelSmall - 1) / kSelSmall);
+  if (!small && (uint32_t)z >= zn) return;
   uint32_t prefix = ns.prefix[node * p + s];   // 12 bits known before stage 1, 22 before stage 2
   uint32_t rank = ns.rank[node * p + s];
   if (small) {
@@ -799,13 +900,13 @@ __global__ __launch_bounds__(kSelBlock) void k_select(NodeSet ns) {
     if (tid < 3) res[tid] = tid == 1 ? 1u : 0u;
     __syncthreads();
     // this block's share of the list, in whole 16-byte words
-    const uint32_t per = ((L + gridDim.z - 1) / gridDim.z + 3) & ~3u;
+    const uint32_t per = ((L + zn - 1) / zn + 3) & ~3u;
     const uint32_t begin = min(L, (uint32_t)z * per), end = min(L, begin + per);
     select_count(list, begin, end, vec, prefix, STAGE == 1 ? kShift0 : kShift1, STAGE == 1 ? kShift1 : 0, nb, hist);
     __syncthreads();
     uint32_t* gh = ns.sel_hist + ((size_t)node * p + s) * kBins1;
     if (tid < nb && hist[tid]) atomicAdd(&gh[tid], hist[tid]);
-    if (!arrive_last(&ns.sel_done[((size_t)node * p + s) * (kArriveFan + 1) * kCounterStride], gridDim.z, z, &s_flag))
+    if (!arrive_last(&ns.sel_done[((size_t)node * p + s) * (kArriveFan + 1) * kCounterStride], zn, z, &s_flag))
       return;
     uint32_t c = 0;
     if (tid < nb) {
@@ -852,7 +953,8 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
   const int GB = (groups + ns.G2 - 1) / ns.G2;
   const int lo = blockIdx.x * GB, hi = min(groups, lo + GB);
   const size_t row = (size_t)node * (size_t)ns.d;
-  const uint2* __restrict__ cand = ns.cand + row;
+  const uint32_t* __restrict__ cval = ns.cand_val + row;
+  const uint16_t* __restrict__ coff = ns.cand_off + row;
   uint32_t T[P], tg[P], te[P];
   double strict[P];
 #pragma unroll
@@ -863,12 +965,13 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
   }
   const uint32_t* __restrict__ counts = ns.grp_count + (size_t)node * groups;
   for (int g = lo + w; g < hi; g += 4) {
+    const GroupHead cur = group_load<false>(cval, coff, counts, g, ns.d, lane);
     uint32_t cg[P], ce[P];
 #pragma unroll
     for (int s = 0; s < P; ++s) cg[s] = ce[s] = 0;
-    visit_group(cand, counts, g, ns.d, lane, [&](uint2 c, bool valid) {
-      const uint32_t key = c.y & 0x7FFFFFFFu;
-      const double dv = (double)__uint_as_float(c.y);
+    group_visit<false>(cur, cval, coff, lane, [&](uint32_t vbits, uint32_t, bool valid) {
+      const uint32_t key = vbits & 0x7FFFFFFFu;
+      const double dv = (double)__uint_as_float(vbits);
       const double ev = dv * dv;
 #pragma unroll
       for (int s = 0; s < P; ++s) {
@@ -1001,7 +1104,8 @@ __global__ __launch_bounds__(kBlock) void k_compact(NodeSet ns, PassArgs a) {
   const int lo = blockIdx.x * GB, hi = min(groups, lo + GB);
   if (lo >= hi) return;
   const size_t row = (size_t)node * (size_t)ns.d;
-  const uint2* __restrict__ cand = ns.cand + row;
+  const uint32_t* __restrict__ cval = ns.cand_val + row;
+  const uint16_t* __restrict__ coff = ns.cand_off + row;
   float* __restrict__ h = a.h + row;
   int32_t* __restrict__ midx = ns.msg_idx + (size_t)node * ns.Kcap;
   float* __restrict__ mval = ns.msg_val + (size_t)node * ns.Kcap;
@@ -1024,21 +1128,24 @@ __global__ __launch_bounds__(kBlock) void k_compact(NodeSet ns, PassArgs a) {
     const int nchunk = min(64, hi - c0);
     for (int i = w; i < nchunk; i += 4) {
       const int g = c0 + i;
+      const GroupHead cur = group_load<true>(cval, coff, counts, g, ns.d, lane);
       uint32_t eqb = __shfl(eqb_l, i, 64);
       uint32_t out = __shfl(out_l, i, 64);
       if (lane == 0) ns.grp_off[(size_t)node * (groups + 1) + g] = out;
-      visit_group(cand, counts, g, ns.d, lane, [&](uint2 c, bool valid) {
-        const uint32_t key = c.y & 0x7FFFFFFFu;
+      const uint32_t gbase = (uint32_t)g * kWaveTile;
+      group_visit<true>(cur, cval, coff, lane, [&](uint32_t vbits, uint32_t off, bool valid) {
+        const uint32_t key = vbits & 0x7FFFFFFFu;
         const bool eq = valid && key == T;
         const uint64_t beq = ballot(eq);
         const bool tk = valid && (key > T || (eq && eqb + below(beq) < r));
         const uint64_t bt = ballot(tk);
         if (tk) {
           const uint32_t pos = out + below(bt);
-          const float val = __uint_as_float(c.y);
-          midx[pos] = (int32_t)c.x;
+          const float val = __uint_as_float(vbits);
+          const uint32_t l = gbase + off;
+          midx[pos] = (int32_t)l;
           mval[pos] = val;
-          h[c.x] = h[c.x] + val;
+          h[l] = h[l] + val;
         }
         eqb += popc64(beq);
         out += popc64(bt);
