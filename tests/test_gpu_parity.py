@@ -470,3 +470,61 @@ def test_overlap_mode_gives_identical_results(mode):
         assert np.array_equal(bits(outs[1][1]), bits(orc.x))
         assert np.array_equal(bits(outs[1][4]), bits(orc.gi))
         assert outs[1][7].tolist() == orc.level_hist_w.tolist()
+
+
+def _run_external(n, d, wl, zw, ml, zm, steps, seed, tag):
+    """Drives engine and oracle with the same supplied gradients and compares every step."""
+    E = _eng()
+    rng = np.random.default_rng(seed)
+    grads = [rng.standard_normal((n, d)).astype(np.float32)]
+    for t in range(steps):      # drifting gradients whose step-to-step change varies over two decades
+        s = np.float32(10.0 ** rng.uniform(-2, 0))
+        grads.append((grads[-1] + s * rng.standard_normal((n, d))).astype(np.float32))
+    x0 = rng.standard_normal(d).astype(np.float32)
+    orc = O.AdaCGDOracle(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zw, master_levels=ml, zeta_master=zm)
+    orc.init(x0, grads[0], O.INIT_FULLGRAD)
+    eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zw, master_levels=ml, zeta_master=zm,
+                   grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=_cuda(grads[0]))
+    mlev = []
+    for t in range(1, steps + 1):
+        res, rm = orc.step(grads=grads[t])
+        eng.step(_cuda(grads[t]))
+        if rm is not None and rm.margins and min(rm.margins) < 1e-12:
+            pytest.skip("a master trigger comparison is within 1e-12 of equality")
+        compare_step(eng, orc, res, rm, (tag, t))
+        if rm is not None:
+            mlev.append(rm.level)
+    hist_w = eng.state(E.F_LEVEL_HIST)
+    assert hist_w.tolist() == orc.level_hist_w.tolist()
+    eng.close()
+    return orc, mlev
+
+
+@pytest.mark.parametrize("zm", [0.3, 1.0, 4.0])
+def test_adaptive_master_bit_exact(zm):
+    """Server-side adaptive compressor (Corollary on bidirectional Ada3PC, Section 4.3): several
+    master levels with a positive trigger constant, including steps where the master sends
+    nothing.  Every master decision, message and the broadcast estimator g match the oracle."""
+    n, d = 3, 3 * 8192 + 516
+    wl = [(O.TOPK, 8), (O.TOPK, 300), (O.TOPK, 4000), (O.TOPK, d // 2)]
+    ml = [(O.TOPK, 4), (O.TOPK, 120), (O.QUANT, 4), (O.TOPK, 2500), (O.TOPK, d)]
+    orc, mlev = _run_external(n, d, wl, 1.5, ml, zm, 8, 77, ("ada-master", zm))
+    assert len(set(mlev)) >= 2, mlev          # the master did adapt over the run
+    assert orc.level_hist_m.sum() == 8
+
+
+@pytest.mark.parametrize("name", ["gd", "ef21_top1", "clag", "lag"])
+def test_special_cases_bit_exact(name):
+    """The methods AdaCGD reduces to (Section 4.3: one level -> CLAG, zeta = 0 -> EF21,
+    identity level -> LAG / plain GD) run through the same kernels and match the oracle."""
+    n, d = 3, 2 * 8192 + 516
+    wl, zw = {"gd": ([(O.TOPK, d)], 0.0), "ef21_top1": ([(O.TOPK, 1)], 0.0),
+              "clag": ([(O.TOPK, 200)], 1.5), "lag": ([(O.TOPK, d)], 1.5)}[name]
+    ml = [(O.TOPK, d)]                         # identity on the server: unidirectional compression
+    orc, _ = _run_external(n, d, wl, zw, ml, 0.0, 6, 5, name)
+    if name == "gd":                           # every worker sends everything at every step
+        assert orc.level_hist_w.tolist() == [0, 6 * n]
+    if name == "ef21_top1":
+        assert orc.level_hist_w.tolist() == [0, 6 * n]
+    if name in ("clag", "lag"):
+        assert orc.level_hist_w[0] > 0          # some communications were skipped
