@@ -806,8 +806,19 @@ constexpr int kSelUnroll = 8;
 __device__ __forceinline__ void select_count(const uint32_t* __restrict__ list, uint32_t begin, uint32_t end, bool vec,
                                              uint32_t prefix, int shift_hi, int shift_lo, int nb, uint32_t* hist) {
   const uint32_t tid = threadIdx.x;
+  // consecutive keys of a thread that fall into the same bin are counted with one atomic: lists
+  // made of one repeated key (all zeros, say) would otherwise serialise on a single LDS word
+  uint32_t run_bin = 0, run_len = 0;
   auto count = [&](uint32_t key, bool ok) {
-    if (ok && (key >> shift_hi) == prefix) atomicAdd(&hist[(key >> shift_lo) & (nb - 1)], 1u);
+    if (ok && (key >> shift_hi) == prefix) {
+      const uint32_t b = (key >> shift_lo) & (nb - 1);
+      if (b != run_bin && run_len) {
+        atomicAdd(&hist[run_bin], run_len);
+        run_len = 0;
+      }
+      run_bin = b;
+      ++run_len;
+    }
   };
   if (vec) {        // begin is a multiple of 4 and the row start is 16-byte aligned
     const uint4* __restrict__ l4 = reinterpret_cast<const uint4*>(list);
@@ -832,6 +843,7 @@ __device__ __forceinline__ void select_count(const uint32_t* __restrict__ list, 
   } else {
     for (uint32_t i = begin + tid; i < end; i += kSelBlock) count(list[i], true);
   }
+  if (run_len) atomicAdd(&hist[run_bin], run_len);
 }
 
 // walks nb <= 1024 bin counts from the top (thread t holds the count of bin nb-1-t) and finds
