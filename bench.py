@@ -90,6 +90,36 @@ def extra_federated(E, W, torch, n, steps=10, warmup=2):
             "note": "one stream, HIP events around every kernel"}
 
 
+def extra_small_logistic(E, W, torch, wl, steps):
+    """Launch-bound small configurations: steps per second and kernel launches per step only."""
+    A, labels = torch.from_numpy(wl.A).cuda(), torch.from_numpy(wl.labels).cuda()
+    x0 = torch.zeros(wl.d, dtype=torch.float32, device="cuda")
+    kw = dict(n=wl.n, d=wl.d, gamma=wl.gamma, lam=wl.lam, worker_levels=wl.worker_levels,
+              zeta_worker=wl.zeta_worker, master_levels=wl.master_levels, zeta_master=wl.zeta_master,
+              grad_mode=E.GRAD_LOGISTIC, A=A, labels=labels, shard_offsets=wl.shard_offsets, x0=x0)
+    eng = E.AdaCGD(flags=0, **kw)
+    eng.step(nsteps=10)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    eng.step(nsteps=steps)                 # one call enqueues all steps: no Python in the loop
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    hist = eng.state(E.F_LEVEL_HIST).astype(np.int64)
+    eng.close()
+    eng = E.AdaCGD(flags=E.FLAG_KERNEL_TIMING, **kw)     # second engine only to count the launches of a step
+    eng.step(nsteps=5)
+    torch.cuda.synchronize()
+    km = eng.kernel_ms()                   # one timed slot per launch, except select (two launches per slot)
+    launches = (sum(cnt for _, cnt in km.values()) + km["w_select"][1] + km["m_select"][1]) / 5.0
+    eng.close()
+    return {"workload": "%s: n=%d, d=%d, %d samples each, logistic regression, levels %s"
+                        % (wl.name, wl.n, wl.d, wl.A.shape[0] // wl.n, [k for _, k in wl.worker_levels]),
+            "steps": steps, "ms_per_step": dt / steps * 1e3, "steps_per_sec": steps / dt,
+            "kernel_launches_per_step": launches,
+            "level_histogram_skip_then_levels_since_init": [int(v) for v in hist],
+            "note": "launch/latency-bound: no roofline applies"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -180,6 +210,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "+".join(group), "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+        "traffic_GBps": traffic / (group_ms * 1e-3) / 1e9 if traffic else None,
         "algorithmic_bytes_per_step": alg_bytes_step, "avg_ms_per_step": group_ms,
         "dominant_kernel": {"name": dom, "avg_ms": per_kernel[dom]["avg_ms"],
                             "bytes_read_per_launch": dom_bytes,
@@ -208,6 +239,8 @@ def main():
     if not args.no_extras:
         other.append(extra_kernel_stress(E, W, torch))
         other.append(extra_federated(E, W, torch, args.federated_n))
+        other.append(extra_small_logistic(E, W, torch, W.tiny(), 1000))
+        other.append(extra_small_logistic(E, W, torch, W.sparse_logreg(), 1000))
 
     out = {
         "metric": "adacgd_compressed_floats_per_sec", "value": floats_per_s, "unit": "floats/s",

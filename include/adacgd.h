@@ -181,7 +181,7 @@ enum adacgd_kernel {
   ADACGD_K_GRAD_MARGIN = 1,
   ADACGD_K_GRAD_COLS = 2,
   ADACGD_K_AGGREGATE = 3,
-  ADACGD_K_W_SAMPLE = 4,   /* histogram of a 1/32 sample: candidate cut-off estimate          */
+  ADACGD_K_W_SAMPLE = 4,   /* histogram of a sample of the vector: candidate cut estimate     */
   ADACGD_K_W_SCAN = 5,     /* differences, norms, first-digit histogram (+ candidates)        */
   ADACGD_K_W_FILTER = 6,   /* candidate extraction, low-band energy, quantiser errors         */
   ADACGD_K_W_GATHER = 7,   /* keys inside the threshold bins -> one list per worker           */

@@ -6,12 +6,13 @@
 
 namespace adacgd {
 
-// Tiling of a length-d vector.  A tile is the unit of candidate grouping:
-// candidates of one tile are stored contiguously and in ascending coordinate.
+// Tiling of a length-d vector.  A block works on tiles; each of its four wavefronts owns a
+// contiguous quarter of the tile, a "group", whose candidates are stored together in
+// ascending coordinate.
 constexpr int kBlock = 256;             // threads per block (4 wavefronts of 64)
 constexpr int kIter = 8;                // 16-byte loads per thread per tile
 constexpr int kTile = kIter * kBlock * 4;   // 8192 coordinates
-constexpr int kWaveTile = kTile / 4;    // contiguous share of one wavefront
+constexpr int kWaveTile = kTile / 4;    // coordinates per group
 
 // Radix digits of the 31-bit magnitude key (bit pattern of |v|), most significant first.
 constexpr int kShift0 = 19, kBins0 = 4096;  // sign-less exponent + 4 mantissa bits
