@@ -1323,7 +1323,10 @@ hipError_t launch_compact(const NodeSet& ns, const PassArgs& a, hipStream_t st) 
 hipError_t launch_qapply(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
   if (ns.lv.nq == 0) return hipSuccess;
-  const dim3 grid(ns.G, ns.nn), block(kBlock);
+  // no per-block set-up or reduction here: about 8192 short blocks in all
+  int gx = (8192 + ns.nn - 1) / ns.nn;
+  if (gx > ns.tiles) gx = ns.tiles;
+  const dim3 grid(gx, ns.nn), block(kBlock);
   const bool v = vec_ok(ns, a);
   if (a.diff) {
     if (v) hipLaunchKernelGGL((k_qapply<true, true>), grid, block, 0, st, ns, a);
