@@ -376,9 +376,14 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
   __shared__ uint32_t lds4[4];
   __shared__ int s_flag;
   __shared__ uint32_t s_rank[kMaxLevels], s_bin[kMaxLevels], s_rk[kMaxLevels], s_cnt[kMaxLevels];
-  constexpr int kStage = 512;            // staged candidates per wavefront (an iteration adds at most 256)
+  // Candidates are staged in LDS per wavefront and written to memory when the block has finished
+  // its tiles (earlier only if the stage fills up): a store issued between the loads makes the
+  // next wait for a load wait for everything outstanding, which drains the wavefront's pipeline.
+  constexpr int kStage = 768;            // staged candidates per wavefront (an iteration adds at most 256)
+  constexpr int kSeg = 8;                // ... belonging to at most kSeg groups
   __shared__ uint32_t st_val[4][kStage];
   __shared__ uint16_t st_off[4][kStage];
+  __shared__ uint32_t sg_grp[4][kSeg], sg_end[4][kSeg], sg_base[4][kSeg];
 
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int64_t d = ns.d;
@@ -396,25 +401,43 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
 
   double S = 0.0, D = 0.0, El = 0.0;
   uint32_t ncand = 0;
-  for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
-    const int64_t base = (int64_t)t * kTile;
-    const int grp = t * 4 + w;
-    uint32_t* __restrict__ sval = cval + (size_t)grp * kWaveTile;
-    uint16_t* __restrict__ soff = coff + (size_t)grp * kWaveTile;
-    const uint32_t rot = group_rot(grp, d);
-    // candidates are staged in LDS and written out at the end of the tile (earlier only when a
-    // dense group fills the stage): stores issued between the loads of a tile would make every
-    // wait for a load also wait for the stores before it
-    uint32_t held = 0, running = 0;      // the group holds running + held candidates
-    auto flush = [&]() {
-      for (uint32_t e = lane; e < held; e += 64) {
-        const uint32_t at = (running + e + rot) & (uint32_t)(kWaveTile - 1);
+  // stage bookkeeping (all values are the same in every lane of the wavefront; every lane writes
+  // and reads the segment table itself, so no lane depends on another's LDS write)
+  uint32_t held = 0;        // entries in the stage
+  uint32_t nseg = 0;        // closed segments: group sg_grp, entries [previous end, sg_end), first entry
+                            // is the group's entry number sg_base
+  uint32_t open_base = 0;   // entries of the open group that were written out already
+  uint32_t open_begin = 0;  // stage index where the open group's entries start
+  // writes segments [0, nseg) and, if `open_grp` >= 0, the open group's staged entries
+  auto flush = [&](int open_grp) {
+    uint32_t begin = 0;
+    const uint32_t total = nseg + (open_grp >= 0 ? 1u : 0u);
+    for (uint32_t sgi = 0; sgi < total; ++sgi) {
+      const bool closed = sgi < nseg;
+      const uint32_t grp = closed ? sg_grp[w][sgi] : (uint32_t)open_grp;
+      const uint32_t end = closed ? sg_end[w][sgi] : held;
+      const uint32_t gbase = closed ? sg_base[w][sgi] : open_base;
+      uint32_t* __restrict__ sval = cval + (size_t)grp * kWaveTile;
+      uint16_t* __restrict__ soff = coff + (size_t)grp * kWaveTile;
+      const uint32_t rot = group_rot((int)grp, d);
+      for (uint32_t e = begin + lane; e < end; e += 64) {
+        const uint32_t at = (gbase + (e - begin) + rot) & (uint32_t)(kWaveTile - 1);
         sval[at] = st_val[w][e];
         soff[at] = st_off[w][e];
       }
-      running += held;
-      held = 0;
-    };
+      if (closed && lane == 0 && (int)grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = gbase + (end - begin);
+      if (!closed) open_base = gbase + (end - begin);
+      begin = end;
+    }
+    nseg = 0;
+    held = 0;
+    open_begin = 0;
+  };
+  for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
+    const int64_t base = (int64_t)t * kTile;
+    const int grp = t * 4 + w;
+    open_base = 0;
+    open_begin = held;
 #pragma unroll
     for (int k = 0; k < kIter; ++k) {
       const int64_t l0 = comp0<VEC>(base, w, lane, k);
@@ -446,13 +469,18 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
           }
         }
       }
-      if (held > (uint32_t)(kStage - 256)) flush();
+      if (held > (uint32_t)(kStage - 256)) flush(grp);         // rare: dense groups
       emit4<VEC>(f, vv, (uint32_t)(l0 - base) - (uint32_t)w * kWaveTile, st_val[w], st_off[w], 0u, held);
     }
-    flush();
-    if (lane == 0 && grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = running;
-    ncand += running;
+    // close the group's segment
+    sg_grp[w][nseg] = (uint32_t)grp;
+    sg_end[w][nseg] = held;
+    sg_base[w][nseg] = open_base;
+    ncand += open_base + (held - open_begin);
+    ++nseg;
+    if (nseg == (uint32_t)kSeg) flush(-1);
   }
+  flush(-1);
   S = block_sum(S, red);
   D = block_sum(D, red);
   El = block_sum(El, red);
