@@ -147,7 +147,9 @@ enum adacgd_field {
   ADACGD_F_LEVEL = 6,        /* int32  [n]     level of the last step: 0 = skip, 1..m         */
   ADACGD_F_SQNORM = 7,       /* double [n]     ||x-h||^2 of the last step                     */
   ADACGD_F_D = 8,            /* double [n]     ||x-y||^2 of the last step                     */
-  ADACGD_F_ERR = 9,          /* double [n x m_worker] realised error of every level           */
+  ADACGD_F_ERR = 9,          /* double [n x m_worker] realised error of every level; NaN in the
+                                rows of workers that skipped (level 0): the cascade stops at
+                                its first condition and their errors are not evaluated       */
   ADACGD_F_MSG_COUNT = 10,   /* int64  [n]     entries of each worker's last Top-K message    */
   ADACGD_F_MSG_IDX = 11,     /* int32  [sum counts] coordinates, ascending per worker, packed */
   ADACGD_F_MSG_VAL = 12,     /* float  [sum counts] values, packed in the same order          */

@@ -124,6 +124,7 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.amax = c.take<uint32_t>(nn);
   ns.best = c.take<uint32_t>(nn);
   ns.redo = c.take<uint32_t>(nn);
+  ns.skip = c.take<uint32_t>(nn);
   ns.partS = c.take<double>(nn * ns.G);
   ns.partD = c.take<double>(nn * ns.G);
   ns.partEb = c.take<double>(nn * ns.G);

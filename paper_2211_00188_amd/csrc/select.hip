@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
   __shared__ uint32_t s_rank[kMaxLevels], s_bin[kMaxLevels], s_rk[kMaxLevels], s_cnt[kMaxLevels];
 
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-  if (REPAIR && ns.redo[node] == 0) return;
+  if (REPAIR && (ns.redo[node] == 0 || ns.skip[node] != 0)) return;
   const int64_t d = ns.d;
   const size_t row = (size_t)node * (size_t)d;
   const float* __restrict__ x = a.x + row;
@@ -263,7 +263,11 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
   }
   if (tid == 0) {
     ns.S[node] = s;
-    ns.D[node] = DIFF ? a.extD[node] : dd;
+    const double dnode = DIFF ? a.extD[node] : dd;
+    ns.D[node] = dnode;
+    // first condition of the cascade: the trigger keeps h, and nothing after this kernel has work
+    // to do for the node (the tally kernel takes the same decision from the same two numbers)
+    ns.skip[node] = s <= ns.lv.zeta * dnode ? 1u : 0u;
     ns.bmin[node] = p > 0 ? s_bin[p - 1] : (uint32_t)kBins0;   // largest K reaches lowest
     if (ns.lv.nq > 0) {
       ns.amax[node] = ld_coherent(&ns.kmax[node]);
@@ -521,7 +525,11 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
   }
   if (tid == 0) {
     ns.S[node] = s;
-    ns.D[node] = DIFF ? a.extD[node] : dd;
+    const double dnode = DIFF ? a.extD[node] : dd;
+    ns.D[node] = dnode;
+    // first condition of the cascade: the trigger keeps h, and nothing after this kernel has work
+    // to do for the node (the tally kernel takes the same decision from the same two numbers)
+    ns.skip[node] = s <= ns.lv.zeta * dnode ? 1u : 0u;
     ns.Eb[node] = el;
     // the K largest all have keys >= cut  <=>  at least K candidates were found
     const uint32_t total = ld_coherent(&ns.ncand[(size_t)node * kCounterStride]);
@@ -575,7 +583,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   __shared__ int s_flag;
 
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-  if (REPAIR && ns.redo[node] == 0) return;
+  if (ns.skip[node] != 0 || (REPAIR && ns.redo[node] == 0)) return;   // skipping nodes need no candidates
   const int64_t d = ns.d;
   const int nq = ns.lv.nq;
   const size_t row = (size_t)node * (size_t)d;
@@ -769,6 +777,7 @@ template <int P>
 __global__ __launch_bounds__(kBlock) void k_gather(NodeSet ns) {
   __shared__ uint32_t buf[4][kGatherCap];
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6;
+  if (ns.skip[node] != 0) return;
   const uint32_t lane = tid & 63;
   const int p = ns.lv.p;
   const size_t row = (size_t)node * (size_t)ns.d;
@@ -910,6 +919,7 @@ __global__ __launch_bounds__(kSelBlock) void k_select(NodeSet ns) {
   __shared__ uint32_t res[3];
   __shared__ int s_flag;
   const int s = blockIdx.x, node = blockIdx.y, z = blockIdx.z, tid = threadIdx.x;
+  if (ns.skip[node] != 0) return;
   const int p = ns.lv.p;
   const uint32_t* __restrict__ list = ns.glist + (size_t)node * (size_t)ns.d;
   const uint32_t L = ns.gcur[(size_t)node * kCurStride];
@@ -1004,7 +1014,8 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
     tg[s] = te[s] = 0;
   }
   const uint32_t* __restrict__ counts = ns.grp_count + (size_t)node * groups;
-  for (int g = lo + w; g < hi; g += 4) {
+  const bool skip = ns.skip[node] != 0;         // the node keeps h: no candidates were extracted
+  for (int g = lo + w; g < (skip ? lo : hi); g += 4) {
     const GroupHead cur = group_load<false>(cval, coff, counts, g, ns.d, lane);
     uint32_t cg[P], ce[P];
 #pragma unroll
@@ -1068,7 +1079,9 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
     const double tau = lv.zeta * D;
     double err[kMaxLevels];
     for (int j = 0; j < lv.m; ++j) {
-      if (lv.kind[j] == kTopK) {
+      if (skip) {
+        err[j] = __longlong_as_double(0x7FF8000000000000ll);    // not evaluated: the cascade stopped before
+      } else if (lv.kind[j] == kTopK) {
         const int s = lv.ref[j];
         const double tv = (double)__uint_as_float(ns.prefix[node * p + s]);
         const double left = (double)(ns.eqcnt[node * p + s] - ns.rank[node * p + s]);   // ties not taken
