@@ -537,3 +537,69 @@ def test_special_cases_bit_exact(name):
         assert orc.level_hist_w.tolist() == [0, 6 * n]
     if name in ("clag", "lag"):
         assert orc.level_hist_w[0] > 0          # some communications were skipped
+
+
+def test_largest_dimension_properties():
+    """d just above 2^30 (every per-worker array crosses 4 GiB), one worker, one step.  The oracle's
+    full sort is out of reach at this size, so what is unique about the result is checked
+    instead, with torch reductions on the device: the message is the exact Top-K support (sorted,
+    K entries, values equal to v there, nothing outside exceeds the smallest value inside), the
+    estimator is h + C(v) bit for bit, and S, D and the chosen level's error match fp64 sums."""
+    E = _eng()
+    import torch
+    d = (1 << 30) + 3 * 8192 + 4
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20221100188)
+    g0 = torch.randn(1, d, dtype=torch.float32, device="cuda", generator=gen)
+    g1 = g0 + 0.3 * torch.randn(1, d, dtype=torch.float32, device="cuda", generator=gen)
+    wl = [(O.TOPK, 16), (O.TOPK, d // 1000), (O.TOPK, d // 50)]
+    zeta = 0.5
+    x0 = torch.zeros(d, dtype=torch.float32, device="cuda")
+    KM = d // 400
+    eng = E.AdaCGD(n=1, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zeta, master_levels=[(O.TOPK, KM)],
+                   zeta_master=0.0, grad_mode=E.GRAD_EXTERNAL, init_mode=E.INIT_ZERO, x0=x0, grad0=g0,
+                   flags=E.FLAG_RETAIN_EXT)
+    eng.step(g1)
+    lev = int(eng.state(E.F_LEVEL)[0])
+    S, D, err = eng.state(E.F_SQNORM)[0], eng.state(E.F_D)[0], eng.state(E.F_ERR)[0]
+    v = g1[0]                                    # h = 0: the compressor's argument is the gradient itself
+    S_ref = float(torch.sum(v.double() ** 2))
+    D_ref = float(torch.sum((g1[0].double() - g0[0].double()) ** 2))
+    assert abs(S - S_ref) <= 1e-10 * S_ref and abs(D - D_ref) <= 1e-10 * D_ref
+    assert lev >= 1 and S > zeta * D
+    assert np.all(np.diff(err) <= 0)             # larger K, smaller error
+    for j in range(1, lev):
+        assert err[j - 1] > zeta * D             # the cascade went past these levels
+    assert lev == len(wl) or err[lev - 1] <= zeta * D
+    K = wl[lev - 1][1]
+    idx, val = eng.messages()[0]
+    assert len(idx) == K and np.all(np.diff(idx) > 0) and idx[0] >= 0 and idx[-1] < d
+    tidx = torch.from_numpy(idx.astype(np.int64)).cuda()
+    tval = torch.from_numpy(val).cuda()
+    assert torch.equal(v[tidx].view(torch.int32), tval.view(torch.int32))
+    rest = v.abs()
+    rest[tidx] = 0
+    assert float(rest.max()) <= float(tval.abs().min())
+    sent = float(torch.sum(tval.double() ** 2))
+    assert abs(err[lev - 1] - (S_ref - sent)) <= 1e-9 * S_ref
+    expect = torch.zeros(d, dtype=torch.float32, device="cuda")
+    expect[tidx] = tval
+    del rest
+    gi = torch.from_numpy(eng.state(E.F_GI)[0]).cuda()
+    assert torch.equal(gi.view(torch.int32), expect.view(torch.int32))
+    del gi
+    # server: with one worker and zero initial estimators g~ = the message, and the master sends
+    # the Top-KM entries of it (g = 0 before): a subset of the worker's message
+    assert np.array_equal(bits(eng.state(E.F_GTILDE)), bits(expect.cpu().numpy()))
+    midx, mval = eng.state(E.F_M_MSG_IDX), eng.state(E.F_M_MSG_VAL)
+    assert int(eng.state(E.F_M_LEVEL)[0]) == 1 and len(midx) == KM and np.all(np.diff(midx) > 0)
+    tm = torch.from_numpy(midx.astype(np.int64)).cuda()
+    tmv = torch.from_numpy(mval).cuda()
+    assert torch.equal(expect[tm].view(torch.int32), tmv.view(torch.int32))
+    rest = expect.abs()
+    rest[tm] = 0
+    assert float(rest.max()) <= float(tmv.abs().min())
+    g = torch.zeros(d, dtype=torch.float32, device="cuda")
+    g[tm] = tmv
+    assert np.array_equal(bits(eng.state(E.F_G)), bits(g.cpu().numpy()))
+    eng.close()
