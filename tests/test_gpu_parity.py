@@ -603,3 +603,13 @@ def test_largest_dimension_properties():
     g[tm] = tmv
     assert np.array_equal(bits(eng.state(E.F_G)), bits(g.cpu().numpy()))
     eng.close()
+
+
+def test_many_workers_small_dimension():
+    """n in the thousands (one grid row per worker), d below one wavefront's share: every kernel's
+    per-node bookkeeping at the other extreme of the shapes."""
+    n, d = 3000, 130
+    wl = [(O.TOPK, 1), (O.TOPK, 13), (O.TOPK, 65), (O.QUANT, 4), (O.TOPK, d)]
+    ml = [(O.TOPK, 7), (O.TOPK, 40)]
+    orc, _ = _run_external(n, d, wl, 1.2, ml, 0.7, 3, 11, "many-workers")
+    assert (orc.level_hist_w > 0).sum() >= 3
