@@ -79,7 +79,7 @@ def extra_federated(E, W, torch, n, steps=10, warmup=2):
     eng.close()
     a_bytes = float(wl.A.nbytes)
     grad_ms = kms.get("grad_margin", 0.0) + kms.get("grad_cols", 0.0)
-    return {"workload": "federated logistic regression: n=%d workers (1000 in the full form), d=%d, %d samples each, "
+    return {"workload": "federated logistic regression: n=%d workers, d=%d, %d samples each, "
                         "levels %s, master Top-%d" % (wl.n, wl.d, wl.A.shape[0] // wl.n, wl.worker_levels,
                                                       wl.master_levels[0][1]),
             "steps": steps, "ms_per_step": dt / steps * 1e3, "floats_per_sec": wl.n * wl.d * steps / dt,
