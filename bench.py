@@ -131,8 +131,8 @@ def main():
     ap.add_argument("--d", type=int, default=11_200_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary workloads")
-    ap.add_argument("--federated-n", type=int, default=250,
-                    help="workers of the secondary federated workload (1000 in its full form)")
+    ap.add_argument("--federated-n", type=int, default=1000,
+                    help="workers of the secondary federated workload (1000 = the full configuration, 8.4 GB of features)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="run the worker and server chains on one stream (the kernel-timing pass always does)")
     args = ap.parse_args()
