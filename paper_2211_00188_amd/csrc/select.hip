@@ -16,15 +16,17 @@
 // One-pass sequence (Top-K levels only, long vectors):
 //   sample  : one block per node histograms a sample of the vector and derives a
 //             conservative candidate cut (a key) for the largest Top-K size
-//   scanx   : v = x - h, S = ||v||^2, D = ||x - y||^2, candidates with key >= cut, their
-//             first-digit histogram and count, the energy below the cut
+//   scanx   : v = x - h, S = ||v||^2, D = ||x - y||^2, candidates with key >= cut (staged in
+//             LDS, written out when the block has finished its tiles), their first-digit
+//             histogram and count, the energy below the cut
 //             epilogue: first digit (bin) and in-bin rank of each Top-K size; marks the node
-//             for repair if fewer candidates than the largest K were found
+//             for repair if fewer candidates than the largest K were found, and as skipping
+//             if S <= zeta D (then every later kernel returns at once for that node)
 //   scan + filter (repair variants): idle unless a node is marked; then they redo the
 //             node in two passes
 // Two-pass sequence (level sets with quantisers, short vectors):
 //   scan    : v, S, D, full first-digit histogram, max |v|
-//             epilogue: bin and in-bin rank of each Top-K size, candidate cut-off bin
+//             epilogue: bin and in-bin rank of each Top-K size, candidate cut-off bin, skip mark
 //   filter  : re-forms v, candidates = keys in bins >= cut-off, energy below, realised
 //             error of every quantiser level (Philox dither)
 // Then, both sequences:

@@ -97,38 +97,48 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
     if (base + c < d) gt_new[base + c] = (float)((double)gt_old[base + c] + acc[c] / n);
 }
 
-// Dense (quantised) messages: a block owns 128 coordinates, each lane two of them; the four
-// wavefronts take one quarter of the workers each, in ascending order, and their partial sums are
-// combined in wavefront order: g~_new = fl(g~_old + (sparse sums + dense sums) / n).
+// Dense (quantised) messages: a block owns 128 coordinates, each lane two of them (one 4-byte
+// load per worker); its eight wavefronts take one eighth of the workers each, in ascending order,
+// eight workers' loads in flight at a time, and their partial sums are combined in wavefront
+// order: g~_new = fl(g~_old + (sparse sums + dense sums) / n).
 constexpr int kDenseCols = 128;
-__global__ __launch_bounds__(kBlock) void k_aggregate_dense(NodeSet ws, const float* __restrict__ gt_old,
-                                                             float* __restrict__ gt_new) {
-  __shared__ double part[4][kDenseCols];
+constexpr int kDenseWaves = 8;
+__global__ __launch_bounds__(64 * kDenseWaves) void k_aggregate_dense(NodeSet ws, const float* __restrict__ gt_old,
+                                                                      float* __restrict__ gt_new) {
+  __shared__ double part[kDenseWaves][kDenseCols];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int64_t d = ws.d;
   const int64_t c0 = (int64_t)blockIdx.x * kDenseCols + 2 * lane;
   const bool ok0 = c0 < d, ok1 = c0 + 1 < d;
-  const int q = (ws.nn + 3) / 4;
+  const bool pair = ok1 && (d % 2 == 0);       // rows are then 4-byte aligned at c0
+  const int q = (ws.nn + kDenseWaves - 1) / kDenseWaves;
   const int i0 = w * q, i1 = min(ws.nn, i0 + q);
   double a0 = 0.0, a1 = 0.0;
   auto decode = [](int code, float sc) {
     const float mag = (float)(code < 0 ? -code : code) * sc;
     return (double)(code < 0 ? -mag : mag);
   };
-  for (int i = i0; i < i1; i += 4) {          // four workers' loads in flight
-    int k0[4], k1[4];
-    float sc[4];
+  constexpr int U = 8;
+  for (int i = i0; i < i1; i += U) {
+    int k0[U], k1[U];
+    float sc[U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int ii = i + u;
       const bool dense = ii < i1 && ws.sel_q[ii] >= 0;
       sc[u] = dense ? ws.qscale[ii] : 0.f;
       const int16_t* __restrict__ codes = ws.qcodes + (size_t)(dense ? ii : 0) * d;
-      k0[u] = (dense && ok0) ? (int)codes[c0] : 0;
-      k1[u] = (dense && ok1) ? (int)codes[c0 + 1] : 0;
+      if (pair) {
+        const uint32_t two = dense ? *reinterpret_cast<const uint32_t*>(codes + c0) : 0u;
+        k0[u] = (int)(int16_t)(two & 0xFFFFu);
+        k1[u] = (int)(int16_t)(two >> 16);
+      } else {
+        k0[u] = (dense && ok0) ? (int)codes[c0] : 0;
+        k1[u] = (dense && ok1) ? (int)codes[c0 + 1] : 0;
+      }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
       a0 += decode(k0[u], sc[u]);
       a1 += decode(k1[u], sc[u]);
     }
@@ -139,7 +149,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_dense(NodeSet ws, const fl
   if (tid < kDenseCols) {
     const int64_t c = (int64_t)blockIdx.x * kDenseCols + tid;
     if (c < d) {
-      const double tot = ws.accbuf[c] + (((part[0][tid] + part[1][tid]) + part[2][tid]) + part[3][tid]);
+      double tot = ws.accbuf[c];
+#pragma unroll
+      for (int j = 0; j < kDenseWaves; ++j) tot += part[j][tid];
       gt_new[c] = (float)((double)gt_old[c] + tot / (double)ws.nn);
     }
   }
@@ -256,7 +268,7 @@ hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_ne
   hipLaunchKernelGGL((k_aggregate<true>), dim3(ws.groups), dim3(kBlock), 0, st, ws, gt_old, gt_new);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_aggregate_dense, dim3((unsigned)((ws.d + kDenseCols - 1) / kDenseCols)), dim3(kBlock), 0, st, ws,
+  hipLaunchKernelGGL(k_aggregate_dense, dim3((unsigned)((ws.d + kDenseCols - 1) / kDenseCols)), dim3(64 * kDenseWaves), 0, st, ws,
                      gt_old, gt_new);
   return hipGetLastError();
 }
