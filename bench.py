@@ -160,6 +160,8 @@ def main():
         pool.append(torch.from_numpy(a).cuda())
     x0 = torch.zeros(d, dtype=torch.float32, device="cuda")
 
+    repairs = []
+
     def run(flags, steps, warmup):
         eng = E.AdaCGD(n=n, d=d, gamma=0.1, worker_levels=wk.worker_levels, zeta_worker=wk.zeta_worker,
                        master_levels=wk.master_levels, zeta_master=wk.zeta_master, grad_mode=E.GRAD_EXTERNAL,
@@ -181,6 +183,7 @@ def main():
         dt = time.perf_counter() - t0
         hist = eng.state(E.F_LEVEL_HIST).astype(np.int64) - h0
         kms = eng.kernel_ms() if flags & E.FLAG_KERNEL_TIMING else None
+        repairs.append([int(v) for v in eng.state(E.F_REPAIRS)])
         eng.close()
         del eng
         torch.cuda.empty_cache()
@@ -255,7 +258,8 @@ def main():
                    "level_histogram_skip_then_levels": [int(v) for v in hist],
                    "streams": "one" if args.no_overlap else
                    "two (worker compression of step t+1 overlaps aggregation + master compression of step t)",
-                   "ms_per_step_one_stream_with_kernel_events": dt_ev / args.steps * 1e3},
+                   "ms_per_step_one_stream_with_kernel_events": dt_ev / args.steps * 1e3,
+                   "second_scans_workers_master": repairs[0]},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "other_workloads": other,

@@ -95,6 +95,7 @@ struct NodeSet {
   int32_t* msg_idx;     // [nn][Kcap]
   float* msg_val;       // [nn][Kcap]
   unsigned long long* level_hist;  // [m+1]
+  unsigned long long* repairs;     // [1] node-steps whose sampled cut was too high (second scan ran)
   int16_t* qcodes;      // [nn][d] (only with quantiser levels)
   float* qscale;        // [nn]
   double* accbuf;       // [d] fp64 sums of the sparse messages (only with quantiser levels)
@@ -132,7 +133,7 @@ hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_gather(const NodeSet& ns, hipStream_t st);
 hipError_t launch_select(const NodeSet& ns, hipStream_t st);
 hipError_t launch_sample(const NodeSet& ns, const PassArgs& a, hipStream_t st);
-hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, hipStream_t st);
+hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, bool repair, hipStream_t st);
 hipError_t launch_tally(const NodeSet& ns, hipStream_t st);
 hipError_t launch_compact(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_qapply(const NodeSet& ns, const PassArgs& a, hipStream_t st);

@@ -115,7 +115,8 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.ncand = c.take<uint32_t>(nn * kCounterStride);
   ns.done = c.take<uint32_t>(nn * (kArriveFan + 1) * kCounterStride);
   ns.kmax = c.take<uint32_t>(nn);
-  ns.level_hist = c.take<unsigned long long>(m + 1);
+  ns.level_hist = c.take<unsigned long long>(m + 2);
+  ns.repairs = ns.level_hist + m + 1;
   // everything up to here must start at zero
   ns.prefix = c.take<uint32_t>(nn * p);
   ns.rank = c.take<uint32_t>(nn * p);
@@ -370,10 +371,9 @@ int compress(adacgd_ctx* c, NodeSet& ns, const PassArgs& a, int slot0, hipEvent_
   int rc;
   if (ns.onepass) {
     if ((rc = timed(c, slot0 + 0, [&] { return launch_sample(ns, a, c->cs); }))) return rc;
-    if ((rc = timed(c, slot0 + 1, [&] { return launch_scanx(ns, a, c->cs); }))) return rc;
-    // repair passes: do nothing unless the sampled cut left fewer candidates than the largest K
-    if ((rc = timed(c, slot0 + 2, [&] { return launch_scan(ns, a, c->cs); }))) return rc;
-    if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->cs); }))) return rc;
+    if ((rc = timed(c, slot0 + 1, [&] { return launch_scanx(ns, a, false, c->cs); }))) return rc;
+    // repair pass: does nothing unless the sampled cut left fewer candidates than the largest K
+    if ((rc = timed(c, slot0 + 2, [&] { return launch_scanx(ns, a, true, c->cs); }))) return rc;
   } else {
     if ((rc = timed(c, slot0 + 1, [&] { return launch_scan(ns, a, c->cs); }))) return rc;
     if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->cs); }))) return rc;
@@ -717,6 +717,13 @@ int adacgd_state(adacgd_ctx* c, int32_t field, void* dst, int64_t dst_bytes, int
       if (!hm) { set_err(c->err, "no master compressor"); return ADACGD_ERR_STATE; }
       return packed(M, M.msg_val, 4, false);
     case ADACGD_F_STEP: return host_out(&c->step, 8);
+    case ADACGD_F_REPAIRS: {
+      uint64_t o[2] = {0, 0};
+      HIPCHK(c, hipMemcpyAsync(&o[0], W.repairs, 8, hipMemcpyDeviceToHost, c->st));
+      if (hm) HIPCHK(c, hipMemcpyAsync(&o[1], M.repairs, 8, hipMemcpyDeviceToHost, c->st));
+      HIPCHK(c, hipStreamSynchronize(c->st));
+      return host_out(o, 16);
+    }
     case ADACGD_F_LEVEL_HIST: return copy(W.level_hist, (int64_t)(W.lv.m + 1) * 8);
     case ADACGD_F_M_LEVEL_HIST: return hm ? copy(M.level_hist, (int64_t)(M.lv.m + 1) * 8) : copy(nullptr, 8);
     case ADACGD_F_COMM: {

@@ -22,8 +22,8 @@
 //             epilogue: first digit (bin) and in-bin rank of each Top-K size; marks the node
 //             for repair if fewer candidates than the largest K were found, and as skipping
 //             if S <= zeta D (then every later kernel returns at once for that node)
-//   scan + filter (repair variants): idle unless a node is marked; then they redo the
-//             node in two passes
+//   scanx (repair variant): idle unless a node is marked; then it redoes the node with the
+//             cut at zero (every coordinate a candidate)
 // Two-pass sequence (level sets with quantisers, short vectors):
 //   scan    : v, S, D, full first-digit histogram, max |v|
 //             epilogue: bin and in-bin rank of each Top-K size, candidate cut-off bin, skip mark
@@ -173,8 +173,7 @@ __device__ __forceinline__ void emit4(uint32_t f, const float (&vv)[4], uint32_t
 // ---------------------------------------------------------------------------
 // scan
 // ---------------------------------------------------------------------------
-// REPAIR: second attempt of the one-pass sequence, only for nodes marked in ns.redo.
-template <bool DIFF, bool VEC, bool REPAIR>
+template <bool DIFF, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
   __shared__ uint32_t hist[kBins0];
   __shared__ double red[4];
@@ -183,13 +182,12 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
   __shared__ uint32_t s_rank[kMaxLevels], s_bin[kMaxLevels], s_rk[kMaxLevels], s_cnt[kMaxLevels];
 
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-  if (REPAIR && (ns.redo[node] == 0 || ns.skip[node] != 0)) return;
   const int64_t d = ns.d;
   const size_t row = (size_t)node * (size_t)d;
   const float* __restrict__ x = a.x + row;
   const float* __restrict__ h = a.h + row;
   const float* __restrict__ y = DIFF ? nullptr : a.y + row;
-  float* __restrict__ yc = (a.ycopy && !REPAIR) ? a.ycopy + row : nullptr;
+  float* __restrict__ yc = a.ycopy ? a.ycopy + row : nullptr;
 
   for (int b = tid; b < kBins0; b += kBlock) hist[b] = 0;
   __syncthreads();
@@ -374,7 +372,10 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample(NodeSet ns, PassArgs a)
 // scanx: scan fused with the candidate extraction at the estimated cut-off bin
 // (16-byte vector path only)
 // ---------------------------------------------------------------------------
-template <bool DIFF>
+// REPAIR: second attempt, only for nodes marked in ns.redo (the sampled cut left fewer
+// candidates than the largest K): the same pass with the cut at zero, i.e. every coordinate
+// becomes a candidate and the histogram is the full one.
+template <bool DIFF, bool REPAIR>
 __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
   constexpr bool VEC = true;
   __shared__ uint32_t hist[kBins0];
@@ -392,15 +393,16 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
   __shared__ uint32_t sg_grp[4][kSeg], sg_end[4][kSeg], sg_base[4][kSeg];
 
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  if (REPAIR && (ns.redo[node] == 0 || ns.skip[node] != 0)) return;
   const int64_t d = ns.d;
   const size_t row = (size_t)node * (size_t)d;
   const float* __restrict__ x = a.x + row;
   const float* __restrict__ h = a.h + row;
   const float* __restrict__ y = DIFF ? nullptr : a.y + row;
-  float* __restrict__ yc = a.ycopy ? a.ycopy + row : nullptr;
+  float* __restrict__ yc = (a.ycopy && !REPAIR) ? a.ycopy + row : nullptr;
   uint32_t* __restrict__ cval = ns.cand_val + row;
   uint16_t* __restrict__ coff = ns.cand_off + row;
-  const uint32_t cut = ns.best[node];
+  const uint32_t cut = REPAIR ? 0u : ns.best[node];
 
   for (int b = tid; b < kBins0; b += kBlock) hist[b] = 0;
   __syncthreads();
@@ -531,12 +533,15 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
     ns.D[node] = dnode;
     // first condition of the cascade: the trigger keeps h, and nothing after this kernel has work
     // to do for the node (the tally kernel takes the same decision from the same two numbers)
-    ns.skip[node] = s <= ns.lv.zeta * dnode ? 1u : 0u;
+    const bool skip = s <= ns.lv.zeta * dnode;
+    ns.skip[node] = skip ? 1u : 0u;
     ns.Eb[node] = el;
     // the K largest all have keys >= cut  <=>  at least K candidates were found
     const uint32_t total = ld_coherent(&ns.ncand[(size_t)node * kCounterStride]);
     ns.ncand[(size_t)node * kCounterStride] = 0;
-    ns.redo[node] = total < ns.lv.K[p - 1] ? 1u : 0u;   // estimate too high: the repair passes run
+    const bool redo = total < ns.lv.K[p - 1];           // estimate too high: the repair pass runs
+    ns.redo[node] = redo ? 1u : 0u;
+    if (redo && !skip) atomicAdd(ns.repairs, 1ull);
   }
 }
 
@@ -577,15 +582,13 @@ __device__ __forceinline__ float quant_one(float v, float a, float s, float c, f
 // ---------------------------------------------------------------------------
 // filter
 // ---------------------------------------------------------------------------
-// REPAIR: the kernel is the repair pass of the one-pass sequence and touches only nodes
-// marked in ns.redo.
-template <bool DIFF, bool VEC, bool QUANT, bool REPAIR>
+template <bool DIFF, bool VEC, bool QUANT>
 __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   __shared__ double red[4];
   __shared__ int s_flag;
 
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-  if (ns.skip[node] != 0 || (REPAIR && ns.redo[node] == 0)) return;   // skipping nodes need no candidates
+  if (ns.skip[node] != 0) return;   // skipping nodes need no candidates
   const int64_t d = ns.d;
   const int nq = ns.lv.nq;
   const size_t row = (size_t)node * (size_t)d;
@@ -1275,15 +1278,12 @@ hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
   const dim3 grid(ns.G, ns.nn), block(kBlock);
   const bool v = vec_ok(ns, a);
-  if (ns.onepass) {          // repair pass (the one-pass sequence implies the vector path)
-    if (a.diff) hipLaunchKernelGGL((k_scan<true, true, true>), grid, block, 0, st, ns, a);
-    else hipLaunchKernelGGL((k_scan<false, true, true>), grid, block, 0, st, ns, a);
-  } else if (a.diff) {
-    if (v) hipLaunchKernelGGL((k_scan<true, true, false>), grid, block, 0, st, ns, a);
-    else hipLaunchKernelGGL((k_scan<true, false, false>), grid, block, 0, st, ns, a);
+  if (a.diff) {
+    if (v) hipLaunchKernelGGL((k_scan<true, true>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_scan<true, false>), grid, block, 0, st, ns, a);
   } else {
-    if (v) hipLaunchKernelGGL((k_scan<false, true, false>), grid, block, 0, st, ns, a);
-    else hipLaunchKernelGGL((k_scan<false, false, false>), grid, block, 0, st, ns, a);
+    if (v) hipLaunchKernelGGL((k_scan<false, true>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_scan<false, false>), grid, block, 0, st, ns, a);
   }
   return hipGetLastError();
 }
@@ -1291,9 +1291,8 @@ hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
 template <bool DIFF, bool VEC>
 static void launch_filter_q(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   const dim3 grid(ns.G, ns.nn), block(kBlock);
-  if (ns.onepass) hipLaunchKernelGGL((k_filter<DIFF, VEC, false, true>), grid, block, 0, st, ns, a);
-  else if (ns.lv.nq > 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, true, false>), grid, block, 0, st, ns, a);
-  else hipLaunchKernelGGL((k_filter<DIFF, VEC, false, false>), grid, block, 0, st, ns, a);
+  if (ns.lv.nq > 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, true>), grid, block, 0, st, ns, a);
+  else hipLaunchKernelGGL((k_filter<DIFF, VEC, false>), grid, block, 0, st, ns, a);
 }
 
 hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
@@ -1317,11 +1316,16 @@ hipError_t launch_sample(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, bool repair, hipStream_t st) {
   (void)hipGetLastError();
   const dim3 grid(ns.G, ns.nn), block(kBlock);
-  if (a.diff) hipLaunchKernelGGL((k_scanx<true>), grid, block, 0, st, ns, a);
-  else hipLaunchKernelGGL((k_scanx<false>), grid, block, 0, st, ns, a);
+  if (repair) {
+    if (a.diff) hipLaunchKernelGGL((k_scanx<true, true>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_scanx<false, true>), grid, block, 0, st, ns, a);
+  } else {
+    if (a.diff) hipLaunchKernelGGL((k_scanx<true, false>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_scanx<false, false>), grid, block, 0, st, ns, a);
+  }
   return hipGetLastError();
 }
 

@@ -423,6 +423,11 @@ def test_long_vectors_one_pass_selection_bit_exact(kind):
         res, rm = orc.step(grads=grads[t])
         eng.step(_cuda(grads[t]))
         compare_step(eng, orc, res, rm, ("long", kind, t))
+    repairs = eng.state(E.F_REPAIRS)
+    if kind == "adversarial":
+        assert repairs[0] > 0                    # the second scan did run
+    if kind in ("normal", "heavy", "two_pass_flag"):
+        assert repairs[0] == 0
     eng.close()
 
 
