@@ -83,7 +83,9 @@ enum adacgd_flags {
                                       next step instead of copying it; the caller must leave that array
                                       untouched until the next adacgd_step call has completed            */
   ADACGD_FLAG_KERNEL_TIMING = 4,   /* record HIP events around every kernel (see ADACGD_F_KERNEL_MS)    */
-  ADACGD_FLAG_TWO_PASS = 8,        /* never use the sampled one-pass selection (same results, slower)   */
+  ADACGD_FLAG_TWO_PASS = 8,        /* always use the general two-pass kernels: neither the sampled one-pass
+                                      selection of long vectors nor the one-block kernel of short ones
+                                      (same results, slower)                                            */
   ADACGD_FLAG_OVERLAP = 16         /* GRAD_EXTERNAL / DIFF_EXTERNAL: run the worker compression on a stream
                                       of the library's own, concurrently with the previous step's
                                       aggregation and master compression on the caller's stream (same

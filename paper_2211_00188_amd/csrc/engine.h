@@ -20,6 +20,7 @@ constexpr int kShift1 = 9, kBins1 = 1024;
 constexpr int kBins2 = 512;
 
 constexpr int kMaxLevels = 16;
+constexpr int kSmallMax = 4096;         // largest d handled by the one-block-per-node kernel
 
 enum { kTopK = 0, kQuant = 1 };
 
@@ -47,6 +48,7 @@ struct NodeSet {
   int G2;           // blocks per node of the candidate kernels
   int GZ;           // blocks per (slot, node) of the select kernels
   int onepass;      // 1: sample + scanx sequence, 0: scan + filter sequence
+  int small;        // 1: d <= kSmallMax: one kernel, one block per node, does the whole step
   uint32_t Kcap;    // message capacity per node = largest Top-K size (0 if none)
   LevelTable lv;
 
@@ -132,6 +134,7 @@ hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_gather(const NodeSet& ns, hipStream_t st);
 hipError_t launch_select(const NodeSet& ns, hipStream_t st);
+hipError_t launch_small(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_sample(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, bool repair, hipStream_t st);
 hipError_t launch_tally(const NodeSet& ns, hipStream_t st);

@@ -177,6 +177,7 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
   // 1/32 sample to be informative, and a candidate set that is a minor part of the vector.
   ns.onepass = (!force_two_pass && ns.lv.nq == 0 && ns.lv.p > 0 && d % 4 == 0 && ns.tiles >= 128 &&
                 4 * (int64_t)ns.Kcap <= d) ? 1 : 0;
+  ns.small = (!force_two_pass && d <= kSmallMax) ? 1 : 0;
   // streaming kernels: about 5120 blocks in all for the fused scan (several short blocks per CU
   // interleave better with kernels of another stream than few long ones), about 2560 for the
   // two-pass scan (whose blocks each flush a full histogram); at most 640 per node
@@ -369,6 +370,10 @@ int drain_spans(adacgd_ctx* c) {
 // reads them on the other stream, must have finished.
 int compress(adacgd_ctx* c, NodeSet& ns, const PassArgs& a, int slot0, hipEvent_t before_tally) {
   int rc;
+  if (ns.small) {      // short vectors: the whole step of a node in one block (timed in the scan's slot)
+    if (before_tally) HIPCHK(c, hipStreamWaitEvent(c->cs, before_tally, 0));
+    return timed(c, slot0 + 1, [&] { return launch_small(ns, a, c->cs); });
+  }
   if (ns.onepass) {
     if ((rc = timed(c, slot0 + 0, [&] { return launch_sample(ns, a, c->cs); }))) return rc;
     if ((rc = timed(c, slot0 + 1, [&] { return launch_scanx(ns, a, false, c->cs); }))) return rc;

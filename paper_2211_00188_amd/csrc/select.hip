@@ -1267,6 +1267,243 @@ __global__ __launch_bounds__(kBlock) void k_qapply(NodeSet ns, PassArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// small: the whole compression step of a node in one block, for d <= kSmallMax (the scale of the
+// paper's own experiments, where a step of the general sequence is a dozen launches of a few
+// microseconds each).  The coordinates are sorted in LDS by the total order of Top-K -- key
+// descending, index ascending -- so every Top-K size is a prefix of the sorted order; errors are
+// sums over the rest; then the cascade, and the message in ascending coordinate by a scan over a
+// flag per coordinate.  Same arithmetic per element as the general kernels.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double small_sum(double v, double* red, int nw) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  double t = 0.0;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+
+template <bool DIFF>
+__global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
+  __shared__ uint64_t ck[kSmallMax];       // (key << 32) | ~index, sorted descending
+  __shared__ float sv[kSmallMax];          // v by coordinate
+  __shared__ uint8_t flag[kSmallMax];      // 1 = coordinate belongs to the message
+  __shared__ double red[16];
+  __shared__ uint32_t redu[16];
+  __shared__ double s_slot_err[kMaxLevels], s_qerr[kMaxLevels];
+  __shared__ int s_slot, s_q;
+  const int node = blockIdx.x, tid = threadIdx.x, NT = blockDim.x, nw = NT >> 6;
+  const int lane = tid & 63, w = tid >> 6;
+  const int d = (int)ns.d;
+  const LevelTable& lv = ns.lv;
+  const int p = lv.p, nq = lv.nq;
+  const size_t row = (size_t)node * (size_t)d;
+  const float* __restrict__ x = a.x + row;
+  float* __restrict__ h = a.h + row;
+  const float* __restrict__ y = DIFF ? nullptr : a.y + row;
+  float* __restrict__ yc = a.ycopy ? a.ycopy + row : nullptr;
+  int dp = 64;
+  while (dp < d) dp <<= 1;
+
+  // ---- v, ||v||^2, ||x - y||^2, max |v|, sort keys ----
+  double S = 0.0, D = 0.0;
+  uint32_t kmax = 0;
+  for (int i = tid; i < dp; i += NT) {
+    if (i < d) {
+      const float xv = x[i];
+      const float v = DIFF ? xv : xv - h[i];
+      if (!DIFF) {
+        const double dw = (double)(xv - y[i]);
+        D = fma(dw, dw, D);
+        if (yc) yc[i] = xv;
+      }
+      const double dv = (double)v;
+      S = fma(dv, dv, S);
+      const uint32_t key = magkey(v);
+      kmax = key > kmax ? key : kmax;
+      sv[i] = v;
+      ck[i] = ((uint64_t)key << 32) | (uint64_t)(~(uint32_t)i);
+    } else {
+      ck[i] = 0;                     // sorts behind every coordinate
+    }
+  }
+  S = small_sum(S, red, nw);
+  D = small_sum(D, red, nw);
+  kmax = wave_max(kmax);
+  __syncthreads();
+  if (lane == 0) redu[w] = kmax;
+  __syncthreads();
+  for (int i = 0; i < nw; ++i) kmax = redu[i] > kmax ? redu[i] : kmax;
+  const double Dn = DIFF ? a.extD[node] : D;
+  const double tau = lv.zeta * Dn;
+  const bool skip = S <= tau;            // first condition of the cascade: nothing else is evaluated
+
+  if (!skip) {
+    // ---- bitonic sort, descending ----
+    for (int k = 2; k <= dp; k <<= 1) {
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        __syncthreads();
+        for (int t = tid; t < (dp >> 1); t += NT) {
+          const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+          const int l = i | j;
+          const uint64_t ai = ck[i], al = ck[l];
+          const bool desc = (i & k) == 0;
+          if (desc ? ai < al : ai > al) {
+            ck[i] = al;
+            ck[l] = ai;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    // ---- realised error of every Top-K size: energy of the ranks behind it ----
+    for (int s = 0; s < p; ++s) {
+      const int K = (int)lv.K[s];
+      double e = 0.0;
+      for (int r = K + tid; r < d; r += NT) {
+        const double f = (double)__uint_as_float((uint32_t)(ck[r] >> 32));
+        e = fma(f, f, e);
+      }
+      e = small_sum(e, red, nw);
+      if (tid == 0) s_slot_err[s] = e;
+    }
+    // ---- realised error of every quantiser level ----
+    if (nq > 0) {
+      const float qa = __uint_as_float(kmax);
+      const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
+      const uint32_t ctr1 = (uint32_t)node | a.node_flag;
+      double qacc[kMaxLevels];
+#pragma unroll
+      for (int q = 0; q < kMaxLevels; ++q) qacc[q] = 0.0;
+      for (int i = tid; i < d; i += NT) {
+        uint32_t r4[4];
+        philox4x32_10((uint32_t)(i >> 2), ctr1, a.step, 0u, k0, k1, r4);
+        const float u = dither_of(r4[i & 3]);
+        const float v = sv[i];
+#pragma unroll
+        for (int q = 0; q < kMaxLevels; ++q) {
+          if (q < nq) {
+            const float qc = qa > 0.f ? (float)((double)qa / lv.qdenom[q]) : 0.f;
+            int code;
+            const float cq = qa > 0.f ? quant_one(v, qa, lv.qs[q], qc, u, &code) : 0.f;
+            const double e = (double)v - (double)cq;
+            qacc[q] = fma(e, e, qacc[q]);
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kMaxLevels; ++q) {
+        if (q < nq) {
+          const double e = small_sum(qacc[q], red, nw);
+          if (tid == 0) s_qerr[q] = e;
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- the cascade ----
+  if (tid == 0) {
+    double err[kMaxLevels];
+    for (int j = 0; j < lv.m; ++j) {
+      if (skip) err[j] = __longlong_as_double(0x7FF8000000000000ll);
+      else err[j] = lv.kind[j] == kTopK ? s_slot_err[lv.ref[j]] : s_qerr[lv.ref[j]];
+      ns.err[node * lv.m + j] = err[j];
+    }
+    int jstar;
+    if (skip) {
+      jstar = 0;
+    } else {
+      jstar = lv.m;
+      for (int j = 1; j < lv.m; ++j)
+        if (err[j - 1] <= tau) { jstar = j; break; }
+    }
+    int slot = -1, q = -1;
+    if (jstar > 0) {
+      if (lv.kind[jstar - 1] == kTopK) slot = lv.ref[jstar - 1];
+      else q = lv.ref[jstar - 1];
+    }
+    ns.S[node] = S;
+    ns.D[node] = Dn;
+    ns.level[node] = jstar;
+    atomicAdd(&ns.level_hist[jstar], 1ull);
+    ns.sel_slot[node] = slot;
+    ns.sel_q[node] = q;
+    ns.msg_count[node] = slot >= 0 ? lv.K[slot] : 0u;
+    ns.qscale[node] = 0.f;
+    s_slot = slot;
+    s_q = q;
+  }
+  __syncthreads();
+  const int slot = s_slot, q = s_q;
+
+  if (slot >= 0) {
+    // ---- message of the chosen Top-K size in ascending coordinate, h <- h + C(v) ----
+    const int K = (int)lv.K[slot];
+    for (int i = tid; i < d; i += NT) flag[i] = 0;
+    __syncthreads();
+    for (int r = tid; r < K; r += NT) flag[~(uint32_t)ck[r]] = 1;
+    __syncthreads();
+    const int E = (d + NT - 1) / NT;               // consecutive coordinates per thread
+    const int lo = min(d, tid * E), hi = min(d, lo + E);
+    uint32_t cnt = 0, low = 0;
+    for (int i = lo; i < hi; ++i) {
+      cnt += flag[i];
+      if (i < kWaveTile) low += flag[i];
+    }
+    // exclusive prefix of cnt over the threads
+    uint32_t inc = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t t = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += t;
+    }
+    if (lane == 63) redu[w] = inc;
+    __syncthreads();
+    uint32_t pos = inc - cnt;
+    for (int i = 0; i < w; ++i) pos += redu[i];
+    __syncthreads();
+    int32_t* __restrict__ midx = ns.msg_idx + (size_t)node * ns.Kcap;
+    float* __restrict__ mval = ns.msg_val + (size_t)node * ns.Kcap;
+    for (int i = lo; i < hi; ++i) {
+      if (flag[i]) {
+        const float v = sv[i];
+        midx[pos] = i;
+        mval[pos] = v;
+        h[i] = h[i] + v;
+        ++pos;
+      }
+    }
+    // message offsets of the groups of 2048 coordinates (the aggregation reads them)
+    const double lowsum = small_sum((double)low, red, nw);
+    if (tid == 0) {
+      uint32_t* go = ns.grp_off + (size_t)node * (ns.groups + 1);
+      go[0] = 0;
+      if (ns.groups == 2) go[1] = (uint32_t)lowsum;
+      go[ns.groups] = (uint32_t)K;
+    }
+  } else if (q >= 0) {
+    // ---- dense update and codes of the chosen quantiser level ----
+    const float qa = __uint_as_float(kmax);
+    const float qs = lv.qs[q];
+    const float qc = qa > 0.f ? (float)((double)qa / lv.qdenom[q]) : 0.f;
+    const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
+    const uint32_t ctr1 = (uint32_t)node | a.node_flag;
+    int16_t* __restrict__ codes = ns.qcodes + row;
+    if (tid == 0) ns.qscale[node] = qc;
+    for (int i = tid; i < d; i += NT) {
+      uint32_t r4[4];
+      philox4x32_10((uint32_t)(i >> 2), ctr1, a.step, 0u, k0, k1, r4);
+      int code = 0;
+      const float cq = qa > 0.f ? quant_one(sv[i], qa, qs, qc, dither_of(r4[i & 3]), &code) : 0.f;
+      h[i] = h[i] + cq;
+      codes[i] = (int16_t)code;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 static inline bool vec_ok(const NodeSet& ns, const PassArgs& a) {
@@ -1305,6 +1542,17 @@ hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
     if (v) launch_filter_q<false, true>(ns, a, st);
     else launch_filter_q<false, false>(ns, a, st);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_small(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
+  (void)hipGetLastError();
+  int dp = 64;
+  while (dp < ns.d) dp <<= 1;
+  int nt = dp / 2;                       // one compare-exchange per thread and sort stage
+  nt = nt < 64 ? 64 : (nt > 1024 ? 1024 : nt);
+  if (a.diff) hipLaunchKernelGGL((k_small<true>), dim3(ns.nn), dim3(nt), 0, st, ns, a);
+  else hipLaunchKernelGGL((k_small<false>), dim3(ns.nn), dim3(nt), 0, st, ns, a);
   return hipGetLastError();
 }
 
