@@ -108,8 +108,10 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("kind", ["normal", "ties", "heavy", "sparse", "denormal", "const"])
-@pytest.mark.parametrize("n,d", SHAPES)
-def test_compression_step_bit_exact_external_gradients(n, d, kind):
+@pytest.mark.parametrize("n,d,general", [(n, d, False) for n, d in SHAPES] +
+                         [(5, 1000, True), (1, 1, True), (3, 4096, False), (2, 4095, True)])
+def test_compression_step_bit_exact_external_gradients(n, d, kind, general):
+    """`general`: short vectors through the general two-pass kernels instead of the one-block kernel."""
     E = _eng()
     rng = np.random.default_rng(1000 + d + len(kind))
     Ks = sorted({max(1, min(d, k)) for k in (1, 7, d // 50, d // 8, d // 2, d)})
@@ -127,7 +129,7 @@ def test_compression_step_bit_exact_external_gradients(n, d, kind):
         eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zeta, master_levels=ml,
                        zeta_master=0.0, grad_mode=E.GRAD_EXTERNAL,
                        init_mode=E.INIT_ZERO if zeta == 0.6 else E.INIT_FULLGRAD, x0=_cuda(x0),
-                       grad0=_cuda(grads[0]))
+                       grad0=_cuda(grads[0]), flags=E.FLAG_TWO_PASS if general else 0)
         assert np.array_equal(bits(eng.state(E.F_GTILDE)), bits(orc.gt))
         for t in range(1, steps + 1):
             res, rm = orc.step(grads=grads[t])
