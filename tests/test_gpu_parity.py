@@ -160,7 +160,7 @@ def test_retained_external_gradient_pointer_matches_copy():
         assert np.array_equal(bits(a), bits(b))
 
 
-@pytest.mark.parametrize("n,d", [(4, 3 * 8192 + 40), (3, 5003)])
+@pytest.mark.parametrize("n,d", [(4, 3 * 8192 + 40), (3, 5003), (6, 3001)])
 def test_difference_mode_with_quantiser_levels_bit_exact(n, d):
     """Caller-supplied difference vectors and trigger right-hand sides; mixed Top-K and
     b-bit levels ordered by contraction parameter; every branch of the cascade occurs."""
