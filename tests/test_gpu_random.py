@@ -41,15 +41,28 @@ def test_random_configurations_bit_exact(seed):
         for t in range(1, steps + 1):
             grads[t] = (grads[t - 1] + grads[t] * np.float32(10.0 ** rng.uniform(-2, 0))).astype(np.float32)
         x0 = rng.standard_normal(d).astype(np.float32)
+        diff_mode = rng.random() < 0.3       # the caller supplies x - h and ||x - y||^2 itself
         orc = O.AdaCGDOracle(n=n, d=d, gamma=0.05, worker_levels=levels, zeta_worker=zw, master_levels=ml,
                              zeta_master=zm, seed=pseed)
-        orc.init(x0, grads[0], O.INIT_FULLGRAD)
-        eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=levels, zeta_worker=zw, master_levels=ml, zeta_master=zm,
-                       grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=_cuda(grads[0]), seed=pseed, flags=flags)
+        if diff_mode:
+            orc.init(x0, None, O.INIT_ZERO)
+            eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=levels, zeta_worker=zw, master_levels=ml,
+                           zeta_master=zm, grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), seed=pseed,
+                           flags=flags)
+        else:
+            orc.init(x0, grads[0], O.INIT_FULLGRAD)
+            eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=levels, zeta_worker=zw, master_levels=ml,
+                           zeta_master=zm, grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=_cuda(grads[0]), seed=pseed,
+                           flags=flags)
         try:
             for t in range(1, steps + 1):
-                res, rm = orc.step(grads=grads[t])
-                eng.step(_cuda(grads[t]))
+                if diff_mode:
+                    Dt = np.sum(grads[t].astype(np.float64) ** 2, axis=1) * 10.0 ** rng.uniform(-2, 1, n)
+                    res, rm = orc.step(diffs=grads[t], D=Dt)
+                    eng.step(_cuda(grads[t]), _cuda(Dt))
+                else:
+                    res, rm = orc.step(grads=grads[t])
+                    eng.step(_cuda(grads[t]))
                 if rm is not None and rm.margins and min(rm.margins) < 1e-12:
                     raise pytest.skip.Exception("a master trigger comparison is within 1e-12 of equality")
                 compare_step(eng, orc, res, rm, tag + (t,))
