@@ -181,8 +181,10 @@ enum adacgd_field {
 };
 
 /* Kernel slots of ADACGD_F_KERNEL_MS.  W = worker side, M = master side.  Long vectors with
- * Top-K levels only run sample + scan (the scan also extracts the candidates) and use filter
- * only to repair a failed estimate; otherwise scan + filter run as two passes. */
+ * Top-K levels only run sample + scan (the scan also extracts the candidates); the filter slot
+ * then holds the second scan that repairs a failed estimate (idle otherwise).  Other vectors run
+ * scan + filter as two passes.  Vectors of at most 4096 coordinates are handled by one kernel
+ * that does the whole compression step of a node, timed in the scan slot. */
 enum adacgd_kernel {
   ADACGD_K_XUPDATE = 0,
   ADACGD_K_GRAD_MARGIN = 1,
