@@ -63,6 +63,19 @@ typedef struct {
 
 #define ADACGD_MAX_LEVELS 16
 
+/* Condition that guards one position of the cascade.  The Ada3PC construction (Section 4.2,
+ * Lemma 2) accepts any conditions P_j; this library offers the family
+ *     P_j :  err_j <= zeta ||x-y||^2 + eta ||x-h||^2
+ * where err_0 = ||x-h||^2 (position 0: keep h, send nothing) and err_j is the realised error
+ * of level j.  zeta = the AdaCGD constant, eta = 0 is the trigger of Eq. (10); zeta = 0 with
+ * eta < 1 accepts the first level whose realised relative error is at most eta (a compressor
+ * that is contractive with alpha = 1 - eta by construction).  The last level has no condition.
+ * The right side is evaluated in fp64 as fl(fl(zeta D) + fl(eta S)). */
+typedef struct {
+  float zeta; /* finite, >= 0 */
+  float eta;  /* finite, >= 0 */
+} adacgd_trigger;
+
 /* Where grad f_i(x^{t+1}) comes from. */
 enum adacgd_grad_mode {
   ADACGD_GRAD_LOGISTIC = 0, /* engine computes the gradient of the Section 6 objective:
@@ -118,6 +131,11 @@ typedef struct {
   void* stream;                 /* hipStream_t; BORROWED                                      */
   void* workspace;              /* device, 256-byte aligned; owned by the context until destroy */
   int64_t workspace_bytes;
+  const adacgd_trigger* worker_triggers; /* host [m_worker]: conditions of cascade positions 0..m_worker-1
+                                            (0 = keep h, j = level j); copied.  NULL: every position uses
+                                            (zeta_worker, 0), the AdaCGD definition; otherwise zeta_worker
+                                            is ignored                                                  */
+  const adacgd_trigger* master_triggers; /* host [m_master], likewise with zeta_master; NULL allowed   */
 } adacgd_config;
 
 /* Device bytes adacgd_init needs for this configuration (workspace and stream

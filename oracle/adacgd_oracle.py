@@ -227,11 +227,19 @@ class CompressResult:
     margins: list = field(default_factory=list)   # |lhs - tau| / max(tau, tiny) of every comparison made
 
 
-def adacgd_compress(h, y, x, levels, zeta, *, seed=0, node=0, step=0, D_given=None, v_given=None) -> CompressResult:
+def adacgd_compress(h, y, x, levels, zeta, *, seed=0, node=0, step=0, D_given=None, v_given=None,
+                    triggers=None) -> CompressResult:
     """Apply the AdaCGD compressor to x with stored estimator h and previous
     point y.  `levels` is the ordered list [(kind, param), ...].
     v_given / D_given replace x - h and ||x - y||^2 when the caller supplies
-    the difference vector directly."""
+    the difference vector directly.
+
+    `triggers` generalises the conditions of the cascade the way the Ada3PC
+    definition (Section 4.2) and Lemma 2 allow: any conditions P_0..P_{m-1} may
+    guard the levels.  The family here is
+        P_j :  err_j <= zeta_j ||x - y||^2 + eta_j ||x - h||^2,   err_0 = ||x - h||^2,
+    given as m pairs (zeta_j, eta_j), j = 0 (keep h) .. m-1; the last level is
+    unconditional.  None means (zeta, 0) for every j: the AdaCGD definition."""
     dt = h.dtype
     d = h.shape[0]
     v = np.asarray(v_given, dtype=dt) if v_given is not None else (x - h).astype(dt)
@@ -243,8 +251,12 @@ def adacgd_compress(h, y, x, levels, zeta, *, seed=0, node=0, step=0, D_given=No
         w = (x - y).astype(dt)
         D = sum_squares(w)
         same_terms = bool(np.array_equal(v, w))
-    tau = float(np.float64(dt.type(zeta))) * D          # zeta is held in the storage dtype
     m = len(levels)
+    if triggers is None:
+        triggers = [(zeta, 0.0)] * m
+    assert len(triggers) == m
+    # the constants are held in the storage dtype; each product and the sum is rounded once (float64)
+    taus = [float(np.float64(dt.type(z))) * D + float(np.float64(dt.type(e))) * S for z, e in triggers]
 
     order = None
     u = None
@@ -265,22 +277,22 @@ def adacgd_compress(h, y, x, levels, zeta, *, seed=0, node=0, step=0, D_given=No
 
     margins = []
 
-    def holds(lhs):
+    def holds(lhs, tau):
         # relative distance from equality; 0 == 0 is exact on any summation order (every term is zero)
         margins.append(float("inf") if lhs == 0.0 and tau == 0.0 else abs(lhs - tau) / max(tau, 1e-300))
         return lhs <= tau
 
-    if same_terms and tau == D:
+    if same_terms and taus[0] == D and float(dt.type(triggers[0][1])) == 0.0:
         margins.append(float("inf"))      # S == D term by term: the comparison is S <= S
         first = True
     else:
-        first = holds(S)
+        first = holds(S, taus[0])
     if first:
         level = 0
     else:
         level = m
         for j in range(1, m):
-            if holds(err[j - 1]):
+            if holds(err[j - 1], taus[j]):
                 level = j
                 break
 
@@ -335,13 +347,14 @@ class AdaCGDOracle:
     h = g^t, y = g~^t)."""
 
     def __init__(self, *, n, d, gamma, worker_levels, zeta_worker, master_levels=(), zeta_master=0.0,
-                 seed=0, dtype=np.float32, shards=None, lam=0.1):
+                 seed=0, dtype=np.float32, shards=None, lam=0.1, worker_triggers=None, master_triggers=None):
         self.n, self.d = int(n), int(d)
         self.dt = np.dtype(dtype)
         self.gamma = float(np.float64(self.dt.type(gamma)))
         self.wl = [tuple(l) for l in worker_levels]
         self.ml = [tuple(l) for l in master_levels]
         self.zw, self.zm = zeta_worker, zeta_master
+        self.tw, self.tm = worker_triggers, master_triggers
         self.seed = int(seed)
         self.shards = shards            # list of (A_i, labels_i) or None
         self.lam = float(np.float64(self.dt.type(lam)))
@@ -398,10 +411,10 @@ class AdaCGDOracle:
         for i in range(n):
             if diffs is not None:
                 r = adacgd_compress(self.gi[i], None, None, self.wl, self.zw, seed=self.seed, node=i, step=self.t,
-                                    D_given=D[i], v_given=diffs[i])
+                                    D_given=D[i], v_given=diffs[i], triggers=self.tw)
             else:
                 r = adacgd_compress(self.gi[i], self.y[i], grads[i], self.wl, self.zw, seed=self.seed, node=i,
-                                    step=self.t)
+                                    step=self.t, triggers=self.tw)
             res.append(r)
             self.gi[i] = r.h_new
             if r.level > 0:
@@ -422,7 +435,7 @@ class AdaCGDOracle:
             rm = None
         else:
             rm = adacgd_compress(self.g, self.gt_prev, self.gt, self.ml, self.zm, seed=self.seed, node=1 << 31,
-                                 step=self.t)
+                                 step=self.t, triggers=self.tm)
             self.g = rm.h_new
             self.level_hist_m[rm.level] += 1
         self.t += 1

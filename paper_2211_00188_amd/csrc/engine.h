@@ -35,7 +35,10 @@ struct LevelTable {
   int qbits[kMaxLevels];
   float qs[kMaxLevels];       // s = 2^(b-1) - 1 magnitude levels
   double qdenom[kMaxLevels];  // s (1 + omega)
-  double zeta;                // trigger constant, the fp32 argument widened
+  // Trigger of cascade position j (0 = keep h, j = level j; the last level has none):
+  //   err_j <= tz[j] ||x-y||^2 + te[j] ||x-h||^2,  err_0 = ||x-h||^2.  fp32 arguments widened.
+  double tz[kMaxLevels];
+  double te[kMaxLevels];
 };
 
 // Device arrays of one side.  nn nodes, each with a length-d vector.

@@ -48,13 +48,22 @@ double level_alpha(const adacgd_level& lv, int64_t d) {
   return 1.0 / (1.0 + w);
 }
 
-int build_levels(const adacgd_level* in, int m, float zeta, int64_t d, uint32_t flags, LevelTable* lt, char* err) {
+int build_levels(const adacgd_level* in, int m, float zeta, const adacgd_trigger* trig, int64_t d, uint32_t flags,
+                 LevelTable* lt, char* err) {
   std::memset(lt, 0, sizeof(*lt));
   if (m < 0 || m > ADACGD_MAX_LEVELS) { set_err(err, "level count %d out of range", m); return ADACGD_ERR_ARG; }
   if (m > 0 && !in) { set_err(err, "level array is null"); return ADACGD_ERR_ARG; }
-  if (!std::isfinite(zeta) || zeta < 0.f) { set_err(err, "zeta must be finite and >= 0"); return ADACGD_ERR_ARG; }
+  if (!trig && (!std::isfinite(zeta) || zeta < 0.f)) { set_err(err, "zeta must be finite and >= 0"); return ADACGD_ERR_ARG; }
   lt->m = m;
-  lt->zeta = (double)zeta;
+  for (int j = 0; j < m; ++j) {
+    const float z = trig ? trig[j].zeta : zeta, e = trig ? trig[j].eta : 0.f;
+    if (!std::isfinite(z) || z < 0.f || !std::isfinite(e) || e < 0.f) {
+      set_err(err, "trigger %d: zeta and eta must be finite and >= 0", j);
+      return ADACGD_ERR_ARG;
+    }
+    lt->tz[j] = (double)z;
+    lt->te[j] = (double)e;
+  }
   for (int j = 0; j < m; ++j) {
     if (in[j].kind == ADACGD_TOPK) {
       if (in[j].param < 1 || in[j].param > d) {
@@ -245,9 +254,9 @@ int validate(const adacgd_config* cfg, LevelTable* wl, LevelTable* ml, char* err
   }
   if (!std::isfinite(cfg->gamma)) { set_err(err, "gamma must be finite"); return ADACGD_ERR_ARG; }
   if (cfg->m_worker < 1) { set_err(err, "at least one worker level is required"); return ADACGD_ERR_ARG; }
-  int rc = build_levels(cfg->worker_levels, cfg->m_worker, cfg->zeta_worker, cfg->d, cfg->flags, wl, err);
+  int rc = build_levels(cfg->worker_levels, cfg->m_worker, cfg->zeta_worker, cfg->worker_triggers, cfg->d, cfg->flags, wl, err);
   if (rc) return rc;
-  rc = build_levels(cfg->master_levels, cfg->m_master, cfg->zeta_master, cfg->d, cfg->flags, ml, err);
+  rc = build_levels(cfg->master_levels, cfg->m_master, cfg->zeta_master, cfg->master_triggers, cfg->d, cfg->flags, ml, err);
   if (rc) return rc;
   if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC) {
     if (!cfg->shard_offsets) { set_err(err, "shard_offsets is null"); return ADACGD_ERR_ARG; }

@@ -21,7 +21,7 @@
 //             histogram and count, the energy below the cut
 //             epilogue: first digit (bin) and in-bin rank of each Top-K size; marks the node
 //             for repair if fewer candidates than the largest K were found, and as skipping
-//             if S <= zeta D (then every later kernel returns at once for that node)
+//             if the first trigger holds, S <= zeta D in the AdaCGD definition (then every later kernel returns at once for that node)
 //   scanx (repair variant): idle unless a node is marked; then it redoes the node with the
 //             cut at zero (every coordinate a candidate)
 // Two-pass sequence (level sets with quantisers, short vectors):
@@ -50,6 +50,14 @@ namespace adacgd {
 // starting at w*2048 + k*256 + 4l.  Scalar path: component c of iteration k is
 // coordinate w*2048 + k*256 + 64c + l.
 // ---------------------------------------------------------------------------
+// Right side of the trigger that guards cascade position j (0 = keep h, j = level j):
+// zeta_j ||x-y||^2 + eta_j ||x-h||^2.  Both products and the sum are rounded separately (no fused
+// multiply-add), so the bound is the same number wherever it is evaluated; with eta_j = 0 it is
+// exactly zeta_j ||x-y||^2, the trigger of Eq. (10).
+__device__ __forceinline__ double trigger_bound(const LevelTable& lv, int j, double S, double D) {
+  return __dadd_rn(__dmul_rn(lv.tz[j], D), __dmul_rn(lv.te[j], S));
+}
+
 template <bool VEC>
 __device__ __forceinline__ int64_t comp0(int64_t base, int w, int lane, int k) {
   return VEC ? base + w * kWaveTile + k * 256 + lane * 4 : base + w * kWaveTile + k * 256 + lane;
@@ -267,7 +275,7 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
     ns.D[node] = dnode;
     // first condition of the cascade: the trigger keeps h, and nothing after this kernel has work
     // to do for the node (the tally kernel takes the same decision from the same two numbers)
-    ns.skip[node] = s <= ns.lv.zeta * dnode ? 1u : 0u;
+    ns.skip[node] = s <= trigger_bound(ns.lv, 0, s, dnode) ? 1u : 0u;
     ns.bmin[node] = p > 0 ? s_bin[p - 1] : (uint32_t)kBins0;   // largest K reaches lowest
     if (ns.lv.nq > 0) {
       ns.amax[node] = ld_coherent(&ns.kmax[node]);
@@ -533,7 +541,7 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
     ns.D[node] = dnode;
     // first condition of the cascade: the trigger keeps h, and nothing after this kernel has work
     // to do for the node (the tally kernel takes the same decision from the same two numbers)
-    const bool skip = s <= ns.lv.zeta * dnode;
+    const bool skip = s <= trigger_bound(ns.lv, 0, s, dnode);
     ns.skip[node] = skip ? 1u : 0u;
     ns.Eb[node] = el;
     // the K largest all have keys >= cut  <=>  at least K candidates were found
@@ -1081,7 +1089,6 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
   if (tid == 0) {
     const LevelTable& lv = ns.lv;
     const double S = ns.S[node], D = ns.D[node], Eb = ns.Eb[node];
-    const double tau = lv.zeta * D;
     double err[kMaxLevels];
     for (int j = 0; j < lv.m; ++j) {
       if (skip) {
@@ -1097,12 +1104,12 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
       ns.err[node * lv.m + j] = err[j];
     }
     int jstar;
-    if (S <= tau) {
+    if (S <= trigger_bound(lv, 0, S, D)) {
       jstar = 0;                                   // keep h: communication skipped
     } else {
       jstar = lv.m;
       for (int j = 1; j < lv.m; ++j)
-        if (err[j - 1] <= tau) { jstar = j; break; }
+        if (err[j - 1] <= trigger_bound(lv, j, S, D)) { jstar = j; break; }
     }
     ns.level[node] = jstar;
     atomicAdd(&ns.level_hist[jstar], 1ull);
@@ -1336,8 +1343,7 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
   __syncthreads();
   for (int i = 0; i < nw; ++i) kmax = redu[i] > kmax ? redu[i] : kmax;
   const double Dn = DIFF ? a.extD[node] : D;
-  const double tau = lv.zeta * Dn;
-  const bool skip = S <= tau;            // first condition of the cascade: nothing else is evaluated
+  const bool skip = S <= trigger_bound(lv, 0, S, Dn);   // first condition of the cascade: nothing else is evaluated
 
   if (!skip) {
     // ---- bitonic sort, descending ----
@@ -1417,7 +1423,7 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
     } else {
       jstar = lv.m;
       for (int j = 1; j < lv.m; ++j)
-        if (err[j - 1] <= tau) { jstar = j; break; }
+        if (err[j - 1] <= trigger_bound(lv, j, S, Dn)) { jstar = j; break; }
     }
     int slot = -1, q = -1;
     if (jstar > 0) {

@@ -38,6 +38,10 @@ class Level(C.Structure):
     _fields_ = [("kind", C.c_int32), ("pad", C.c_int32), ("param", C.c_int64)]
 
 
+class Trigger(C.Structure):
+    _fields_ = [("zeta", C.c_float), ("eta", C.c_float)]
+
+
 class Config(C.Structure):
     _fields_ = [
         ("n", C.c_int64), ("d", C.c_int64), ("grad_mode", C.c_int32), ("init_mode", C.c_int32),
@@ -47,6 +51,7 @@ class Config(C.Structure):
         ("master_levels", C.POINTER(Level)), ("m_master", C.c_int32), ("zeta_master", C.c_float),
         ("seed", C.c_uint64), ("flags", C.c_uint32), ("pad", C.c_uint32),
         ("stream", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64),
+        ("worker_triggers", C.POINTER(Trigger)), ("master_triggers", C.POINTER(Trigger)),
     ]
 
 
@@ -94,13 +99,25 @@ def _levels(levels):
     return arr
 
 
+def _triggers(trig, m):
+    if trig is None:
+        return None
+    trig = list(trig)
+    if len(trig) != m:
+        raise ValueError("need one (zeta, eta) pair per cascade position 0..m-1: %d given for %d levels" % (len(trig), m))
+    arr = (Trigger * max(1, m))()
+    for j, (z, e) in enumerate(trig):
+        arr[j].zeta, arr[j].eta = float(z), float(e)
+    return arr
+
+
 def _ptr(t):
     return None if t is None else C.c_void_p(t.data_ptr())
 
 
 def make_config(*, n, d, worker_levels, zeta_worker, master_levels=(), zeta_master=0.0, gamma=0.1, lam=0.1,
                 grad_mode=GRAD_EXTERNAL, init_mode=INIT_FULLGRAD, A=None, labels=None, shard_offsets=None,
-                x0=None, grad0=None, seed=0, flags=0, stream=0):
+                x0=None, grad0=None, seed=0, flags=0, stream=0, worker_triggers=None, master_triggers=None):
     """Fills an adacgd_config.  Tensor arguments are CUDA float32 tensors (borrowed);
     shard_offsets is a host int64 NumPy array.  Returns (cfg, keepalive)."""
     cfg = Config()
@@ -115,7 +132,12 @@ def make_config(*, n, d, worker_levels, zeta_worker, master_levels=(), zeta_mast
     cfg.master_levels, cfg.m_master, cfg.zeta_master = ml, len(list(master_levels)), float(zeta_master)
     cfg.seed, cfg.flags, cfg.pad = int(seed), int(flags), 0
     cfg.stream = C.c_void_p(int(stream)) if stream else None
-    return cfg, (wl, ml, so, A, labels, x0, grad0)
+    tw, tm = _triggers(worker_triggers, cfg.m_worker), _triggers(master_triggers, cfg.m_master)
+    if tw is not None:
+        cfg.worker_triggers = tw
+    if tm is not None:
+        cfg.master_triggers = tm
+    return cfg, (wl, ml, so, A, labels, x0, grad0, tw, tm)
 
 
 def adacgd_workspace_bytes(cfg: Config) -> int:

@@ -47,6 +47,9 @@ def test_workspace_size_is_reported_and_grows_with_problem():
     (dict(worker_levels=[(E.TOPK, 50), (E.QUANT, 2)]), 2),
     (dict(grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_FULLGRAD), 1),
     (dict(grad_mode=5), 1),
+    (dict(worker_triggers=[(1.0, 0.0), (1.0, -0.1)]), 1),
+    (dict(worker_triggers=[(float("inf"), 0.0), (1.0, 0.0)]), 1),
+    (dict(master_triggers=[(0.0, float("nan"))]), 1),
 ])
 def test_bad_configurations_are_rejected(kw, code):
     with pytest.raises(E.AdaCGDError) as ei:
@@ -75,3 +78,11 @@ def test_logistic_shards_validated():
     with pytest.raises(E.AdaCGDError) as ei:
         E.adacgd_workspace_bytes(_cfg(grad_mode=E.GRAD_LOGISTIC, shard_offsets=so)[0])
     assert ei.value.code == 1 and "empty shard" in str(ei.value)
+
+
+def test_triggers_replace_the_zeta_argument():
+    # with a trigger array the scalar is not read, so an invalid scalar is not an error
+    cfg, _ = _cfg(zeta_worker=-1.0, worker_triggers=[(1.0, 0.0), (0.5, 0.1)])
+    assert E.adacgd_workspace_bytes(cfg) > 0
+    with pytest.raises(ValueError):
+        _cfg(worker_triggers=[(1.0, 0.0)])           # one pair per cascade position

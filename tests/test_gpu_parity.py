@@ -620,3 +620,44 @@ def test_many_workers_small_dimension():
     ml = [(O.TOPK, 7), (O.TOPK, 40)]
     orc, _ = _run_external(n, d, wl, 1.2, ml, 0.7, 3, 11, "many-workers")
     assert (orc.level_hist_w > 0).sum() >= 3
+
+
+@pytest.mark.parametrize("n,d,quant", [(4, 900, True), (3, 20000 + 13, True), (2, 140 * 8192 + 36, False),
+                                       (3, 2 * 8192 + 517, False)])
+def test_general_triggers_bit_exact(n, d, quant):
+    """Conditions of the cascade from the wider family err_j <= zeta_j D + eta_j S (Section 4.2,
+    Lemma 2 allow any), different at every position, on both sides; short vectors (one-block
+    kernel), the two-pass sequence with a quantiser level, and the one-pass sequence."""
+    E = _eng()
+    rng = np.random.default_rng(31 * d + n)
+    Ks = sorted({max(1, min(d, k)) for k in (2, d // 100, d // 16, d // 3)})
+    wl = [(O.TOPK, k) for k in Ks]
+    if quant:
+        wl.insert(2, (O.QUANT, 4))
+    wl.append((O.TOPK, d))
+    ml = [(O.TOPK, max(1, d // 50)), (O.TOPK, max(2, d // 5))]
+    steps = 5
+    grads = [make_vectors(rng, n, d, "heavy") for _ in range(steps + 1)]
+    for t in range(1, steps + 1):
+        grads[t] = (grads[t - 1] + grads[t] * np.float32(10.0 ** rng.uniform(-1.5, 0))).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    seen = set()
+    for trial in range(3):
+        tw = [(float(rng.uniform(0, 1.5)) * (trial > 0), float(rng.uniform(0.0, 0.5))) for _ in wl]
+        tw[0] = (tw[0][0], float(rng.uniform(0, 0.2)))
+        tm = [(float(rng.uniform(0, 2)), float(rng.uniform(0, 0.3))) for _ in ml]
+        kw = dict(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=99.0, master_levels=ml, zeta_master=99.0,
+                  worker_triggers=tw, master_triggers=tm, seed=5)
+        orc = O.AdaCGDOracle(**kw)
+        orc.init(x0, grads[0], O.INIT_ZERO)
+        eng = E.AdaCGD(grad_mode=E.GRAD_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), grad0=_cuda(grads[0]),
+                       flags=E.FLAG_ANY_LEVEL_ORDER, **kw)
+        for t in range(1, steps + 1):
+            res, rm = orc.step(grads=grads[t])
+            eng.step(_cuda(grads[t]))
+            compare_step(eng, orc, res, rm, (n, d, trial, t))
+            seen.update(r.level for r in res)
+        assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+        assert eng.state(E.F_M_LEVEL_HIST).tolist() == orc.level_hist_m.tolist()
+        eng.close()
+    assert len(seen) >= 3, seen

@@ -278,3 +278,81 @@ def test_quantiser_level_inside_cascade_is_ef21_with_dense_message():
     c, codes, scale = O.quantize(v, 8, O.dither_uniforms(d, 5, 2, 3))
     assert np.array_equal(r.h_new, (h + c).astype(np.float32))
     assert r.err[1] == O.sum_sq_diff(v, c)
+
+
+# ------------------------------------------------------------ general triggers (Section 4.2, Lemma 2)
+def test_triggers_default_is_the_adacgd_definition():
+    rng = np.random.default_rng(5)
+    levels = [(T, 2), (T, 8), (O.QUANT, 4), (T, 40)]
+    for zeta in (0.0, 0.3, 1.0, 7.0):
+        for _ in range(20):
+            h, y, x = (rng.standard_normal(64).astype(np.float32) for _ in range(3))
+            a = O.adacgd_compress(h, y, x, levels, zeta, seed=3, node=1, step=2)
+            b = O.adacgd_compress(h, y, x, levels, 123.0, seed=3, node=1, step=2, triggers=[(zeta, 0.0)] * 4)
+            assert a.level == b.level and np.array_equal(a.h_new, b.h_new) and a.err == b.err
+
+
+def test_trigger_decision_table_with_both_terms():
+    # v = (4,3,2,1): S = 30, Top-1/2/3 errors 14, 5, 1; D = 4.
+    v = np.array([4.0, -3, 2, -1])
+    levels = [(T, 1), (T, 2), (T, 3), (T, 4)]
+
+    def level(trig):
+        return O.adacgd_compress(np.zeros(4), None, None, levels, 0.0, D_given=4.0, v_given=v, triggers=trig).level
+
+    assert level([(0, 0)] * 4) == 4                                   # nothing is accepted: last level
+    assert level([(7.5, 0), (0, 0), (0, 0), (0, 0)]) == 0             # 30 <= 7.5 * 4
+    assert level([(7.4, 0), (3.5, 0), (0, 0), (0, 0)]) == 1           # 30 > 29.6, 14 <= 14
+    assert level([(0, 0.99), (0, 0.4), (0, 0.2), (0, 0)]) == 2        # 30 > 29.7, 14 > 12, 5 <= 6
+    assert level([(0, 1.0), (0, 0), (0, 0), (0, 0)]) == 0             # eta_0 = 1 always keeps h
+    assert level([(0, 0), (1.25, 0.3), (0, 0), (0, 0)]) == 1          # 14 <= 5 + 9
+    assert level([(0, 0), (1.2, 0.3), (1.25, 0), (0, 0)]) == 2        # 14 > 13.8, 5 <= 5
+    assert level([(0, 0), (0, 0), (0, 0), (0.25, 0)]) == 3            # 1 <= 1
+    assert level([(0, 0), (0, 0), (0, 0), (0.2, 0.005)]) == 4         # 1 > 0.8 + 0.15
+    assert level([(0, 0), (0, 0), (0, 0), (0.2, 0.02)]) == 3          # 1 <= 0.8 + 0.6
+
+
+def test_relative_error_triggers_pick_the_smallest_sufficient_K():
+    """zeta_j = 0, eta_j = eta: the cascade accepts the first Top-K level whose realised error is at
+    most eta ||v||^2.  Recomputed here from the sorted squares: the error of Top-K is the energy
+    of the d - K smallest magnitudes."""
+    rng = np.random.default_rng(11)
+    Ks = [1, 3, 10, 30, 100, 300]
+    levels = [(T, k) for k in Ks]
+    seen = set()
+    for trial in range(60):
+        d = 300
+        v = (rng.standard_normal(d) * np.exp(rng.uniform(0, 4) * rng.standard_normal(d))).astype(np.float64)
+        eta = float(rng.choice([0.5, 0.1, 0.01, 1e-4]))
+        r = O.adacgd_compress(np.zeros(d), None, None, levels, 0.0, D_given=1.0, v_given=v,
+                              triggers=[(0.0, eta)] * len(Ks))
+        sq = np.sort(v * v)                      # ascending
+        tail = np.concatenate([[0.0], np.cumsum(sq)])          # tail[q] = energy of the q smallest
+        want = len(Ks)
+        for j, k in enumerate(Ks[:-1], start=1):
+            if tail[d - k] <= eta * tail[d]:
+                want = j
+                break
+        if min(r.margins) > 1e-9:
+            assert r.level == want, (trial, eta)
+        seen.add(r.level)
+        # contractive by construction with alpha = 1 - eta (last level is the identity here)
+        assert O.sum_sq_diff(r.h_new, v) <= eta * r.S * (1 + 1e-12)
+    assert len(seen) >= 4
+
+
+def test_per_level_zeta_is_first_condition_that_holds():
+    rng = np.random.default_rng(12)
+    levels = [(T, 1), (T, 4), (O.QUANT, 3), (T, 32), (T, 64)]
+    hist = np.zeros(6, dtype=int)
+    for trial in range(200):
+        h, y, x = (rng.standard_normal(64).astype(np.float32) for _ in range(3))
+        y = (x + rng.uniform(0.05, 1.5) * (y - x)).astype(np.float32)
+        trig = [(float(rng.uniform(0, 2)), float(rng.uniform(0, 0.6))) for _ in levels]
+        r = O.adacgd_compress(h, y, x, levels, 0.0, seed=1, node=0, step=trial, triggers=trig)
+        lhs = [r.S] + r.err[:-1]
+        rhs = [float(np.float32(z)) * r.D + float(np.float32(e)) * r.S for z, e in trig]
+        first = next((j for j in range(5) if lhs[j] <= rhs[j]), 5)
+        assert r.level == first
+        hist[r.level] += 1
+    assert (hist > 0).sum() >= 5
