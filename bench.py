@@ -90,13 +90,44 @@ def extra_federated(E, W, torch, n, steps=10, warmup=2):
             "note": "one stream, HIP events around every kernel"}
 
 
-def extra_small_logistic(E, W, torch, wl, steps):
+def extra_sparse_features(E, W, torch, steps=20, warmup=3):
+    """Secondary workload: logistic regression on binary features kept as compressed sparse rows."""
+    wl = W.sparse_features()
+    nnz = int(wl.csr[0][-1])
+    rows = wl.labels.shape[0]
+    x0 = torch.zeros(wl.d, dtype=torch.float32, device="cuda")
+    eng = E.AdaCGD(n=wl.n, d=wl.d, gamma=wl.gamma, lam=wl.lam, worker_levels=wl.worker_levels,
+                   zeta_worker=wl.zeta_worker, master_levels=wl.master_levels, zeta_master=wl.zeta_master,
+                   grad_mode=E.GRAD_LOGISTIC_CSR, labels=torch.from_numpy(wl.labels).cuda(),
+                   shard_offsets=wl.shard_offsets, csr=wl.csr, x0=x0, flags=E.FLAG_KERNEL_TIMING)
+    dt, hist, kms = _timed_steps(eng, E, torch, lambda t: eng.step(), warmup, steps)
+    eng.close()
+    # stored entries: column + gathered x (margins), row + gathered fp64 margin (column sums); per row the
+    # pointer, label and margin; per (worker, column) the column pointer and the gradient written
+    alg = nnz * (4 + 4 + 4 + 8) + rows * (8 + 4 + 8) + wl.n * wl.d * (4 + 4)
+    grad_ms = kms.get("grad_margin", 0.0) + kms.get("grad_cols", 0.0)
+    return {"workload": "sparse binary features: n=%d workers, d=%d, %d rows each, %d stored entries per row, "
+                        "Top-K levels %s, master Top-%d" % (wl.n, wl.d, rows // wl.n, nnz // rows,
+                                                            [k for _, k in wl.worker_levels], wl.master_levels[0][1]),
+            "steps": steps, "ms_per_step": dt / steps * 1e3, "floats_per_sec": wl.n * wl.d * steps / dt,
+            "level_histogram_skip_then_levels": [int(v) for v in hist], "kernels_avg_ms": kms,
+            "gradient_kernels": {"algorithmic_bytes": alg, "avg_ms": grad_ms,
+                                 "GB/s": alg / (grad_ms * 1e-3) / 1e9 if grad_ms else None,
+                                 "dense_matrix_bytes_for_comparison": 4.0 * rows * wl.d},
+            "note": "one stream, HIP events around every kernel"}
+
+
+def extra_small_logistic(E, W, torch, wl, steps, sparse_rows=False):
     """Launch-bound small configurations: steps per second and kernel launches per step only."""
-    A, labels = torch.from_numpy(wl.A).cuda(), torch.from_numpy(wl.labels).cuda()
+    labels = torch.from_numpy(wl.labels).cuda()
     x0 = torch.zeros(wl.d, dtype=torch.float32, device="cuda")
     kw = dict(n=wl.n, d=wl.d, gamma=wl.gamma, lam=wl.lam, worker_levels=wl.worker_levels,
               zeta_worker=wl.zeta_worker, master_levels=wl.master_levels, zeta_master=wl.zeta_master,
-              grad_mode=E.GRAD_LOGISTIC, A=A, labels=labels, shard_offsets=wl.shard_offsets, x0=x0)
+              labels=labels, shard_offsets=wl.shard_offsets, x0=x0)
+    if sparse_rows:
+        kw.update(grad_mode=E.GRAD_LOGISTIC_CSR, csr=W.to_csr(wl.A, binary=True))
+    else:
+        kw.update(grad_mode=E.GRAD_LOGISTIC, A=torch.from_numpy(wl.A).cuda())
     eng = E.AdaCGD(flags=0, **kw)
     eng.step(nsteps=10)
     torch.cuda.synchronize()
@@ -112,8 +143,9 @@ def extra_small_logistic(E, W, torch, wl, steps):
     km = eng.kernel_ms()                   # one timed slot per launch, except select (two launches per slot)
     launches = (sum(cnt for _, cnt in km.values()) + km["w_select"][1] + km["m_select"][1]) / 5.0
     eng.close()
-    return {"workload": "%s: n=%d, d=%d, %d samples each, logistic regression, levels %s"
-                        % (wl.name, wl.n, wl.d, wl.A.shape[0] // wl.n, [k for _, k in wl.worker_levels]),
+    return {"workload": "%s%s: n=%d, d=%d, %d samples each, logistic regression, levels %s"
+                        % (wl.name, " (features as sparse rows)" if sparse_rows else "", wl.n, wl.d,
+                           wl.A.shape[0] // wl.n, [k for _, k in wl.worker_levels]),
             "steps": steps, "ms_per_step": dt / steps * 1e3, "steps_per_sec": steps / dt,
             "kernel_launches_per_step": launches,
             "level_histogram_skip_then_levels_since_init": [int(v) for v in hist],
@@ -244,6 +276,8 @@ def main():
         other.append(extra_federated(E, W, torch, args.federated_n))
         other.append(extra_small_logistic(E, W, torch, W.tiny(), 1000))
         other.append(extra_small_logistic(E, W, torch, W.sparse_logreg(), 1000))
+        other.append(extra_small_logistic(E, W, torch, W.sparse_logreg(), 1000, sparse_rows=True))
+        other.append(extra_sparse_features(E, W, torch))
 
     out = {
         "metric": "adacgd_compressed_floats_per_sec", "value": floats_per_s, "unit": "floats/s",

@@ -81,7 +81,10 @@ enum adacgd_grad_mode {
   ADACGD_GRAD_LOGISTIC = 0, /* engine computes the gradient of the Section 6 objective:
                                f_i(x) = (1/N_i) sum_l log(1+exp(-y_l a_l^T x)) + lambda sum_j x_j^2/(1+x_j^2) */
   ADACGD_GRAD_EXTERNAL = 1, /* caller passes grad f_i(x^{t+1}) to adacgd_step                         */
-  ADACGD_DIFF_EXTERNAL = 2  /* caller passes x - h (the compressor's argument) and ||x-y||^2 directly  */
+  ADACGD_DIFF_EXTERNAL = 2, /* caller passes x - h (the compressor's argument) and ||x-y||^2 directly  */
+  ADACGD_GRAD_LOGISTIC_CSR = 3 /* as GRAD_LOGISTIC, with the features given as compressed sparse rows
+                               (the data sets of Section 6 are sparse, several of them binary); the
+                               gradient is summed over the stored entries only, in a fixed order   */
 };
 
 /* g~_i^0 ("known by nodes" in Algorithm 1's input line; the paper leaves it free). */
@@ -113,8 +116,8 @@ typedef struct {
   int32_t grad_mode;            /* adacgd_grad_mode                                           */
   int32_t init_mode;            /* adacgd_init_mode (DIFF_EXTERNAL requires INIT_ZERO)        */
   const float* A;               /* LOGISTIC: device [sum N_i x d] features; BORROWED for the context's life */
-  const float* labels;          /* LOGISTIC: device [sum N_i], each -1 or +1; BORROWED       */
-  const int64_t* shard_offsets; /* LOGISTIC: host [n+1], rows of worker i are [off[i],off[i+1]); copied */
+  const float* labels;          /* LOGISTIC, LOGISTIC_CSR: device [sum N_i], each -1 or +1; BORROWED */
+  const int64_t* shard_offsets; /* LOGISTIC, LOGISTIC_CSR: host [n+1], rows of worker i are [off[i],off[i+1]); copied */
   const float* x0;              /* device [d] starting point; copied                          */
   const float* grad0;           /* GRAD_EXTERNAL: device [n x d] grad f_i(x^0); copied        */
   float lambda;                 /* regulariser weight                                         */
@@ -136,6 +139,14 @@ typedef struct {
                                             (zeta_worker, 0), the AdaCGD definition; otherwise zeta_worker
                                             is ignored                                                  */
   const adacgd_trigger* master_triggers; /* host [m_master], likewise with zeta_master; NULL allowed   */
+  /* GRAD_LOGISTIC_CSR: the feature matrix [sum N_i x d] in compressed sparse row form, all three in HOST
+   * memory, read and copied by adacgd_workspace_bytes / adacgd_init (the context keeps a device copy of
+   * the rows and a second one sorted by column inside every worker's shard, both in the workspace).
+   * labels and shard_offsets are as in GRAD_LOGISTIC; A is not read. */
+  const int64_t* csr_row_ptr; /* host [rows+1], rows = shard_offsets[n] < 2^31; starts at 0, non-decreasing */
+  const int32_t* csr_col;     /* host [nnz]: columns in [0,d), strictly ascending inside a row; anything
+                                 else is rejected with ADACGD_ERR_ARG before the device is touched     */
+  const float* csr_val;       /* host [nnz], or NULL: every stored entry is 1 (binary features)        */
 } adacgd_config;
 
 /* Device bytes adacgd_init needs for this configuration (workspace and stream
@@ -148,7 +159,7 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out);
 
 /* Runs nsteps iterations of Algorithm 2 (all of: iterate update, local gradients,
  * worker compression with level choice, server aggregation, master compression).
- *   LOGISTIC      ext = ext_D = NULL.
+ *   LOGISTIC, LOGISTIC_CSR   ext = ext_D = NULL.
  *   GRAD_EXTERNAL ext = device [nsteps x n x d], one gradient array per step; ext_D = NULL.
  *   DIFF_EXTERNAL ext = device [nsteps x n x d] difference vectors v_i, ext_D = device
  *                 [nsteps x n] fp64 values of ||x-y||^2; g~_i accumulates C(v_i).

@@ -130,6 +130,19 @@ struct LogisticData {
   double* margins;         // [rows]  s_l = -y_l / (1 + exp(y_l a_l^T x)) / N_i
   double* part;            // [n][row_chunks][d] when row_chunks > 1
   int row_chunks;
+  // Sparse features (GRAD_LOGISTIC_CSR): device copies made at init.  The transposed copy holds
+  // every worker's entries sorted by column, then by row, so that one thread sums a column of a
+  // shard in a fixed order.
+  int csr;                 // 1: the fields below are used instead of A
+  int binary;              // 1: every stored entry is 1 (no value arrays)
+  int64_t nnz;
+  const int64_t* rp;       // [rows+1]
+  const int32_t* ci;       // [nnz] column of each entry, ascending within a row
+  const float* cv;         // [nnz]
+  const int64_t* wbase;    // [n+1]  first entry of each worker = rp[offsets[i]]
+  const uint32_t* cptr;    // [n][d+1]  start of column j of worker i in the transposed copy, relative to wbase[i]
+  const int32_t* trow;     // [nnz] row (global) of each transposed entry
+  const float* tval;       // [nnz]
 };
 
 // launchers (each enqueues on the stream and returns the launch status)

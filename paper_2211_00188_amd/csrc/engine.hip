@@ -242,11 +242,13 @@ struct adacgd_ctx {
 
 namespace {
 
+inline bool logistic_mode(int mode) { return mode == ADACGD_GRAD_LOGISTIC || mode == ADACGD_GRAD_LOGISTIC_CSR; }
+
 int validate(const adacgd_config* cfg, LevelTable* wl, LevelTable* ml, char* err) {
   if (!cfg) { set_err(err, "config is null"); return ADACGD_ERR_ARG; }
   if (cfg->n < 1 || cfg->n > 65535) { set_err(err, "n must be in [1, 65535]"); return ADACGD_ERR_ARG; }
   if (cfg->d < 1 || cfg->d >= (int64_t(1) << 31)) { set_err(err, "d must be in [1, 2^31)"); return ADACGD_ERR_ARG; }
-  if (cfg->grad_mode < 0 || cfg->grad_mode > 2) { set_err(err, "unknown grad_mode"); return ADACGD_ERR_ARG; }
+  if (cfg->grad_mode < 0 || cfg->grad_mode > 3) { set_err(err, "unknown grad_mode"); return ADACGD_ERR_ARG; }
   if (cfg->init_mode < 0 || cfg->init_mode > 1) { set_err(err, "unknown init_mode"); return ADACGD_ERR_ARG; }
   if (cfg->grad_mode == ADACGD_DIFF_EXTERNAL && cfg->init_mode != ADACGD_INIT_ZERO) {
     set_err(err, "DIFF_EXTERNAL requires INIT_ZERO");
@@ -258,13 +260,36 @@ int validate(const adacgd_config* cfg, LevelTable* wl, LevelTable* ml, char* err
   if (rc) return rc;
   rc = build_levels(cfg->master_levels, cfg->m_master, cfg->zeta_master, cfg->master_triggers, cfg->d, cfg->flags, ml, err);
   if (rc) return rc;
-  if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC) {
+  if (logistic_mode(cfg->grad_mode)) {
     if (!cfg->shard_offsets) { set_err(err, "shard_offsets is null"); return ADACGD_ERR_ARG; }
     if (!std::isfinite(cfg->lambda)) { set_err(err, "lambda must be finite"); return ADACGD_ERR_ARG; }
     if (cfg->shard_offsets[0] != 0) { set_err(err, "shard_offsets[0] must be 0"); return ADACGD_ERR_ARG; }
     for (int64_t i = 0; i < cfg->n; ++i)
       if (cfg->shard_offsets[i + 1] <= cfg->shard_offsets[i]) {
         set_err(err, "worker %lld has an empty shard", (long long)i);
+        return ADACGD_ERR_ARG;
+      }
+  }
+  if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC_CSR) {
+    // The kernels index x and the gradient rows with the stored columns: every one is checked here.
+    const int64_t rows = cfg->shard_offsets[cfg->n];
+    const int64_t* rp = cfg->csr_row_ptr;
+    const int32_t* ci = cfg->csr_col;
+    if (rows >= (int64_t(1) << 31)) { set_err(err, "more than 2^31 - 1 rows"); return ADACGD_ERR_ARG; }
+    if (!rp) { set_err(err, "csr_row_ptr is null"); return ADACGD_ERR_ARG; }
+    if (rp[0] != 0) { set_err(err, "csr_row_ptr[0] must be 0"); return ADACGD_ERR_ARG; }
+    for (int64_t l = 0; l < rows; ++l)
+      if (rp[l + 1] < rp[l]) { set_err(err, "csr_row_ptr decreases at row %lld", (long long)l); return ADACGD_ERR_ARG; }
+    if (rp[rows] > 0 && !ci) { set_err(err, "csr_col is null"); return ADACGD_ERR_ARG; }
+    for (int64_t l = 0; l < rows; ++l)
+      for (int64_t k = rp[l]; k < rp[l + 1]; ++k)
+        if (ci[k] < 0 || ci[k] >= cfg->d || (k > rp[l] && ci[k] <= ci[k - 1])) {
+          set_err(err, "row %lld: columns must be in [0, d) and strictly ascending", (long long)l);
+          return ADACGD_ERR_ARG;
+        }
+    for (int64_t i = 0; i < cfg->n; ++i)
+      if (rp[cfg->shard_offsets[i + 1]] - rp[cfg->shard_offsets[i]] >= (int64_t(1) << 32)) {
+        set_err(err, "worker %lld stores 2^32 or more entries", (long long)i);
         return ADACGD_ERR_ARG;
       }
   }
@@ -277,6 +302,10 @@ struct Layout {
   int32_t* row_node;
   double* margins;
   double* part;
+  int64_t *rp, *wbase;
+  int32_t *ci, *trow;
+  float *cv, *tval;
+  uint32_t* cptr;
   size_t w_zero, m_zero;
 };
 
@@ -299,12 +328,12 @@ size_t carve_all(char* base, const adacgd_config* cfg, NodeSet& W, NodeSet& M, L
   L.gi = c.take<float>(n * d);
   if (cfg->grad_mode != ADACGD_DIFF_EXTERNAL) {
     L.yb0 = c.take<float>(n * d);
-    const bool second = cfg->grad_mode == ADACGD_GRAD_LOGISTIC || !(cfg->flags & ADACGD_FLAG_RETAIN_EXT);
+    const bool second = logistic_mode(cfg->grad_mode) || !(cfg->flags & ADACGD_FLAG_RETAIN_EXT);
     L.yb1 = second ? c.take<float>(n * d) : nullptr;
   } else {
     L.yb0 = L.yb1 = nullptr;
   }
-  if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC) {
+  if (logistic_mode(cfg->grad_mode)) {
     const size_t rows = cfg->shard_offsets[n];
     L.offsets = c.take<int64_t>(n + 1);
     L.row_node = c.take<int32_t>(rows);
@@ -313,13 +342,31 @@ size_t carve_all(char* base, const adacgd_config* cfg, NodeSet& W, NodeSet& M, L
   } else {
     L.offsets = nullptr; L.row_node = nullptr; L.margins = nullptr; L.part = nullptr;
   }
+  if (ld.csr) {
+    const size_t rows = cfg->shard_offsets[n], nnz = (size_t)ld.nnz;
+    L.rp = c.take<int64_t>(rows + 1);
+    L.wbase = c.take<int64_t>(n + 1);
+    L.cptr = c.take<uint32_t>(n * (d + 1));
+    L.ci = c.take<int32_t>(nnz);
+    L.trow = c.take<int32_t>(nnz);
+    L.cv = ld.binary ? nullptr : c.take<float>(nnz);
+    L.tval = ld.binary ? nullptr : c.take<float>(nnz);
+  }
   return (c.off + 255) & ~size_t(255);
 }
 
 void shape_logistic(const adacgd_config* cfg, LogisticData& ld) {
   std::memset(&ld, 0, sizeof(ld));
-  if (cfg->grad_mode != ADACGD_GRAD_LOGISTIC) return;
+  if (!logistic_mode(cfg->grad_mode)) return;
   ld.rows = cfg->shard_offsets[cfg->n];
+  if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC_CSR) {
+    ld.csr = 1;
+    ld.binary = cfg->csr_val == nullptr;
+    ld.nnz = cfg->csr_row_ptr[ld.rows];
+    ld.row_chunks = 1;
+    ld.lambda = (double)cfg->lambda;
+    return;
+  }
   int64_t mx = 0;
   for (int64_t i = 0; i < cfg->n; ++i) mx = std::max<int64_t>(mx, cfg->shard_offsets[i + 1] - cfg->shard_offsets[i]);
   ld.max_rows = mx;
@@ -422,7 +469,7 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
   a.seed = c->seed;
   a.step = (uint32_t)c->step;
   a.node_flag = 0;
-  if (c->grad_mode == ADACGD_GRAD_LOGISTIC) {
+  if (logistic_mode(c->grad_mode)) {
     float* fresh = c->yb[c->ycur ^ 1];
     if ((rc = gradients(c, fresh))) return rc;
     a.x = fresh;
@@ -444,7 +491,7 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
     c->cs = c->st;
     HIPCHK(c, hipStreamWaitEvent(c->st, c->ev_worker, 0));
   }
-  if (c->grad_mode == ADACGD_GRAD_LOGISTIC) {
+  if (logistic_mode(c->grad_mode)) {
     c->ycur ^= 1;
   } else if (c->grad_mode == ADACGD_GRAD_EXTERNAL) {
     if (c->flags & ADACGD_FLAG_RETAIN_EXT) c->y_ext = ext;
@@ -532,6 +579,10 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
     set_err(g_err, "A / labels is null");
     return ADACGD_ERR_ARG;
   }
+  if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC_CSR && !cfg->labels) {
+    set_err(g_err, "labels is null");
+    return ADACGD_ERR_ARG;
+  }
   if (cfg->grad_mode == ADACGD_GRAD_EXTERNAL && !cfg->grad0) {
     set_err(g_err, "grad0 is required in GRAD_EXTERNAL mode");
     return ADACGD_ERR_ARG;
@@ -567,6 +618,10 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
   c->yb[0] = L.yb0; c->yb[1] = L.yb1;
   c->ld.A = cfg->A; c->ld.labels = cfg->labels; c->ld.offsets = L.offsets; c->ld.row_node = L.row_node;
   c->ld.margins = L.margins; c->ld.part = L.part;
+  if (c->ld.csr) {
+    c->ld.rp = L.rp; c->ld.wbase = L.wbase; c->ld.cptr = L.cptr; c->ld.ci = L.ci; c->ld.trow = L.trow;
+    c->ld.cv = L.cv; c->ld.tval = L.tval;
+  }
 
   auto fail = [&](int code) { std::memcpy(g_err, c->err, sizeof(g_err)); delete c; return code; };
 #define INITCHK(call)                                                                       \
@@ -582,7 +637,47 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
   INITCHK(launch_fill_u32((uint32_t*)c->W.hist0, 0u, L.w_zero / 4, c->st));
   if (c->has_master) INITCHK(launch_fill_u32((uint32_t*)c->M.hist0, 0u, L.m_zero / 4, c->st));
   INITCHK(launch_copy_f32(c->x, cfg->x0, (size_t)c->d, c->st));
-  if (cfg->grad_mode == ADACGD_GRAD_LOGISTIC) {
+  if (c->ld.csr) {
+    // Device copy of the rows, and of every shard sorted by column (a counting sort that keeps
+    // the row order inside a column), one worker at a time.
+    const int64_t rows = c->ld.rows, d = c->d;
+    const int64_t* rp = cfg->csr_row_ptr;
+    const size_t nnz = (size_t)c->ld.nnz;
+    INITCHK(hipMemcpy(L.rp, rp, (size_t)(rows + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
+    if (nnz) {
+      INITCHK(hipMemcpy(L.ci, cfg->csr_col, nnz * sizeof(int32_t), hipMemcpyHostToDevice));
+      if (L.cv) INITCHK(hipMemcpy(L.cv, cfg->csr_val, nnz * sizeof(float), hipMemcpyHostToDevice));
+    }
+    std::vector<int64_t> wbase((size_t)c->n + 1);
+    std::vector<uint32_t> cp((size_t)d + 1), cur((size_t)d);
+    std::vector<int32_t> trow;
+    std::vector<float> tval;
+    for (int64_t i = 0; i < c->n; ++i) {
+      const int64_t r0 = cfg->shard_offsets[i], r1 = cfg->shard_offsets[i + 1];
+      const int64_t e0 = rp[r0], e1 = rp[r1];
+      wbase[(size_t)i] = e0;
+      std::fill(cp.begin(), cp.end(), 0u);
+      for (int64_t k = e0; k < e1; ++k) ++cp[(size_t)cfg->csr_col[k] + 1];
+      for (int64_t j = 0; j < d; ++j) cp[(size_t)j + 1] += cp[(size_t)j];
+      std::copy(cp.begin(), cp.end() - 1, cur.begin());
+      trow.resize((size_t)(e1 - e0));
+      if (L.tval) tval.resize((size_t)(e1 - e0));
+      for (int64_t l = r0; l < r1; ++l)
+        for (int64_t k = rp[l]; k < rp[l + 1]; ++k) {
+          const uint32_t at = cur[(size_t)cfg->csr_col[k]]++;
+          trow[at] = (int32_t)l;
+          if (L.tval) tval[at] = cfg->csr_val[k];
+        }
+      INITCHK(hipMemcpy(L.cptr + (size_t)i * (size_t)(d + 1), cp.data(), cp.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+      if (e1 > e0) {
+        INITCHK(hipMemcpy(L.trow + e0, trow.data(), trow.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+        if (L.tval) INITCHK(hipMemcpy(L.tval + e0, tval.data(), tval.size() * sizeof(float), hipMemcpyHostToDevice));
+      }
+    }
+    wbase[(size_t)c->n] = rp[rows];
+    INITCHK(hipMemcpy(L.wbase, wbase.data(), wbase.size() * sizeof(int64_t), hipMemcpyHostToDevice));
+  }
+  if (logistic_mode(cfg->grad_mode)) {
     std::vector<int32_t> rn((size_t)c->ld.rows);
     for (int64_t i = 0; i < c->n; ++i)
       for (int64_t l = cfg->shard_offsets[i]; l < cfg->shard_offsets[i + 1]; ++l) rn[(size_t)l] = (int32_t)i;
@@ -609,7 +704,7 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
     INITCHK(launch_fill_u32(c->M.msg_count, 0u, 1, c->st));
     INITCHK(launch_fill_u32((uint32_t*)c->M.level, 0u, 1, c->st));
   }
-  if ((cfg->flags & ADACGD_FLAG_OVERLAP) && cfg->grad_mode != ADACGD_GRAD_LOGISTIC) {
+  if ((cfg->flags & ADACGD_FLAG_OVERLAP) && !logistic_mode(cfg->grad_mode)) {
     INITCHK(hipStreamSynchronize(c->st));     // the worker stream starts from a finished initial state
     INITCHK(hipStreamCreateWithFlags(&c->wst, hipStreamNonBlocking));
     INITCHK(hipEventCreateWithFlags(&c->ev_worker, hipEventDisableTiming));
@@ -623,7 +718,7 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
 int adacgd_step(adacgd_ctx* c, const float* ext, const double* ext_D, int32_t nsteps) {
   if (!c) return ADACGD_ERR_ARG;
   if (nsteps < 0) { set_err(c->err, "nsteps < 0"); return ADACGD_ERR_ARG; }
-  if (c->grad_mode == ADACGD_GRAD_LOGISTIC) {
+  if (logistic_mode(c->grad_mode)) {
     if (ext || ext_D) { set_err(c->err, "LOGISTIC mode takes no external arrays"); return ADACGD_ERR_STATE; }
   } else {
     if (!ext) { set_err(c->err, "ext is null"); return ADACGD_ERR_ARG; }

@@ -239,6 +239,49 @@ __global__ __launch_bounds__(kBlock) void k_grad_finish(LogisticData ld, const f
 }
 
 // ---------------------------------------------------------------------------
+// The same gradient for sparse features (rows in CSR form, and per worker by column).
+// margins: LPR lanes per row (a power of two) sum the row's stored entries in fp64.
+// cols   : one thread per (worker, column) sums s_l a_lj over the column's entries of that
+//          worker's shard, in row order, then adds the regulariser and rounds once.
+// ---------------------------------------------------------------------------
+template <int LPR>
+__global__ __launch_bounds__(kBlock) void k_csr_margins(LogisticData ld, const float* __restrict__ x) {
+  const int64_t l = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LPR;
+  const int sub = threadIdx.x % LPR;
+  const bool live = l < ld.rows;
+  const int64_t b = live ? ld.rp[l] : 0, e = live ? ld.rp[l + 1] : 0;
+  double acc = 0.0;
+  for (int64_t k = b + sub; k < e; k += LPR) {
+    const double a = ld.binary ? 1.0 : (double)ld.cv[k];
+    acc = fma(a, (double)x[ld.ci[k]], acc);
+  }
+#pragma unroll
+  for (int o = LPR >> 1; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+  if (live && sub == 0) {
+    const int node = ld.row_node[l];
+    const double N = (double)(ld.offsets[node + 1] - ld.offsets[node]);
+    const double yl = (double)ld.labels[l];
+    ld.margins[l] = -yl / (1.0 + exp(yl * acc)) / N;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_csr_cols(LogisticData ld, const float* __restrict__ x,
+                                                      float* __restrict__ grads, int64_t d) {
+  const int node = blockIdx.y;
+  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (j >= d) return;
+  const uint32_t* __restrict__ cp = ld.cptr + (size_t)node * (size_t)(d + 1);
+  const int64_t w0 = ld.wbase[node];
+  const int64_t b = w0 + cp[j], e = w0 + cp[j + 1];
+  double acc = 0.0;
+  for (int64_t k = b; k < e; ++k) {
+    const double a = ld.binary ? 1.0 : (double)ld.tval[k];
+    acc = fma(ld.margins[ld.trow[k]], a, acc);
+  }
+  grads[(size_t)node * d + j] = (float)(acc + reg_grad(ld.lambda, (double)x[j]));
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 static inline unsigned blocks_for(size_t count, unsigned cap = 65535u * 16u) {
@@ -289,6 +332,15 @@ hipError_t launch_copy_f32(float* dst, const float* src, size_t count, hipStream
 
 hipError_t launch_grad_margins(const LogisticData& ld, const float* x, int64_t d, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  if (ld.csr) {
+    const int64_t per_row = ld.nnz / (ld.rows > 0 ? ld.rows : 1);
+    const int lpr = per_row >= 128 ? 64 : per_row >= 16 ? 16 : 4;
+    const unsigned grid = (unsigned)((ld.rows * lpr + kBlock - 1) / kBlock);
+    if (lpr == 64) hipLaunchKernelGGL((k_csr_margins<64>), dim3(grid), dim3(kBlock), 0, st, ld, x);
+    else if (lpr == 16) hipLaunchKernelGGL((k_csr_margins<16>), dim3(grid), dim3(kBlock), 0, st, ld, x);
+    else hipLaunchKernelGGL((k_csr_margins<4>), dim3(grid), dim3(kBlock), 0, st, ld, x);
+    return hipGetLastError();
+  }
   const int vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(ld.A) & 15u) == 0) &&
                   ((reinterpret_cast<uintptr_t>(x) & 15u) == 0);
   hipLaunchKernelGGL(k_grad_margins, dim3((unsigned)((ld.rows + 3) / 4)), dim3(kBlock), 0, st, ld, x, d, vec);
@@ -297,6 +349,10 @@ hipError_t launch_grad_margins(const LogisticData& ld, const float* x, int64_t d
 
 hipError_t launch_grad_cols(const LogisticData& ld, const float* x, float* grads, int n, int64_t d, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
+  if (ld.csr) {
+    hipLaunchKernelGGL(k_csr_cols, dim3((unsigned)((d + kBlock - 1) / kBlock), n), dim3(kBlock), 0, st, ld, x, grads, d);
+    return hipGetLastError();
+  }
   const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(ld.A) & 15u) == 0);
   const int rpc = (int)((ld.max_rows + ld.row_chunks - 1) / ld.row_chunks);
   const int64_t cols_per_block = (int64_t)kBlock * (vec ? 4 : 1);

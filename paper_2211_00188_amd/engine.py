@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libadacgd.so")
 
 TOPK, QUANT = 0, 1
-GRAD_LOGISTIC, GRAD_EXTERNAL, DIFF_EXTERNAL = 0, 1, 2
+GRAD_LOGISTIC, GRAD_EXTERNAL, DIFF_EXTERNAL, GRAD_LOGISTIC_CSR = 0, 1, 2, 3
 INIT_FULLGRAD, INIT_ZERO = 0, 1
 FLAG_ANY_LEVEL_ORDER, FLAG_RETAIN_EXT, FLAG_KERNEL_TIMING, FLAG_TWO_PASS, FLAG_OVERLAP = 1, 2, 4, 8, 16
 MAX_LEVELS = 16
@@ -52,6 +52,7 @@ class Config(C.Structure):
         ("seed", C.c_uint64), ("flags", C.c_uint32), ("pad", C.c_uint32),
         ("stream", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64),
         ("worker_triggers", C.POINTER(Trigger)), ("master_triggers", C.POINTER(Trigger)),
+        ("csr_row_ptr", C.c_void_p), ("csr_col", C.c_void_p), ("csr_val", C.c_void_p),
     ]
 
 
@@ -117,9 +118,11 @@ def _ptr(t):
 
 def make_config(*, n, d, worker_levels, zeta_worker, master_levels=(), zeta_master=0.0, gamma=0.1, lam=0.1,
                 grad_mode=GRAD_EXTERNAL, init_mode=INIT_FULLGRAD, A=None, labels=None, shard_offsets=None,
-                x0=None, grad0=None, seed=0, flags=0, stream=0, worker_triggers=None, master_triggers=None):
+                x0=None, grad0=None, seed=0, flags=0, stream=0, worker_triggers=None, master_triggers=None,
+                csr=None):
     """Fills an adacgd_config.  Tensor arguments are CUDA float32 tensors (borrowed);
-    shard_offsets is a host int64 NumPy array.  Returns (cfg, keepalive)."""
+    shard_offsets is a host int64 NumPy array; csr = (row_ptr, col, val or None) are host
+    NumPy arrays (GRAD_LOGISTIC_CSR).  Returns (cfg, keepalive)."""
     cfg = Config()
     wl, ml = _levels(list(worker_levels)), _levels(list(master_levels))
     so = None if shard_offsets is None else np.ascontiguousarray(shard_offsets, dtype=np.int64)
@@ -137,7 +140,16 @@ def make_config(*, n, d, worker_levels, zeta_worker, master_levels=(), zeta_mast
         cfg.worker_triggers = tw
     if tm is not None:
         cfg.master_triggers = tm
-    return cfg, (wl, ml, so, A, labels, x0, grad0, tw, tm)
+    keep_csr = None
+    if csr is not None:
+        rp = np.ascontiguousarray(csr[0], dtype=np.int64)
+        ci = np.ascontiguousarray(csr[1], dtype=np.int32)
+        cv = None if csr[2] is None else np.ascontiguousarray(csr[2], dtype=np.float32)
+        cfg.csr_row_ptr = rp.ctypes.data_as(C.c_void_p)
+        cfg.csr_col = ci.ctypes.data_as(C.c_void_p)
+        cfg.csr_val = None if cv is None else cv.ctypes.data_as(C.c_void_p)
+        keep_csr = (rp, ci, cv)
+    return cfg, (wl, ml, so, A, labels, x0, grad0, tw, tm, keep_csr)
 
 
 def adacgd_workspace_bytes(cfg: Config) -> int:

@@ -39,6 +39,7 @@ class LogisticWorkload:
     zeta_worker: float
     zeta_master: float
     T: int
+    csr: tuple = None          # (row_ptr, col, val or None) when the features are kept as sparse rows
 
     def shards(self):
         o = self.shard_offsets
@@ -84,6 +85,19 @@ def _planted_labels(rng, A, w):
     return np.where(p - rng.random(A.shape[0]) > 0, 1.0, -1.0).astype(np.float32)
 
 
+def to_csr(A: np.ndarray, binary: bool = False):
+    """Compressed-sparse-row arrays (row_ptr int64, col int32, val float32 or None) of the
+    non-zero entries of a dense matrix, columns ascending inside every row.  `binary`: the
+    matrix holds only 0 and 1 and no value array is returned."""
+    rows, cols = np.nonzero(A)                      # row-major order: rows, then columns, ascending
+    row_ptr = np.zeros(A.shape[0] + 1, dtype=np.int64)
+    np.cumsum(np.bincount(rows, minlength=A.shape[0]), out=row_ptr[1:])
+    val = None if binary else np.ascontiguousarray(A[rows, cols], dtype=np.float32)
+    if binary:
+        assert np.all(A[rows, cols] == 1)
+    return row_ptr, cols.astype(np.int32), val
+
+
 def tiny(seed=1, n=4, d=100, N=64, T=100, zeta=1.0) -> LogisticWorkload:
     """n=4 workers, d=100, 64 dense N(0,1) samples each, labels from a planted
     logistic model; Top-K levels {1,5,10,25,d}, master Top-25."""
@@ -124,6 +138,26 @@ def federated(seed=5, n=1000, d=65536, N=32, T=200, zeta=1.0, clusters=10) -> Lo
     lv = sort_levels(list(dict.fromkeys(lv)), d)
     return LogisticWorkload("federated", n, d, A, labels, np.arange(n + 1, dtype=np.int64) * N, 0.1, 0.1,
                             lv, [(TOPK, min(d, 4096))], zeta, 0.0, T)
+
+
+def sparse_features(seed=6, n=200, d=65536, N=1000, per_row=64, T=50, zeta=1.0) -> LogisticWorkload:
+    """Binary features kept as sparse rows only (no dense copy): every row stores `per_row` ones, one in
+    each of `per_row` equal column strata (so the columns of a row are distinct and ascending); labels
+    from a planted weight vector with 5 % flips.  Stands in for high-dimensional sparse LIBSVM-style
+    data split over many workers."""
+    rng = _rng(seed)
+    rows = n * N
+    stride = d // per_row
+    col = (np.arange(per_row, dtype=np.int64)[None, :] * stride
+           + rng.integers(0, stride, size=(rows, per_row))).astype(np.int32)
+    w = rng.standard_normal(d)
+    z = w[col].sum(axis=1)
+    labels = np.where(z - np.median(z) > 0, 1.0, -1.0)
+    labels = np.where(rng.random(rows) < 0.05, -labels, labels).astype(np.float32)
+    row_ptr = np.arange(rows + 1, dtype=np.int64) * per_row
+    lv = [(TOPK, ratio_K(r, d)) for r in (1e-3, 1e-2, 5e-2, 0.25)]
+    return LogisticWorkload("sparse_features", n, d, None, labels, np.arange(n + 1, dtype=np.int64) * N, 0.1, 0.5,
+                            lv, [(TOPK, ratio_K(0.05, d))], zeta, 0.0, T, csr=(row_ptr, col.reshape(-1), None))
 
 
 def kernel_stress(seed=3, n=32, d=1 << 20, T=50, zeta=1.0) -> VectorWorkload:

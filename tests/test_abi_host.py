@@ -86,3 +86,29 @@ def test_triggers_replace_the_zeta_argument():
     assert E.adacgd_workspace_bytes(cfg) > 0
     with pytest.raises(ValueError):
         _cfg(worker_triggers=[(1.0, 0.0)])           # one pair per cascade position
+
+
+def _csr_cfg(row_ptr, col, val=None, d=6, n=2, offsets=(0, 2, 3)):
+    return _cfg(n=n, d=d, worker_levels=[(E.TOPK, 1)], master_levels=[], grad_mode=E.GRAD_LOGISTIC_CSR,
+                shard_offsets=np.array(offsets, dtype=np.int64), csr=(row_ptr, col, val))
+
+
+def test_sparse_rows_are_validated_on_the_host():
+    ok = _csr_cfg([0, 2, 2, 4], [1, 5, 0, 3])
+    assert E.adacgd_workspace_bytes(ok[0]) > 0
+    with_values = _csr_cfg([0, 2, 2, 4], [1, 5, 0, 3], [0.5, -1, 2, 3])
+    assert E.adacgd_workspace_bytes(with_values[0]) > E.adacgd_workspace_bytes(ok[0])
+    for row_ptr, col, what in [
+        ([1, 2, 2, 4], [1, 5, 0, 3], "row_ptr[0]"),
+        ([0, 2, 1, 4], [1, 5, 0, 3], "decreases"),
+        ([0, 2, 2, 4], [1, 6, 0, 3], "columns"),        # column == d
+        ([0, 2, 2, 4], [1, 5, 0, -1], "columns"),
+        ([0, 2, 2, 4], [5, 1, 0, 3], "columns"),        # not ascending
+        ([0, 2, 2, 4], [1, 1, 0, 3], "columns"),        # duplicate
+    ]:
+        with pytest.raises(E.AdaCGDError) as ei:
+            E.adacgd_workspace_bytes(_csr_cfg(row_ptr, col)[0])
+        assert ei.value.code == 1 and what in str(ei.value), (row_ptr, col, str(ei.value))
+    cfg, _ = _cfg(grad_mode=E.GRAD_LOGISTIC_CSR, shard_offsets=np.array([0, 1, 2, 3, 4], dtype=np.int64))
+    with pytest.raises(E.AdaCGDError):
+        E.adacgd_workspace_bytes(cfg)               # no row_ptr

@@ -661,3 +661,90 @@ def test_general_triggers_bit_exact(n, d, quant):
         assert eng.state(E.F_M_LEVEL_HIST).tolist() == orc.level_hist_m.tolist()
         eng.close()
     assert len(seen) >= 3, seen
+
+
+def _csr_engine(wl, csr, x0=None, **kw):
+    E = _eng()
+    x0 = _cuda(np.zeros(wl.d, dtype=np.float32) if x0 is None else x0)
+    return E.AdaCGD(n=wl.n, d=wl.d, gamma=wl.gamma, lam=wl.lam, worker_levels=wl.worker_levels,
+                    zeta_worker=wl.zeta_worker, master_levels=wl.master_levels, zeta_master=wl.zeta_master,
+                    grad_mode=E.GRAD_LOGISTIC_CSR, labels=_cuda(wl.labels), shard_offsets=wl.shard_offsets,
+                    csr=csr, x0=x0, **kw)
+
+
+def _sparsify(wl, density, rng, binary):
+    """Keeps a random subset of the entries of a dense workload (some rows and columns end up
+    empty); `binary` replaces the kept entries by 1."""
+    keep = rng.random(wl.A.shape) < density
+    keep[rng.integers(0, wl.A.shape[0], 3)] = False          # empty rows
+    keep[:, rng.integers(0, wl.d, 2)] = False                # empty columns
+    wl.A = np.where(keep, np.float32(1) if binary else wl.A, np.float32(0)).astype(np.float32)
+    if wl.A.shape[1] > 3:
+        wl.A[:, 3] = 1 if binary else wl.A[:, 3] + 2         # a dense column: long per-column lists
+    return wl
+
+
+@pytest.mark.parametrize("n,d,N,density,binary", [(4, 100, 64, 0.1, False), (3, 101, 50, 0.5, True),
+                                                  (5, 8192 + 12, 7, 0.02, False), (2, 300, 2500, 0.04, True),
+                                                  (2, 1500, 40, 0.6, False)])
+def test_sparse_gradient_kernel_matches_oracle(n, d, N, density, binary):
+    """grad f_i(x) from compressed sparse rows against the oracle on the same matrix stored
+    densely: both accumulate in fp64 and round once, so values agree to one fp32 unit in the
+    last place (the sparse kernels add the stored entries only, in another order)."""
+    E = _eng()
+    rng = np.random.default_rng(7 * d + N)
+    wl = _sparsify(W.tiny(seed=22, n=n, d=d, N=N), density, rng, binary)
+    csr = W.to_csr(wl.A, binary)
+    for scale in (0.0, 0.05, 3.0):
+        x0 = (scale * rng.standard_normal(d)).astype(np.float32)
+        eng = _csr_engine(wl, csr, x0=x0)
+        got = eng.state(E.F_GRAD)
+        eng.close()
+        ref = np.stack([O.logistic_grad(A, y, x0, np.float64(np.float32(wl.lam)), np.float32) for A, y in wl.shards()])
+        # sums of equal terms of both signs cancel to a residue at the fp64 rounding level (1e-18 next
+        # to terms of 1e-2) whose value depends on the order: one fp32 unit, or that residue
+        ulp = np.maximum(np.spacing(np.abs(ref)).astype(np.float64), 1e-15)
+        assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= ulp)
+        assert_close_rel(got, ref, TRAJ_RTOL, ("grad", n, d, N, scale))
+        if scale > 0:
+            assert np.mean(bits(got) != bits(ref)) < 0.01
+
+
+def test_trajectory_sparse_logreg_from_sparse_rows():
+    """The binary-feature workload run from its compressed sparse rows: same bars as the dense run."""
+    E = _eng()
+    wl = W.sparse_logreg(T=300)
+    orc = _logistic_oracle(wl)
+    eng = _csr_engine(wl, W.to_csr(wl.A, binary=True))
+    assert_close_rel(eng.state(E.F_GRAD), orc.y, TRAJ_RTOL, "grad0")
+    for t in range(wl.T):
+        orc.step()
+        eng.step()
+        if (t + 1) % 10 == 0:
+            assert_close_rel(eng.state(E.F_X), orc.x, TRAJ_RTOL, ("x", t))
+            assert_close_rel(eng.state(E.F_GRAD), orc.y, TRAJ_RTOL, ("grad", t))
+            assert_close_rel(eng.state(E.F_G), orc.g, TRAJ_RTOL, ("g", t))
+    assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+    eng.close()
+
+
+def test_trajectory_sparse_features_reduced():
+    """The sparse-rows workload of the benchmark at a size the oracle handles (dense copy made here)."""
+    E = _eng()
+    wl = W.sparse_features(n=6, d=8192 + 128, N=40, per_row=16, T=25)
+    row_ptr, col, _ = wl.csr
+    A = np.zeros((wl.labels.shape[0], wl.d), dtype=np.float32)
+    A[np.repeat(np.arange(A.shape[0]), np.diff(row_ptr)), col] = 1
+    wl.A = A
+    orc = _logistic_oracle(wl)
+    eng = _csr_engine(wl, wl.csr)
+    assert_close_rel(eng.state(E.F_GRAD), orc.y, TRAJ_RTOL, "grad0")
+    for t in range(wl.T):
+        orc.step()
+        eng.step()
+        assert_close_rel(eng.state(E.F_X), orc.x, TRAJ_RTOL, ("x", t))
+        assert_close_rel(eng.state(E.F_GRAD), orc.y, TRAJ_RTOL, ("grad", t))
+        assert_close_rel(eng.state(E.F_G), orc.g, TRAJ_RTOL, ("g", t))
+    assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+    assert (orc.level_hist_w > 0).sum() >= 2
+    eng.close()
