@@ -104,6 +104,9 @@ struct NodeSet {
   int16_t* qcodes;      // [nn][d] (only with quantiser levels)
   float* qscale;        // [nn]
   double* accbuf;       // [d] fp64 sums of the sparse messages (only with quantiser levels)
+  int AS;               // aggregation: blocks that share one group's workers (1 = one block per group)
+  double* agg_part;     // [AS][groups][kWaveTile] their partial sums (AS > 1)
+  uint32_t* agg_done;   // [groups][kArriveFan+1] arrival counters (AS > 1); zero between launches
 };
 
 // Operands of one application of the compressor C_{h,y}(x) to every node of a set.

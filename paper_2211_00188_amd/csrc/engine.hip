@@ -124,6 +124,7 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.ncand = c.take<uint32_t>(nn * kCounterStride);
   ns.done = c.take<uint32_t>(nn * (kArriveFan + 1) * kCounterStride);
   ns.kmax = c.take<uint32_t>(nn);
+  ns.agg_done = ns.AS > 1 ? c.take<uint32_t>((size_t)ns.groups * (kArriveFan + 1) * kCounterStride) : nullptr;
   ns.level_hist = c.take<unsigned long long>(m + 2);
   ns.repairs = ns.level_hist + m + 1;
   // everything up to here must start at zero
@@ -167,6 +168,7 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.qcodes = nq ? c.take<int16_t>(nn * (size_t)ns.d) : nullptr;
   ns.qscale = c.take<float>(nn);
   ns.accbuf = nq ? c.take<double>((size_t)ns.d) : nullptr;
+  ns.agg_part = ns.AS > 1 ? c.take<double>((size_t)ns.AS * ns.groups * kWaveTile) : nullptr;
 }
 
 void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
@@ -196,6 +198,15 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
   if (ns.G < 1) ns.G = 1;
   // select kernels: up to 8 blocks per (Top-K size, node) share a long list (most lists are
   // short and all but a few blocks exit at once, so the launch should stay small)
+  // aggregation: one block per group of 2048 coordinates adds every worker's share; short vectors
+  // with many workers have too few groups to fill the device, so up to 1024 / groups blocks share
+  // a group's workers (at least 8 workers each) and the last one to finish adds their partial sums
+  ns.AS = 1;
+  if (nn >= 64 && ns.groups < 256) {
+    const int by_workers = (nn + 7) / 8, by_groups = 1024 / ns.groups;
+    ns.AS = by_workers < by_groups ? by_workers : by_groups;
+    if (ns.AS < 1) ns.AS = 1;
+  }
   int gz = (int)((d + 262143) / 262144);
   ns.GZ = gz < 1 ? 1 : (gz > 8 ? 8 : gz);
 }

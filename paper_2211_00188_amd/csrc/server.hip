@@ -55,15 +55,19 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
   __shared__ double acc[kWaveTile];
   __shared__ uint32_t s_lo[kBlock], s_pre[kBlock + 1];
   __shared__ uint32_t lds4[4];
+  __shared__ int s_flag;
   const int g = blockIdx.x, tid = threadIdx.x;
   const int64_t d = ws.d;
   const int64_t base = (int64_t)g * kWaveTile;
+  // this block's share of the workers (all of them unless several blocks share the group)
+  const int AS = gridDim.y, per = (ws.nn + AS - 1) / AS;
+  const int n_lo = (int)blockIdx.y * per, n_hi = min(ws.nn, n_lo + per);
   for (int c = tid; c < kWaveTile; c += kBlock) acc[c] = 0.0;
   __syncthreads();
-  for (int n0 = 0; n0 < ws.nn; n0 += kBlock) {
+  for (int n0 = n_lo; n0 < n_hi; n0 += kBlock) {
     const int i = n0 + tid;
     uint32_t lo = 0, cnt = 0;
-    if (i < ws.nn) {
+    if (i < n_hi) {
       if (ws.sel_slot[i] >= 0) {
         lo = ws.grp_off[(size_t)i * (ws.groups + 1) + g];
         cnt = ws.grp_off[(size_t)i * (ws.groups + 1) + g + 1] - lo;
@@ -86,6 +90,17 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
       unsafeAtomicAdd(&acc[ws.msg_idx[off] - base], (double)ws.msg_val[off]);
     }
     __syncthreads();
+  }
+  if (AS > 1) {
+    // partial sums of the blocks that share this group; the last one to arrive adds them in block order
+    for (int c = tid; c < kWaveTile; c += kBlock)
+      st_coherent(&ws.agg_part[((size_t)blockIdx.y * ws.groups + g) * kWaveTile + c], acc[c]);
+    if (!arrive_last(&ws.agg_done[(size_t)g * (kArriveFan + 1) * kCounterStride], (uint32_t)AS, blockIdx.y, &s_flag)) return;
+    for (int c = tid; c < kWaveTile; c += kBlock) {
+      double t = 0.0;
+      for (int b = 0; b < AS; ++b) t += ld_coherent(&ws.agg_part[((size_t)b * ws.groups + g) * kWaveTile + c]);
+      acc[c] = t;       // thread tid wrote and reads the same entries: no barrier needed
+    }
   }
   if (DENSE_LATER) {
     for (int c = tid; c < kWaveTile; c += kBlock)
@@ -305,10 +320,10 @@ hipError_t launch_mean(const float* gi, float* o0, float* o1, float* o2, int n, 
 hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_new, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
   if (ws.lv.nq == 0) {
-    hipLaunchKernelGGL((k_aggregate<false>), dim3(ws.groups), dim3(kBlock), 0, st, ws, gt_old, gt_new);
+    hipLaunchKernelGGL((k_aggregate<false>), dim3(ws.groups, ws.AS), dim3(kBlock), 0, st, ws, gt_old, gt_new);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL((k_aggregate<true>), dim3(ws.groups), dim3(kBlock), 0, st, ws, gt_old, gt_new);
+  hipLaunchKernelGGL((k_aggregate<true>), dim3(ws.groups, ws.AS), dim3(kBlock), 0, st, ws, gt_old, gt_new);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_aggregate_dense, dim3((unsigned)((ws.d + kDenseCols - 1) / kDenseCols)), dim3(64 * kDenseWaves), 0, st, ws,
