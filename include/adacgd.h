@@ -90,7 +90,10 @@ enum adacgd_grad_mode {
 /* g~_i^0 ("known by nodes" in Algorithm 1's input line; the paper leaves it free). */
 enum adacgd_init_mode {
   ADACGD_INIT_FULLGRAD = 0, /* g~_i^0 = grad f_i(x^0)  */
-  ADACGD_INIT_ZERO = 1      /* g~_i^0 = 0              */
+  ADACGD_INIT_ZERO = 1,     /* g~_i^0 = 0              */
+  ADACGD_INIT_COMPRESSED = 2 /* g~_i^0 = C_m(grad f_i(x^0)), C_m the last worker level, which must be a
+                               Top-K sparsifier: the start of EF21 and CLAG when only a compressed
+                               gradient can be sent in round 0 */
 };
 
 enum adacgd_flags {

@@ -260,7 +260,7 @@ int validate(const adacgd_config* cfg, LevelTable* wl, LevelTable* ml, char* err
   if (cfg->n < 1 || cfg->n > 65535) { set_err(err, "n must be in [1, 65535]"); return ADACGD_ERR_ARG; }
   if (cfg->d < 1 || cfg->d >= (int64_t(1) << 31)) { set_err(err, "d must be in [1, 2^31)"); return ADACGD_ERR_ARG; }
   if (cfg->grad_mode < 0 || cfg->grad_mode > 3) { set_err(err, "unknown grad_mode"); return ADACGD_ERR_ARG; }
-  if (cfg->init_mode < 0 || cfg->init_mode > 1) { set_err(err, "unknown init_mode"); return ADACGD_ERR_ARG; }
+  if (cfg->init_mode < 0 || cfg->init_mode > 2) { set_err(err, "unknown init_mode"); return ADACGD_ERR_ARG; }
   if (cfg->grad_mode == ADACGD_DIFF_EXTERNAL && cfg->init_mode != ADACGD_INIT_ZERO) {
     set_err(err, "DIFF_EXTERNAL requires INIT_ZERO");
     return ADACGD_ERR_ARG;
@@ -269,6 +269,10 @@ int validate(const adacgd_config* cfg, LevelTable* wl, LevelTable* ml, char* err
   if (cfg->m_worker < 1) { set_err(err, "at least one worker level is required"); return ADACGD_ERR_ARG; }
   int rc = build_levels(cfg->worker_levels, cfg->m_worker, cfg->zeta_worker, cfg->worker_triggers, cfg->d, cfg->flags, wl, err);
   if (rc) return rc;
+  if (cfg->init_mode == ADACGD_INIT_COMPRESSED && wl->kind[wl->m - 1] != kTopK) {
+    set_err(err, "INIT_COMPRESSED needs a Top-K sparsifier as the last worker level");
+    return ADACGD_ERR_ARG;
+  }
   rc = build_levels(cfg->master_levels, cfg->m_master, cfg->zeta_master, cfg->master_triggers, cfg->d, cfg->flags, ml, err);
   if (rc) return rc;
   if (logistic_mode(cfg->grad_mode)) {
@@ -703,6 +707,29 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
   }
   if (cfg->init_mode == ADACGD_INIT_FULLGRAD) INITCHK(launch_copy_f32(c->gi, c->yb[0], nd, c->st));
   else INITCHK(launch_fill_u32((uint32_t*)c->gi, 0u, nd, c->st));
+  if (cfg->init_mode == ADACGD_INIT_COMPRESSED) {
+    // g~_i^0 = C_m(grad f_i(x^0)): one application of the compressor with the last level as the only
+    // one, h = 0 and a zero trigger (kept only if the gradient is zero, and then h = 0 is the answer)
+    NodeSet one = c->W;
+    const LevelTable& lv = c->W.lv;
+    one.lv.m = 1;
+    one.lv.kind[0] = kTopK;
+    one.lv.ref[0] = lv.ref[lv.m - 1];
+    one.lv.tz[0] = 0.0;
+    one.lv.te[0] = 0.0;
+    PassArgs a{};
+    a.x = c->yb[0];
+    a.y = c->yb[0];
+    a.h = c->gi;
+    a.seed = c->seed;
+    const bool timing = c->timing;
+    c->timing = false;
+    const int rc1 = compress(c, one, a, ADACGD_K_W_SAMPLE, nullptr);
+    c->timing = timing;
+    if (rc1) return fail(rc1);
+    // the counters of that application do not belong to the run
+    INITCHK(launch_fill_u32((uint32_t*)c->W.level_hist, 0u, (size_t)(lv.m + 2) * 2, c->st));
+  }
   INITCHK(launch_mean(c->gi, c->gt[0], c->gt[1], c->g_own, (int)c->n, c->d, c->st));
   // message tables start empty
   INITCHK(launch_fill_u32((uint32_t*)c->W.sel_slot, 0xFFFFFFFFu, (size_t)c->n, c->st));

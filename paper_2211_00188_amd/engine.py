@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libadacgd.so")
 
 TOPK, QUANT = 0, 1
 GRAD_LOGISTIC, GRAD_EXTERNAL, DIFF_EXTERNAL, GRAD_LOGISTIC_CSR = 0, 1, 2, 3
-INIT_FULLGRAD, INIT_ZERO = 0, 1
+INIT_FULLGRAD, INIT_ZERO, INIT_COMPRESSED = 0, 1, 2
 FLAG_ANY_LEVEL_ORDER, FLAG_RETAIN_EXT, FLAG_KERNEL_TIMING, FLAG_TWO_PASS, FLAG_OVERLAP = 1, 2, 4, 8, 16
 MAX_LEVELS = 16
 

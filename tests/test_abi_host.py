@@ -47,6 +47,8 @@ def test_workspace_size_is_reported_and_grows_with_problem():
     (dict(worker_levels=[(E.TOPK, 50), (E.QUANT, 2)]), 2),
     (dict(grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_FULLGRAD), 1),
     (dict(grad_mode=5), 1),
+    (dict(init_mode=3), 1),
+    (dict(init_mode=E.INIT_COMPRESSED, worker_levels=[(E.TOPK, 1), (E.QUANT, 8)]), 1),
     (dict(worker_triggers=[(1.0, 0.0), (1.0, -0.1)]), 1),
     (dict(worker_triggers=[(float("inf"), 0.0), (1.0, 0.0)]), 1),
     (dict(master_triggers=[(0.0, float("nan"))]), 1),

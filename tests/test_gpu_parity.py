@@ -748,3 +748,32 @@ def test_trajectory_sparse_features_reduced():
     assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
     assert (orc.level_hist_w > 0).sum() >= 2
     eng.close()
+
+
+@pytest.mark.parametrize("n,d", [(4, 700), (3, 2 * 8192 + 516), (2, 130 * 8192)])
+def test_compressed_initial_estimators_bit_exact(n, d):
+    """g~_i^0 = Top-K(grad f_i(x^0)) with the last level's K (the CLAG / EF21 start), then a few steps."""
+    E = _eng()
+    rng = np.random.default_rng(d + n)
+    wl = [(O.TOPK, max(1, d // 200)), (O.TOPK, max(2, d // 20))]
+    grads = [make_vectors(rng, n, d, "heavy") for _ in range(4)]
+    grads[0][0, : d // 2] = 0.0                        # a gradient with many zeros
+    if n > 2:
+        grads[0][2] = 0.0                              # ... and one that is zero
+    for t in range(1, 4):
+        grads[t] = (grads[t - 1] + grads[t] * np.float32(0.2)).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    orc = O.AdaCGDOracle(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0)
+    orc.init(x0, grads[0], O.INIT_COMPRESSED)
+    eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0, grad_mode=E.GRAD_EXTERNAL,
+                   init_mode=E.INIT_COMPRESSED, x0=_cuda(x0), grad0=_cuda(grads[0]))
+    assert np.array_equal(bits(eng.state(E.F_GI)), bits(orc.gi))
+    assert np.array_equal(bits(eng.state(E.F_GTILDE)), bits(orc.gt))
+    assert np.array_equal(bits(eng.state(E.F_G)), bits(orc.g))
+    assert eng.state(E.F_LEVEL_HIST).sum() == 0 and eng.state(E.F_MSG_COUNT).sum() == 0
+    for t in range(1, 4):
+        res, rm = orc.step(grads=grads[t])
+        eng.step(_cuda(grads[t]))
+        compare_step(eng, orc, res, rm, (n, d, t))
+    assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+    eng.close()
