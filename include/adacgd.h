@@ -207,9 +207,12 @@ enum adacgd_field {
   ADACGD_F_KERNEL_MS = 26,   /* double [2 x ADACGD_NUM_KERNELS] per kernel: summed milliseconds, then
                                 launch counts, since init or the last query (query resets)    */
   ADACGD_F_GRAD = 27,        /* float  [n x d] same as PREV_GRAD (the gradients of the last step) */
-  ADACGD_F_REPAIRS = 28      /* uint64 [2]     node-steps (workers, master) on which the sampled candidate cut
+  ADACGD_F_REPAIRS = 28,     /* uint64 [2]     node-steps (workers, master) on which the sampled candidate cut
                                 of the one-pass selection was too high and the vector was scanned a
                                 second time; a diagnostic: the results do not depend on it           */
+  ADACGD_F_ESTIMATOR_ERR = 29  /* double [1]   G = (1/n) sum_i ||grad f_i(x^t) - g~_i^t||^2 after the last step, the
+                                quantity whose contraction drives the convergence proofs (from the
+                                realised errors of the chosen levels; needs at least one step)  */
 };
 
 /* Kernel slots of ADACGD_F_KERNEL_MS.  W = worker side, M = master side.  Long vectors with

@@ -871,6 +871,20 @@ int adacgd_state(adacgd_ctx* c, int32_t field, void* dst, int64_t dst_bytes, int
       HIPCHK(c, hipStreamSynchronize(c->st));
       return host_out(o, 16);
     }
+    case ADACGD_F_ESTIMATOR_ERR: {
+      if (c->step == 0) { set_err(c->err, "no step has run yet"); return ADACGD_ERR_STATE; }
+      const int m = W.lv.m;
+      std::vector<int32_t> lev((size_t)n);
+      std::vector<double> S((size_t)n), err((size_t)n * m);
+      HIPCHK(c, hipMemcpyAsync(lev.data(), W.level, (size_t)n * 4, hipMemcpyDeviceToHost, c->st));
+      HIPCHK(c, hipMemcpyAsync(S.data(), W.S, (size_t)n * 8, hipMemcpyDeviceToHost, c->st));
+      HIPCHK(c, hipMemcpyAsync(err.data(), W.err, (size_t)n * m * 8, hipMemcpyDeviceToHost, c->st));
+      HIPCHK(c, hipStreamSynchronize(c->st));
+      double G = 0.0;     // what is left of x - h after the update: all of it on a skip, else the level's error
+      for (int64_t i = 0; i < n; ++i) G += lev[(size_t)i] == 0 ? S[(size_t)i] : err[(size_t)i * m + lev[(size_t)i] - 1];
+      G /= (double)n;
+      return host_out(&G, 8);
+    }
     case ADACGD_F_LEVEL_HIST: return copy(W.level_hist, (int64_t)(W.lv.m + 1) * 8);
     case ADACGD_F_M_LEVEL_HIST: return hm ? copy(M.level_hist, (int64_t)(M.lv.m + 1) * 8) : copy(nullptr, 8);
     case ADACGD_F_COMM: {

@@ -77,6 +77,10 @@ def compare_step(eng, orc, res, rm, tag, check_master=True):
             assert np.array_equal(eng.state(E.F_M_MSG_IDX), rm.msg_idx)
             assert np.array_equal(bits(eng.state(E.F_M_MSG_VAL)), bits(rm.msg_val))
     assert np.array_equal(bits(eng.state(E.F_X)), bits(orc.x)), (tag, "x")
+    # G = (1/n) sum ||x_i - g~_i||^2 after the update: the realised error of what each worker applied
+    want = np.mean([r.S if r.level == 0 else r.err[r.level - 1] for r in res])
+    got = float(eng.state(E.F_ESTIMATOR_ERR)[0])
+    assert abs(got - want) <= RED_RTOL * max(want, 1e-300), (tag, "G", got, want)
 
 
 def make_vectors(rng, n, d, kind):
@@ -384,6 +388,12 @@ def test_trajectory_with_oracle_gradients_is_bit_exact():
         assert np.array_equal(bits(eng.state(E.F_X)), bits(orc.x)), t
         assert np.array_equal(bits(eng.state(E.F_G)), bits(orc.g)), t
         assert np.array_equal(bits(eng.state(E.F_GI)), bits(orc.gi)), t
+        # the diagnostic G^t against its definition, from the vectors themselves
+        direct = np.mean([O.sum_sq_diff(orc.y[i], orc.gi[i]) for i in range(wl.n)])
+        # (h + C(v) is rounded to fp32: when everything is sent the realised error is 0 and the vectors
+        # differ by that rounding only)
+        floor = 1e-12 * np.mean([O.sum_squares(orc.y[i]) for i in range(wl.n)])
+        assert abs(float(eng.state(E.F_ESTIMATOR_ERR)[0]) - direct) <= 1e-5 * direct + floor
     assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
     assert (orc.level_hist_w > 0).sum() >= 3
     eng.close()
