@@ -96,9 +96,19 @@ def method_levels(method, d, adacgd_ratios=(0.01, 0.05, 0.1, 0.25, 0.5), zeta=1.
     raise ValueError(method)
 
 
+def largest_message_bits(levels, d):
+    """Cost of the most expensive message of a level set, by the rule of the engine's counters:
+    level id + K (32 + ceil(log2 d)) bits for Top-K, + d b + 32 for b bits."""
+    idb = max(1, math.ceil(math.log2(len(levels) + 1)))
+    ib = max(1, math.ceil(math.log2(d)))
+    return idb + max(p * (32 + ib) if kind == W.TOPK else d * p + 32 for kind, p in levels)
+
+
 def run(wl, method, multiplier, bit_budget, max_steps=100000, zeta=1.0, chunk=50, base_gamma=None):
     """Runs one method on the GPU until the uplink cost reaches `bit_budget` bits per worker.
-    Returns (steps, bits per worker, ||grad f(x)||^2), sampled every `chunk` steps."""
+    Returns (steps, bits per worker, ||grad f(x)||^2), sampled after at most `chunk` steps: the
+    number of steps between two samples is what the remaining budget covers at the price of the
+    level set's most expensive message, so a run ends within one step of the budget."""
     import torch
     from . import engine as E
     levels, z = method_levels(method, wl.d, zeta=zeta)
@@ -115,9 +125,12 @@ def run(wl, method, multiplier, bit_budget, max_steps=100000, zeta=1.0, chunk=50
     g = eng.state(E.F_PREV_GRAD).astype(np.float64).mean(axis=0)
     gn.append(float(g @ g))
     t = 0
+    worst = largest_message_bits(levels, wl.d)
     while t < max_steps and bits[-1] < bit_budget and np.isfinite(gn[-1]):
-        eng.step(nsteps=chunk)
-        t += chunk
+        todo = int(min(chunk, max(1.0, (bit_budget - bits[-1]) / worst)))
+        todo = min(todo, max_steps - t)
+        eng.step(nsteps=todo)
+        t += todo
         comm = eng.state(E.F_COMM)
         g = eng.state(E.F_PREV_GRAD).astype(np.float64).mean(axis=0)
         steps.append(t)

@@ -84,14 +84,23 @@ def test_run_matches_oracle_loop(method):
     orc.init(np.zeros(wl.d, dtype=np.float32))
     up = 0
     ref_bits, ref_gn = [0.0], [float(np.sum(orc.y.astype(np.float64).mean(0) ** 2))]
+    assert steps.tolist() == [0, 20, 40, 60]
     for t in range(60):
         res, _ = orc.step()
         up += sum(O.AdaCGDOracle.message_bits(r.level, orc.wl, wl.d) for r in res)
-        if (t + 1) % 20 == 0:
+        if t + 1 in steps:
             ref_bits.append(up / wl.n)
             ref_gn.append(float(np.sum(orc.y.astype(np.float64).mean(0) ** 2)))
-    assert steps.tolist() == [0, 20, 40, 60]
     assert bits.tolist() == ref_bits
     assert np.allclose(gn, ref_gn, rtol=1e-4, atol=0)
     if method == "gd":
         assert bits[-1] == 60 * (1 + wl.d * (32 + 7))      # every coordinate, every step
+
+
+@pytest.mark.gpu
+def test_run_stops_close_to_the_budget():
+    wl = W.tiny()
+    per_step = 1 + wl.d * (32 + 7)                    # plain gradient descent sends everything
+    steps, bits, gn = X.run(wl, "gd", 1, bit_budget=37.5 * per_step, base_gamma=0.3)
+    assert steps[-1] == 38 and bits[-1] == 38 * per_step
+    assert X.largest_message_bits([(W.TOPK, wl.d)], wl.d) == per_step
