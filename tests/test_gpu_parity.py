@@ -787,3 +787,28 @@ def test_compressed_initial_estimators_bit_exact(n, d):
         compare_step(eng, orc, res, rm, (n, d, t))
     assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
     eng.close()
+
+
+def test_sparse_rows_degenerate_shapes():
+    """No stored entry at all (the gradient is the regulariser's), and one row per worker with d = 1."""
+    E = _eng()
+    wl = W.tiny(seed=3, n=3, d=37, N=5)
+    wl.A[:] = 0
+    x0 = np.linspace(-2, 2, wl.d).astype(np.float32)
+    eng = _csr_engine(wl, (np.zeros(wl.A.shape[0] + 1, dtype=np.int64), np.zeros(0, dtype=np.int32), None), x0=x0)
+    ref = np.stack([O.logistic_grad(A, y, x0, np.float64(np.float32(wl.lam)), np.float32) for A, y in wl.shards()])
+    assert np.array_equal(bits(eng.state(E.F_GRAD)), bits(ref))
+    eng.step(nsteps=3)
+    eng.close()
+    wl = W.tiny(seed=4, n=2, d=1, N=1)
+    wl.worker_levels, wl.master_levels = [(O.TOPK, 1)], []
+    x0 = np.array([0.7], dtype=np.float32)
+    eng = _csr_engine(wl, W.to_csr(wl.A), x0=x0)
+    ref = np.stack([O.logistic_grad(A, y, x0, np.float64(np.float32(wl.lam)), np.float32) for A, y in wl.shards()])
+    assert_close_rel(eng.state(E.F_GRAD), ref, TRAJ_RTOL, "d = 1")
+    orc = _logistic_oracle(wl, x0=x0)
+    for t in range(5):
+        orc.step()
+        eng.step()
+        assert_close_rel(eng.state(E.F_X), orc.x, TRAJ_RTOL, ("x", t))
+    eng.close()
