@@ -1,5 +1,6 @@
 """Randomised parity sweep: shapes around every tiling boundary, random level sets (Top-K sizes over four
-decades, quantisers, the identity), trigger constants, input kinds and kernel paths, three steps each,
+decades, quantisers, the identity), trigger constants or per-position trigger pairs, the three ways to
+start the estimators, input kinds and kernel paths, three steps each,
 compared with the oracle bit for bit exactly as the fixed cases are."""
 import numpy as np
 import pytest
@@ -42,18 +43,23 @@ def test_random_configurations_bit_exact(seed):
             grads[t] = (grads[t - 1] + grads[t] * np.float32(10.0 ** rng.uniform(-2, 0))).astype(np.float32)
         x0 = rng.standard_normal(d).astype(np.float32)
         diff_mode = rng.random() < 0.3       # the caller supplies x - h and ||x - y||^2 itself
-        orc = O.AdaCGDOracle(n=n, d=d, gamma=0.05, worker_levels=levels, zeta_worker=zw, master_levels=ml,
-                             zeta_master=zm, seed=pseed)
+        # a third of the cases: a (zeta_j, eta_j) pair per cascade position instead of the one constant
+        tw = tm = None
+        if rng.random() < 0.35:
+            tw = [(float(rng.choice([0.0, 0.4, 1.0, 2.5])), float(rng.choice([0.0, 0.0, 0.05, 0.3]))) for _ in levels]
+            tm = [(float(rng.choice([0.0, 0.5])), float(rng.choice([0.0, 0.1]))) for _ in ml]
+        compressed_start = (not diff_mode) and levels[-1][0] == O.TOPK and rng.random() < 0.25
+        kw = dict(n=n, d=d, gamma=0.05, worker_levels=levels, zeta_worker=zw, master_levels=ml, zeta_master=zm,
+                  seed=pseed, worker_triggers=tw, master_triggers=tm)
+        tag = tag + (tw, tm, diff_mode, compressed_start)
+        orc = O.AdaCGDOracle(**kw)
         if diff_mode:
             orc.init(x0, None, O.INIT_ZERO)
-            eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=levels, zeta_worker=zw, master_levels=ml,
-                           zeta_master=zm, grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), seed=pseed,
-                           flags=flags)
+            eng = E.AdaCGD(grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), flags=flags, **kw)
         else:
-            orc.init(x0, grads[0], O.INIT_FULLGRAD)
-            eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=levels, zeta_worker=zw, master_levels=ml,
-                           zeta_master=zm, grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=_cuda(grads[0]), seed=pseed,
-                           flags=flags)
+            orc.init(x0, grads[0], O.INIT_COMPRESSED if compressed_start else O.INIT_FULLGRAD)
+            eng = E.AdaCGD(grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=_cuda(grads[0]), flags=flags,
+                           init_mode=E.INIT_COMPRESSED if compressed_start else E.INIT_FULLGRAD, **kw)
         try:
             for t in range(1, steps + 1):
                 if diff_mode:

@@ -356,3 +356,30 @@ def test_per_level_zeta_is_first_condition_that_holds():
         assert r.level == first
         hist[r.level] += 1
     assert (hist > 0).sum() >= 5
+
+
+def test_compressed_start_is_topk_of_the_first_gradients():
+    """INIT_COMPRESSED: g~_i^0 = C_m(grad f_i(x^0)), here against a sort of (|value|, index) pairs,
+    and the run that follows with zeta = 0 and one level is EF21 from that start."""
+    rng = np.random.default_rng(21)
+    n, d, K = 3, 40, 7
+    g0 = rng.standard_normal((n, d)).astype(np.float32)
+    g0[0, ::2] = 0.0
+    g0[0, 1] = -0.0
+    orc = O.AdaCGDOracle(n=n, d=d, gamma=0.1, worker_levels=[(T, 2), (T, K)], zeta_worker=0.0)
+    orc.init(np.zeros(d, dtype=np.float32), g0, O.INIT_COMPRESSED)
+    for i in range(n):
+        order = sorted(range(d), key=lambda l: (-abs(float(g0[i, l])), l))[:K]
+        want = np.zeros(d, dtype=np.float32)
+        want[order] = g0[i, order]
+        assert np.array_equal(orc.gi[i], want)              # (-0 == +0 here: the sign of a zero is not fixed)
+    assert np.allclose(orc.gt, orc.gi.astype(np.float64).mean(0), rtol=1e-7, atol=0)
+    h = orc.gi.copy()
+    g1 = (g0 + 0.1 * rng.standard_normal((n, d))).astype(np.float32)
+    orc.step(grads=g1)
+    for i in range(n):
+        v = g1[i] - h[i]
+        order = sorted(range(d), key=lambda l: (-abs(float(v[l])), l))[:K]
+        want = h[i].copy()
+        want[order] = h[i][order] + v[order]
+        assert np.array_equal(orc.gi[i], want)
