@@ -256,8 +256,8 @@ __global__ __launch_bounds__(kBlock) void k_grad_finish(LogisticData ld, const f
 // ---------------------------------------------------------------------------
 // The same gradient for sparse features (rows in CSR form, and per worker by column).
 // margins: LPR lanes per row (a power of two) sum the row's stored entries in fp64.
-// cols   : one thread per (worker, column) sums s_l a_lj over the column's entries of that
-//          worker's shard, in row order, then adds the regulariser and rounds once.
+// cols   : 1, 16 or 64 lanes per (worker, column) sum s_l a_lj over the column's entries of that
+//          worker's shard in a fixed order, then add the regulariser and round once.
 // ---------------------------------------------------------------------------
 template <int LPR>
 __global__ __launch_bounds__(kBlock) void k_csr_margins(LogisticData ld, const float* __restrict__ x) {
@@ -280,20 +280,24 @@ __global__ __launch_bounds__(kBlock) void k_csr_margins(LogisticData ld, const f
   }
 }
 
+template <int LPC>   // lanes per column, a power of two: long columns are shared by 16 or 64 lanes
 __global__ __launch_bounds__(kBlock) void k_csr_cols(LogisticData ld, const float* __restrict__ x,
                                                       float* __restrict__ grads, int64_t d) {
   const int node = blockIdx.y;
-  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (j >= d) return;
+  const int64_t j = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LPC;
+  const int sub = threadIdx.x % LPC;
+  const bool live = j < d;
   const uint32_t* __restrict__ cp = ld.cptr + (size_t)node * (size_t)(d + 1);
   const int64_t w0 = ld.wbase[node];
-  const int64_t b = w0 + cp[j], e = w0 + cp[j + 1];
+  const int64_t b = live ? w0 + cp[j] : 0, e = live ? w0 + cp[j + 1] : 0;
   double acc = 0.0;
-  for (int64_t k = b; k < e; ++k) {
+  for (int64_t k = b + sub; k < e; k += LPC) {
     const double a = ld.binary ? 1.0 : (double)ld.tval[k];
     acc = fma(ld.margins[ld.trow[k]], a, acc);
   }
-  grads[(size_t)node * d + j] = (float)(acc + reg_grad(ld.lambda, (double)x[j]));
+#pragma unroll
+  for (int o = LPC >> 1; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+  if (live && sub == 0) grads[(size_t)node * d + j] = (float)(acc + reg_grad(ld.lambda, (double)x[j]));
 }
 
 // ---------------------------------------------------------------------------
@@ -365,7 +369,12 @@ hipError_t launch_grad_margins(const LogisticData& ld, const float* x, int64_t d
 hipError_t launch_grad_cols(const LogisticData& ld, const float* x, float* grads, int n, int64_t d, hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
   if (ld.csr) {
-    hipLaunchKernelGGL(k_csr_cols, dim3((unsigned)((d + kBlock - 1) / kBlock), n), dim3(kBlock), 0, st, ld, x, grads, d);
+    const int64_t per_col = ld.nnz / ((int64_t)n * d);
+    const int lpc = per_col >= 256 ? 64 : per_col >= 16 ? 16 : 1;
+    const dim3 grid((unsigned)((d * lpc + kBlock - 1) / kBlock), n);
+    if (lpc == 64) hipLaunchKernelGGL((k_csr_cols<64>), grid, dim3(kBlock), 0, st, ld, x, grads, d);
+    else if (lpc == 16) hipLaunchKernelGGL((k_csr_cols<16>), grid, dim3(kBlock), 0, st, ld, x, grads, d);
+    else hipLaunchKernelGGL((k_csr_cols<1>), grid, dim3(kBlock), 0, st, ld, x, grads, d);
     return hipGetLastError();
   }
   const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(ld.A) & 15u) == 0);

@@ -696,7 +696,7 @@ def _sparsify(wl, density, rng, binary):
 
 @pytest.mark.parametrize("n,d,N,density,binary", [(4, 100, 64, 0.1, False), (3, 101, 50, 0.5, True),
                                                   (5, 8192 + 12, 7, 0.02, False), (2, 300, 2500, 0.04, True),
-                                                  (2, 1500, 40, 0.6, False)])
+                                                  (2, 1500, 40, 0.6, False), (2, 40, 1200, 0.5, False)])
 def test_sparse_gradient_kernel_matches_oracle(n, d, N, density, binary):
     """grad f_i(x) from compressed sparse rows against the oracle on the same matrix stored
     densely: both accumulate in fp64 and round once, so values agree to one fp32 unit in the
