@@ -21,6 +21,7 @@ constexpr int kBins2 = 512;
 
 constexpr int kMaxLevels = 16;
 constexpr int kSmallMax = 4096;         // largest d handled by the one-block-per-node kernel
+constexpr int kSmallServeMax = 64;      // ... which also aggregates when there are at most this many workers
 
 enum { kTopK = 0, kQuant = 1 };
 
@@ -120,6 +121,15 @@ struct PassArgs {
   uint64_t seed;       // Philox key
   uint32_t step;       // Philox counter word 2
   uint32_t node_flag;  // OR-ed into counter word 1 (0 for workers, 2^31 for the master)
+  // Server work that the one-block kernel for short vectors can take over (each part optional):
+  // the block that finishes last adds every node's message to the server vector, g~_new =
+  // fl(g~_old + sum / nn); and the iterate update that opens the next step, x_next = fl(x - gamma g),
+  // with g = g~_new when it follows the aggregation, else g = the updated estimator of node 0 (the master).
+  const float* agg_old;
+  float* agg_new;
+  const float* xu_x;
+  float* xu_out;
+  double xu_gamma;
 };
 
 struct LogisticData {

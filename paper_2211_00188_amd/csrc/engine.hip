@@ -228,6 +228,8 @@ struct adacgd_ctx {
   NodeSet W, M;
   bool has_master;
   float* x;
+  float* x_next;    // x - gamma g, when the kernel that produced g has already written it (short vectors)
+  bool x_next_valid;
   float* g_own;     // master estimator g when the master compresses
   float* gt[2];     // g~^t and g~^{t-1}; cur indexes g~^t
   int cur;
@@ -312,7 +314,7 @@ int validate(const adacgd_config* cfg, LevelTable* wl, LevelTable* ml, char* err
 }
 
 struct Layout {
-  float *x, *g_own, *gt0, *gt1, *gi, *yb0, *yb1;
+  float *x, *x_next, *g_own, *gt0, *gt1, *gi, *yb0, *yb1;
   int64_t* offsets;
   int32_t* row_node;
   double* margins;
@@ -337,6 +339,7 @@ size_t carve_all(char* base, const adacgd_config* cfg, NodeSet& W, NodeSet& M, L
     L.m_zero = base ? (size_t)((char*)M.prefix - (char*)M.hist0) : 0;
   }
   L.x = c.take<float>(d);
+  L.x_next = W.small ? c.take<float>(d) : nullptr;
   L.g_own = M.lv.m > 0 ? c.take<float>(d) : nullptr;
   L.gt0 = c.take<float>(d);
   L.gt1 = c.take<float>(d);
@@ -476,9 +479,16 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
   // depend on the server chain of step t (gradients are supplied), so the two run concurrently.
   const bool ov = c->wst != nullptr;
   c->cs = c->st;
-  // x^{t+1} = x^t - gamma g^t
-  if ((rc = timed(c, ADACGD_K_XUPDATE, [&] { return launch_xupdate(c->x, c->g(), c->gamma, c->d, c->cs); })))
+  // x^{t+1} = x^t - gamma g^t (already there if the kernel that finished g^t wrote it as well)
+  if (c->x_next_valid) {
+    std::swap(c->x, c->x_next);
+    c->x_next_valid = false;
+  } else if ((rc = timed(c, ADACGD_K_XUPDATE, [&] { return launch_xupdate(c->x, c->g(), c->gamma, c->d, c->cs); }))) {
     return rc;
+  }
+  // Short vectors, few workers, Top-K messages only: the one-block kernel of the workers also does the
+  // aggregation (its last block), and the kernel that finishes g the next iterate update.
+  const bool serve = c->W.small && c->W.lv.nq == 0 && c->n <= kSmallServeMax && !ov;
   PassArgs a{};
   a.h = c->gi;
   a.seed = c->seed;
@@ -498,6 +508,18 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
     a.diff = 1;
     a.extD = extD;
   }
+  float* gt_old = c->gt[c->cur];
+  float* gt_new = c->gt[c->cur ^ 1];
+  if (serve) {
+    a.agg_old = gt_old;
+    a.agg_new = gt_new;
+    if (!c->has_master) {
+      a.xu_x = c->x;
+      a.xu_out = c->x_next;
+      a.xu_gamma = c->gamma;
+      c->x_next_valid = true;
+    }
+  }
   // g~_i^{t+1} = C^AC_{g~_i^t, grad f_i(x^t)}(grad f_i(x^{t+1}))
   if (ov) c->cs = c->wst;
   if ((rc = compress(c, c->W, a, ADACGD_K_W_SAMPLE, ov && c->agg_recorded ? c->ev_agg : nullptr))) return rc;
@@ -513,9 +535,8 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
     else c->ycur ^= 1;
   }
   // g~^{t+1} = g~^t + (1/n) sum_i messages
-  float* gt_old = c->gt[c->cur];
-  float* gt_new = c->gt[c->cur ^ 1];
-  if ((rc = timed(c, ADACGD_K_AGGREGATE, [&] { return launch_aggregate(c->W, gt_old, gt_new, c->cs); }))) return rc;
+  if (!serve && (rc = timed(c, ADACGD_K_AGGREGATE, [&] { return launch_aggregate(c->W, gt_old, gt_new, c->cs); })))
+    return rc;
   if (ov) {
     HIPCHK(c, hipEventRecord(c->ev_agg, c->st));
     c->agg_recorded = true;
@@ -530,6 +551,12 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
     m.seed = c->seed;
     m.step = (uint32_t)c->step;
     m.node_flag = 0x80000000u;
+    if (c->M.small) {
+      m.xu_x = c->x;
+      m.xu_out = c->x_next;
+      m.xu_gamma = c->gamma;
+      c->x_next_valid = true;
+    }
     if ((rc = compress(c, c->M, m, ADACGD_K_M_SAMPLE, nullptr))) return rc;
   }
   c->step += 1;
@@ -629,7 +656,7 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
     delete c;
     return ADACGD_ERR_ALLOC;
   }
-  c->x = L.x; c->g_own = L.g_own; c->gt[0] = L.gt0; c->gt[1] = L.gt1; c->gi = L.gi;
+  c->x = L.x; c->x_next = L.x_next; c->x_next_valid = false; c->g_own = L.g_own; c->gt[0] = L.gt0; c->gt[1] = L.gt1; c->gi = L.gi;
   c->yb[0] = L.yb0; c->yb[1] = L.yb1;
   c->ld.A = cfg->A; c->ld.labels = cfg->labels; c->ld.offsets = L.offsets; c->ld.row_node = L.row_node;
   c->ld.margins = L.margins; c->ld.part = L.part;

@@ -1300,6 +1300,8 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
   __shared__ uint32_t redu[16];
   __shared__ double s_slot_err[kMaxLevels], s_qerr[kMaxLevels];
   __shared__ int s_slot, s_q;
+  __shared__ int s_flag;
+  const bool serve = a.agg_new != nullptr;     // what the aggregation reads goes through coherent accesses
   const int node = blockIdx.x, tid = threadIdx.x, NT = blockDim.x, nw = NT >> 6;
   const int lane = tid & 63, w = tid >> 6;
   const int d = (int)ns.d;
@@ -1434,7 +1436,8 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
     ns.D[node] = Dn;
     ns.level[node] = jstar;
     atomicAdd(&ns.level_hist[jstar], 1ull);
-    ns.sel_slot[node] = slot;
+    if (serve) st_coherent(&ns.sel_slot[node], slot);
+    else ns.sel_slot[node] = slot;
     ns.sel_q[node] = q;
     ns.msg_count[node] = slot >= 0 ? lv.K[slot] : 0u;
     ns.qscale[node] = 0.f;
@@ -1475,8 +1478,13 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
     for (int i = lo; i < hi; ++i) {
       if (flag[i]) {
         const float v = sv[i];
-        midx[pos] = i;
-        mval[pos] = v;
+        if (serve) {
+          st_coherent(&midx[pos], (int32_t)i);
+          st_coherent(&mval[pos], v);
+        } else {
+          midx[pos] = i;
+          mval[pos] = v;
+        }
         h[i] = h[i] + v;
         ++pos;
       }
@@ -1506,6 +1514,35 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
       h[i] = h[i] + cq;
       codes[i] = (int16_t)code;
     }
+  }
+
+  // ---- iterate update that opens the next step, from this node's new estimator (the master) ----
+  if (a.xu_out && !serve) {
+    __syncthreads();                               // h is complete
+    if (node == 0)
+      for (int i = tid; i < d; i += NT) a.xu_out[i] = (float)((double)a.xu_x[i] - a.xu_gamma * (double)h[i]);
+  }
+  if (!serve) return;
+
+  // ---- server aggregation, by the block that finishes last (Top-K messages only) ----
+  if (!arrive_last(ns.done, (uint32_t)ns.nn, (uint32_t)node, &s_flag)) return;
+  double* acc = reinterpret_cast<double*>(ck);     // the sort buffer is free now
+  for (int i = tid; i < d; i += NT) acc[i] = 0.0;
+  __syncthreads();
+  for (int i = 0; i < ns.nn; ++i) {
+    const int sl = ld_coherent(&ns.sel_slot[i]);
+    if (sl < 0) continue;                          // same in every thread
+    const int K = (int)lv.K[sl];
+    const int32_t* __restrict__ mi = ns.msg_idx + (size_t)i * ns.Kcap;
+    const float* __restrict__ mv = ns.msg_val + (size_t)i * ns.Kcap;
+    for (int e = tid; e < K; e += NT) acc[ld_coherent(&mi[e])] += (double)ld_coherent(&mv[e]);   // distinct coordinates
+    __syncthreads();
+  }
+  const double nn = (double)ns.nn;
+  for (int i = tid; i < d; i += NT) {
+    const float gn = (float)((double)a.agg_old[i] + acc[i] / nn);
+    a.agg_new[i] = gn;
+    if (a.xu_out) a.xu_out[i] = (float)((double)a.xu_x[i] - a.xu_gamma * (double)gn);
   }
 }
 
