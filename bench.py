@@ -129,7 +129,7 @@ def extra_small_logistic(E, W, torch, wl, steps, sparse_rows=False):
     else:
         kw.update(grad_mode=E.GRAD_LOGISTIC, A=torch.from_numpy(wl.A).cuda())
     eng = E.AdaCGD(flags=0, **kw)
-    eng.step(nsteps=10)
+    eng.step(nsteps=500)                   # a step takes tens of microseconds: let the clocks settle
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     eng.step(nsteps=steps)                 # one call enqueues all steps: no Python in the loop
@@ -149,7 +149,7 @@ def extra_small_logistic(E, W, torch, wl, steps, sparse_rows=False):
             "steps": steps, "ms_per_step": dt / steps * 1e3, "steps_per_sec": steps / dt,
             "kernel_launches_per_step": launches,
             "level_histogram_skip_then_levels_since_init": [int(v) for v in hist],
-            "note": "launch/latency-bound: no roofline applies"}
+            "note": "a step is four short dependent kernels: latency-bound, no roofline applies"}
 
 
 def main():
@@ -274,9 +274,9 @@ def main():
     if not args.no_extras:
         other.append(extra_kernel_stress(E, W, torch))
         other.append(extra_federated(E, W, torch, args.federated_n))
-        other.append(extra_small_logistic(E, W, torch, W.tiny(), 1000))
-        other.append(extra_small_logistic(E, W, torch, W.sparse_logreg(), 1000))
-        other.append(extra_small_logistic(E, W, torch, W.sparse_logreg(), 1000, sparse_rows=True))
+        other.append(extra_small_logistic(E, W, torch, W.tiny(), 2000))
+        other.append(extra_small_logistic(E, W, torch, W.sparse_logreg(), 2000))
+        other.append(extra_small_logistic(E, W, torch, W.sparse_logreg(), 2000, sparse_rows=True))
         other.append(extra_sparse_features(E, W, torch))
 
     out = {

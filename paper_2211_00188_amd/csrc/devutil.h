@@ -115,6 +115,22 @@ __device__ __forceinline__ bool arrive_last(uint32_t* counters, uint32_t nblocks
   return *lds_flag != 0;
 }
 
+// The same for a few dozen blocks: one counter is enough.
+__device__ __forceinline__ bool arrive_last_few(uint32_t* counter, uint32_t nblocks, int* lds_flag) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = prev == nblocks - 1;
+    if (last) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *lds_flag = last;
+  }
+  __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  return *lds_flag != 0;
+}
+
 // LDS histogram increment by the lanes that call it (they may be a divergent subset).  The
 // lanes that share the first active lane's bin are counted with one atomic: vectors with many
 // equal magnitudes (zeros above all) would otherwise serialise up to 64 same-address atomics.

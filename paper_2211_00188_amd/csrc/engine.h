@@ -142,6 +142,7 @@ struct LogisticData {
   double lambda;
   double* margins;         // [rows]  s_l = -y_l / (1 + exp(y_l a_l^T x)) / N_i
   double* part;            // [n][row_chunks][d] when row_chunks > 1
+  uint32_t* col_done;      // [n][column blocks] arrival counters when row_chunks > 1; zero between launches
   int row_chunks;
   // Sparse features (GRAD_LOGISTIC_CSR): device copies made at init.  The transposed copy holds
   // every worker's entries sorted by column, then by row, so that one thread sums a column of a

@@ -319,6 +319,7 @@ struct Layout {
   int32_t* row_node;
   double* margins;
   double* part;
+  uint32_t* col_done;
   int64_t *rp, *wbase;
   int32_t *ci, *trow;
   float *cv, *tval;
@@ -357,8 +358,9 @@ size_t carve_all(char* base, const adacgd_config* cfg, NodeSet& W, NodeSet& M, L
     L.row_node = c.take<int32_t>(rows);
     L.margins = c.take<double>(rows);
     L.part = ld.row_chunks > 1 ? c.take<double>(n * ld.row_chunks * d) : nullptr;
+    L.col_done = ld.row_chunks > 1 ? c.take<uint32_t>(n * ((d + 63) / 64)) : nullptr;
   } else {
-    L.offsets = nullptr; L.row_node = nullptr; L.margins = nullptr; L.part = nullptr;
+    L.offsets = nullptr; L.row_node = nullptr; L.margins = nullptr; L.part = nullptr; L.col_done = nullptr;
   }
   if (ld.csr) {
     const size_t rows = cfg->shard_offsets[n], nnz = (size_t)ld.nnz;
@@ -388,7 +390,7 @@ void shape_logistic(const adacgd_config* cfg, LogisticData& ld) {
   int64_t mx = 0;
   for (int64_t i = 0; i < cfg->n; ++i) mx = std::max<int64_t>(mx, cfg->shard_offsets[i + 1] - cfg->shard_offsets[i]);
   ld.max_rows = mx;
-  int64_t chunks = (mx + 63) / 64;      // about 64 rows per block ...
+  int64_t chunks = (mx + 255) / 256;    // about 256 rows per block (64 per wavefront) ...
   if (chunks > 64) chunks = 64;         // ... but a bounded number of partial sums
   ld.row_chunks = (int)chunks;
   ld.lambda = (double)cfg->lambda;
@@ -659,7 +661,7 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
   c->x = L.x; c->x_next = L.x_next; c->x_next_valid = false; c->g_own = L.g_own; c->gt[0] = L.gt0; c->gt[1] = L.gt1; c->gi = L.gi;
   c->yb[0] = L.yb0; c->yb[1] = L.yb1;
   c->ld.A = cfg->A; c->ld.labels = cfg->labels; c->ld.offsets = L.offsets; c->ld.row_node = L.row_node;
-  c->ld.margins = L.margins; c->ld.part = L.part;
+  c->ld.margins = L.margins; c->ld.part = L.part; c->ld.col_done = L.col_done;
   if (c->ld.csr) {
     c->ld.rp = L.rp; c->ld.wbase = L.wbase; c->ld.cptr = L.cptr; c->ld.ci = L.ci; c->ld.trow = L.trow;
     c->ld.cv = L.cv; c->ld.tval = L.tval;
@@ -719,6 +721,7 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
     wbase[(size_t)c->n] = rp[rows];
     INITCHK(hipMemcpy(L.wbase, wbase.data(), wbase.size() * sizeof(int64_t), hipMemcpyHostToDevice));
   }
+  if (L.col_done) INITCHK(launch_fill_u32(L.col_done, 0u, (size_t)c->n * (size_t)((c->d + 63) / 64), c->st));
   if (logistic_mode(cfg->grad_mode)) {
     std::vector<int32_t> rn((size_t)c->ld.rows);
     for (int64_t i = 0; i < c->n; ++i)

@@ -175,18 +175,24 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_aggregate_dense(NodeSet ws
 // ---------------------------------------------------------------------------
 // logistic gradient, Section 6:
 //   grad f_i(x) = -(1/N_i) sum_l y_l a_l / (1 + exp(y_l a_l^T x)) + 2 lambda x_j / (1 + x_j^2)^2
-// margins: one wavefront per sample computes a_l^T x in fp64 and s_l = -y_l/(1+exp(y_l z_l))/N_i.
-// cols   : each thread owns 4 columns and sums s_l a_l over a chunk of the shard's rows in fp64.
+// margins: LPR lanes per sample (64, or 16 for rows shorter than 1024 so that a wavefront works on four
+//          rows at once) compute a_l^T x in fp64 and s_l = -y_l/(1+exp(y_l z_l))/N_i.
+// cols   : a block owns 64 column groups (4 columns each on the 16-byte path) and a chunk of the shard's
+//          rows; its four wavefronts take every fourth row, sum s_l a_l in fp64, and the four partial
+//          sums are added in wavefront order.  Shards of more than 256 rows are shared by several
+//          blocks; the one that finishes last adds their sums in chunk order.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_grad_margins(LogisticData ld, const float* __restrict__ x, int64_t d,
-                                                          int vec) {
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int64_t l = (int64_t)blockIdx.x * 4 + w;
-  if (l >= ld.rows) return;
-  const float* __restrict__ a = ld.A + (size_t)l * d;
+template <int LPR, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_grad_margins(LogisticData ld, const float* __restrict__ x, int64_t d) {
+  const int64_t l = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LPR;
+  const int sub = threadIdx.x % LPR;
+  const bool live = l < ld.rows;
+  const float* __restrict__ a = ld.A + (size_t)(live ? l : 0) * d;
+  const int64_t dd = live ? d : 0;
   double acc0 = 0.0, acc1 = 0.0;
-  if (vec) {
-    for (int64_t j = (int64_t)lane * 4; j < d; j += 256) {
+  if (VEC) {
+#pragma unroll 4
+    for (int64_t j = (int64_t)sub * 4; j < dd; j += LPR * 4) {
       const float4 av = *reinterpret_cast<const float4*>(a + j);
       const float4 xv = *reinterpret_cast<const float4*>(x + j);
       acc0 = fma((double)av.x, (double)xv.x, acc0);
@@ -195,10 +201,13 @@ __global__ __launch_bounds__(kBlock) void k_grad_margins(LogisticData ld, const 
       acc1 = fma((double)av.w, (double)xv.w, acc1);
     }
   } else {
-    for (int64_t j = lane; j < d; j += 64) acc0 = fma((double)a[j], (double)x[j], acc0);
+#pragma unroll 4
+    for (int64_t j = sub; j < dd; j += LPR) acc0 = fma((double)a[j], (double)x[j], acc0);
   }
-  const double z = wave_sum(acc0 + acc1);
-  if (lane == 0) {
+  double z = acc0 + acc1;
+#pragma unroll
+  for (int o = LPR >> 1; o > 0; o >>= 1) z += __shfl_xor(z, o);
+  if (live && sub == 0) {
     const int node = ld.row_node[l];
     const double N = (double)(ld.offsets[node + 1] - ld.offsets[node]);
     const double yl = (double)ld.labels[l];
@@ -214,43 +223,65 @@ __device__ __forceinline__ double reg_grad(double lambda, double xj) {
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_grad_cols(LogisticData ld, const float* __restrict__ x,
                                                        float* __restrict__ grads, int64_t d, int rows_per_chunk) {
-  const int node = blockIdx.z, rc = blockIdx.y;
-  const int64_t j0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * (VEC ? 4 : 1);
-  if (j0 >= d) return;
+  constexpr int CPL = VEC ? 4 : 1;                 // columns per lane
+  __shared__ double part[4][64 * CPL];
+  __shared__ int s_flag;
+  const int node = blockIdx.z, rc = blockIdx.y, w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t j0 = ((int64_t)blockIdx.x * 64 + lane) * CPL;
+  const bool live = j0 < d;
   const int64_t r_begin = ld.offsets[node] + (int64_t)rc * rows_per_chunk;
   const int64_t r_end = min(ld.offsets[node + 1], r_begin + rows_per_chunk);
   double acc[4] = {0.0, 0.0, 0.0, 0.0};
-  const float* __restrict__ a = ld.A + (size_t)r_begin * d + j0;
-  for (int64_t l = r_begin; l < r_end; ++l, a += d) {
-    const double s = ld.margins[l];
-    if (VEC) {
-      const float4 av = *reinterpret_cast<const float4*>(a);
-      acc[0] = fma(s, (double)av.x, acc[0]);
-      acc[1] = fma(s, (double)av.y, acc[1]);
-      acc[2] = fma(s, (double)av.z, acc[2]);
-      acc[3] = fma(s, (double)av.w, acc[3]);
-    } else {
-      acc[0] = fma(s, (double)a[0], acc[0]);
+  if (live) {
+    const float* __restrict__ a = ld.A + (size_t)(r_begin + w) * d + j0;
+#pragma unroll 4
+    for (int64_t l = r_begin + w; l < r_end; l += 4, a += 4 * d) {
+      const double s = ld.margins[l];
+      if (VEC) {
+        const float4 av = *reinterpret_cast<const float4*>(a);
+        acc[0] = fma(s, (double)av.x, acc[0]);
+        acc[1] = fma(s, (double)av.y, acc[1]);
+        acc[2] = fma(s, (double)av.z, acc[2]);
+        acc[3] = fma(s, (double)av.w, acc[3]);
+      } else {
+        acc[0] = fma(s, (double)a[0], acc[0]);
+      }
     }
   }
-  if (ld.row_chunks == 1) {
 #pragma unroll
-    for (int c = 0; c < (VEC ? 4 : 1); ++c)
-      grads[(size_t)node * d + j0 + c] = (float)(acc[c] + reg_grad(ld.lambda, (double)x[j0 + c]));
-  } else {
+  for (int c = 0; c < CPL; ++c) part[w][lane * CPL + c] = acc[c];
+  __syncthreads();
+  double t[4];
 #pragma unroll
-    for (int c = 0; c < (VEC ? 4 : 1); ++c) ld.part[((size_t)node * ld.row_chunks + rc) * d + j0 + c] = acc[c];
+  for (int c = 0; c < CPL; ++c)
+    t[c] = ((part[0][lane * CPL + c] + part[1][lane * CPL + c]) + part[2][lane * CPL + c]) + part[3][lane * CPL + c];
+  if (ld.row_chunks > 1) {
+    // several blocks share the shard's rows: each leaves its sums, the last to arrive adds them in chunk order
+    if (w == 0 && live) {
+#pragma unroll
+      for (int c = 0; c < CPL; ++c) st_coherent(&ld.part[((size_t)node * ld.row_chunks + rc) * d + j0 + c], t[c]);
+    }
+    if (!arrive_last_few(&ld.col_done[(size_t)node * gridDim.x + blockIdx.x], (uint32_t)ld.row_chunks, &s_flag)) return;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) t[c] = 0.0;
+    if (w == 0 && live) {
+      for (int r0 = 0; r0 < ld.row_chunks; r0 += 8) {        // eight chunks' loads in flight, added in chunk order
+        double v[8][4];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int c = 0; c < CPL; ++c)
+            v[u][c] = r0 + u < ld.row_chunks ? ld_coherent(&ld.part[((size_t)node * ld.row_chunks + r0 + u) * d + j0 + c]) : 0.0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int c = 0; c < CPL; ++c) t[c] += v[u][c];
+      }
+    }
   }
-}
-
-__global__ __launch_bounds__(kBlock) void k_grad_finish(LogisticData ld, const float* __restrict__ x,
-                                                         float* __restrict__ grads, int64_t d) {
-  const int node = blockIdx.y;
-  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (j >= d) return;
-  double acc = 0.0;
-  for (int rc = 0; rc < ld.row_chunks; ++rc) acc += ld.part[((size_t)node * ld.row_chunks + rc) * d + j];
-  grads[(size_t)node * d + j] = (float)(acc + reg_grad(ld.lambda, (double)x[j]));
+  if (w != 0 || !live) return;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) grads[(size_t)node * d + j0 + c] = (float)(t[c] + reg_grad(ld.lambda, (double)x[j0 + c]));
 }
 
 // ---------------------------------------------------------------------------
@@ -360,9 +391,17 @@ hipError_t launch_grad_margins(const LogisticData& ld, const float* x, int64_t d
     else hipLaunchKernelGGL((k_csr_margins<4>), dim3(grid), dim3(kBlock), 0, st, ld, x);
     return hipGetLastError();
   }
-  const int vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(ld.A) & 15u) == 0) &&
-                  ((reinterpret_cast<uintptr_t>(x) & 15u) == 0);
-  hipLaunchKernelGGL(k_grad_margins, dim3((unsigned)((ld.rows + 3) / 4)), dim3(kBlock), 0, st, ld, x, d, vec);
+  const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(ld.A) & 15u) == 0) &&
+                   ((reinterpret_cast<uintptr_t>(x) & 15u) == 0);
+  const int lpr = d >= 1024 ? 64 : 16;
+  const dim3 grid((unsigned)((ld.rows * lpr + kBlock - 1) / kBlock));
+  if (lpr == 64) {
+    if (vec) hipLaunchKernelGGL((k_grad_margins<64, true>), grid, dim3(kBlock), 0, st, ld, x, d);
+    else hipLaunchKernelGGL((k_grad_margins<64, false>), grid, dim3(kBlock), 0, st, ld, x, d);
+  } else {
+    if (vec) hipLaunchKernelGGL((k_grad_margins<16, true>), grid, dim3(kBlock), 0, st, ld, x, d);
+    else hipLaunchKernelGGL((k_grad_margins<16, false>), grid, dim3(kBlock), 0, st, ld, x, d);
+  }
   return hipGetLastError();
 }
 
@@ -379,18 +418,11 @@ hipError_t launch_grad_cols(const LogisticData& ld, const float* x, float* grads
   }
   const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(ld.A) & 15u) == 0);
   const int rpc = (int)((ld.max_rows + ld.row_chunks - 1) / ld.row_chunks);
-  const int64_t cols_per_block = (int64_t)kBlock * (vec ? 4 : 1);
+  const int64_t cols_per_block = 64 * (vec ? 4 : 1);
   const dim3 grid((unsigned)((d + cols_per_block - 1) / cols_per_block), ld.row_chunks, n);
   if (vec) hipLaunchKernelGGL((k_grad_cols<true>), grid, dim3(kBlock), 0, st, ld, x, grads, d, rpc);
   else hipLaunchKernelGGL((k_grad_cols<false>), grid, dim3(kBlock), 0, st, ld, x, grads, d, rpc);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  if (ld.row_chunks > 1) {
-    hipLaunchKernelGGL(k_grad_finish, dim3((unsigned)((d + kBlock - 1) / kBlock), n), dim3(kBlock), 0, st, ld, x,
-                       grads, d);
-    e = hipGetLastError();
-  }
-  return e;
+  return hipGetLastError();
 }
 
 }  // namespace adacgd
