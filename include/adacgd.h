@@ -219,7 +219,9 @@ enum adacgd_field {
  * Top-K levels only run sample + scan (the scan also extracts the candidates); the filter slot
  * then holds the second scan that repairs a failed estimate (idle otherwise).  Other vectors run
  * scan + filter as two passes.  Vectors of at most 4096 coordinates are handled by one kernel
- * that does the whole compression step of a node, timed in the scan slot. */
+ * that does the whole compression step of a node, timed in the scan slot; with at most 64 workers
+ * and Top-K levels only that launch also aggregates (the aggregate slot stays empty), and the
+ * launch that finishes g also writes the next iterate (the xupdate slot stays empty). */
 enum adacgd_kernel {
   ADACGD_K_XUPDATE = 0,
   ADACGD_K_GRAD_MARGIN = 1,
