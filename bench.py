@@ -249,7 +249,8 @@ def main():
         "algorithmic_bytes_per_step": alg_bytes_step, "avg_ms_per_step": group_ms,
         "dominant_kernel": {"name": dom, "avg_ms": per_kernel[dom]["avg_ms"],
                             "bytes_read_per_launch": dom_bytes,
-                            "GB/s": dom_bytes / (per_kernel[dom]["avg_ms"] * 1e-3) / 1e9},
+                            "GB/s": dom_bytes / (per_kernel[dom]["avg_ms"] * 1e-3) / 1e9,
+                            "frac": dom_bytes / (per_kernel[dom]["avg_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "kernels_avg_ms": {k: round(v["avg_ms"], 5) for k, v in per_kernel.items()},
     }
 
