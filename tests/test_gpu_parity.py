@@ -812,3 +812,33 @@ def test_sparse_rows_degenerate_shapes():
         eng.step()
         assert_close_rel(eng.state(E.F_X), orc.x, TRAJ_RTOL, ("x", t))
     eng.close()
+
+
+@pytest.mark.parametrize("master", [True, False])
+@pytest.mark.parametrize("n", [5, 70])
+def test_overlap_mode_short_vectors(n, master):
+    """Overlap mode on the one-block path (with and without the aggregation done by the workers' launch,
+    with and without a master compressor): same results as the oracle, step by step."""
+    E = _eng()
+    d = 700
+    rng = np.random.default_rng(n)
+    wl = [(O.TOPK, 3), (O.TOPK, 40), (O.TOPK, 300)]
+    ml = [(O.TOPK, 50)] if master else []
+    grads = [rng.standard_normal((n, d)).astype(np.float32)]
+    for t in range(8):
+        grads.append((grads[-1] + np.float32(10.0 ** rng.uniform(-2, 0)) * rng.standard_normal((n, d))).astype(np.float32))
+    x0 = rng.standard_normal(d).astype(np.float32)
+    orc = O.AdaCGDOracle(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0, master_levels=ml, zeta_master=0.5)
+    orc.init(x0, grads[0], O.INIT_FULLGRAD)
+    arrs = [_cuda(g) for g in grads]
+    eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0, master_levels=ml, zeta_master=0.5,
+                   grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=arrs[0], flags=E.FLAG_OVERLAP | E.FLAG_RETAIN_EXT)
+    for t in range(1, 9):
+        res, rm = orc.step(grads=grads[t])
+        eng.step(arrs[t])
+        if t % 3 == 0 or t == 8:
+            if rm is not None and rm.margins and min(rm.margins) < 1e-12:
+                pytest.skip("a master trigger comparison is within 1e-12 of equality")
+            compare_step(eng, orc, res, rm, (n, master, t))
+    assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+    eng.close()
