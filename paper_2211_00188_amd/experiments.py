@@ -154,7 +154,7 @@ def sweep(wl, methods=METHODS, multipliers=tuple(2 ** k for k in range(9)), bit_
             final = gn[-1] if np.isfinite(gn[-1]) else float("inf")
             if best is None or final < best["grad_norm_sq"]:
                 best = {"multiplier": mult, "grad_norm_sq": final, "steps": int(s[-1]), "bits_per_worker": float(b[-1]),
-                        "gamma": g0 * mult}
+                        "gamma": g0 * mult, "curve": (s, b, gn)}
         out[m] = best
     return out
 
@@ -165,6 +165,8 @@ def main():
     ap.add_argument("--budget-bits", type=float, default=2e6, help="uplink bits per worker at which a run stops")
     ap.add_argument("--max-multiplier-log2", type=int, default=8)
     ap.add_argument("--zeta", type=float, default=1.0)
+    ap.add_argument("--curves", metavar="FILE", help="write the best run of every method as CSV rows "
+                    "method,step,bits_per_worker,grad_norm_sq (the axes of the paper's figures)")
     args = ap.parse_args()
     wl = W.tiny() if args.workload == "tiny" else W.sparse_logreg()
     res = sweep(wl, multipliers=tuple(2 ** k for k in range(args.max_multiplier_log2 + 1)),
@@ -173,6 +175,12 @@ def main():
     for m, r in res.items():
         print("%-8s %10d %12.4g %10d %16.4g %14.6g" % (m, r["multiplier"], r["gamma"], r["steps"],
                                                      r["bits_per_worker"], r["grad_norm_sq"]))
+    if args.curves:
+        with open(args.curves, "w") as f:
+            f.write("method,step,bits_per_worker,grad_norm_sq\n")
+            for m, r in res.items():
+                for st, b, g in zip(*r["curve"]):
+                    f.write("%s,%d,%.17g,%.17g\n" % (m, st, b, g))
 
 
 if __name__ == "__main__":
