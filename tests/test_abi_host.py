@@ -114,3 +114,27 @@ def test_sparse_rows_are_validated_on_the_host():
     cfg, _ = _cfg(grad_mode=E.GRAD_LOGISTIC_CSR, shard_offsets=np.array([0, 1, 2, 3, 4], dtype=np.int64))
     with pytest.raises(E.AdaCGDError):
         E.adacgd_workspace_bytes(cfg)               # no row_ptr
+
+
+def test_header_is_plain_c_and_matches_the_binding(tmp_path):
+    """The header compiles as C99 on its own, and the configuration struct has the size and field
+    offsets the ctypes binding assumes."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    fields = [name for name, _ in E.Config._fields_]
+    renamed = {"lam": "lambda"}
+    src = tmp_path / "abi.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "adacgd.h"\n'
+        "int main(void) {\n"
+        '  printf("%zu %zu %zu\\n", sizeof(adacgd_config), sizeof(adacgd_level), sizeof(adacgd_trigger));\n'
+        + "".join('  printf("%%zu\\n", offsetof(adacgd_config, %s));\n' % renamed.get(f, f) for f in fields)
+        + "  return (int)(ADACGD_NUM_KERNELS - 20 + ADACGD_F_ESTIMATOR_ERR - 29);\n}\n")
+    exe = tmp_path / "abi"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert [int(v) for v in out[:3]] == [C.sizeof(E.Config), C.sizeof(E.Level), C.sizeof(E.Trigger)]
+    assert [int(v) for v in out[3:]] == [getattr(E.Config, f).offset for f in fields]
