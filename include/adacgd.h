@@ -251,6 +251,18 @@ enum adacgd_kernel {
  * size exactly, else ADACGD_ERR_FIELD and nothing is written. */
 int adacgd_state(adacgd_ctx* ctx, int32_t field, void* dst, int64_t dst_bytes, int32_t dst_on_device);
 
+/* Restores persistent state, e.g. from a checkpoint made of adacgd_state copies: field is one of
+ * F_X, F_G (only with a master compressor; otherwise g is g~), F_GTILDE, F_GTILDE_PREV, F_GI,
+ * F_PREV_GRAD, F_STEP (also the Philox counter of the next step), F_LEVEL_HIST, F_M_LEVEL_HIST; any
+ * other field gives ADACGD_ERR_FIELD.  src is host memory, or device memory if src_on_device != 0;
+ * src_bytes must equal the field's size exactly, else ADACGD_ERR_FIELD and nothing is written.
+ * Synchronises the context's stream before and after the copy.  The per-step outputs of the last
+ * step (levels, errors, messages) are not part of this state and keep their values until the next
+ * step.  With ADACGD_FLAG_RETAIN_EXT, F_PREV_GRAD is copied into the engine's own buffer, which
+ * replaces the caller's retained array as y of the next step.  A run restored with all nine fields
+ * continues bit for bit like the run the copies were taken from. */
+int adacgd_set_state(adacgd_ctx* ctx, int32_t field, const void* src, int64_t src_bytes, int32_t src_on_device);
+
 /* Synchronises the stream and frees the context (the workspace returns to the
  * caller).  NULL is accepted. */
 int adacgd_destroy(adacgd_ctx* ctx);

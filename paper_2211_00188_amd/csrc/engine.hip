@@ -952,6 +952,60 @@ int adacgd_state(adacgd_ctx* c, int32_t field, void* dst, int64_t dst_bytes, int
   }
 }
 
+int adacgd_set_state(adacgd_ctx* c, int32_t field, const void* src, int64_t src_bytes, int32_t src_on_device) {
+  if (!c) return ADACGD_ERR_ARG;
+  if (!src) { set_err(c->err, "src is null"); return ADACGD_ERR_ARG; }
+  if (c->wst) HIPCHK(c, hipStreamSynchronize(c->wst));
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  const int64_t n = c->n, d = c->d;
+  const hipMemcpyKind kind = src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+  auto put = [&](void* dst, int64_t bytes) -> int {
+    if (bytes != src_bytes) {
+      set_err(c->err, "field %d holds %lld bytes, source has %lld", field, (long long)bytes, (long long)src_bytes);
+      return ADACGD_ERR_FIELD;
+    }
+    if (!dst) { set_err(c->err, "field %d is not kept in this mode", field); return ADACGD_ERR_STATE; }
+    HIPCHK(c, hipMemcpyAsync(dst, src, (size_t)bytes, kind, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    return ADACGD_OK;
+  };
+  switch (field) {
+    case ADACGD_F_X:
+      c->x_next_valid = false;      // the iterate written ahead belonged to the old x
+      return put(c->x, d * 4);
+    case ADACGD_F_G:
+      c->x_next_valid = false;
+      return put(c->has_master ? c->g_own : nullptr, d * 4);
+    case ADACGD_F_GTILDE:
+      if (!c->has_master) c->x_next_valid = false;   // g is g~ then
+      return put(c->gt[c->cur], d * 4);
+    case ADACGD_F_GTILDE_PREV: return put(c->gt[c->cur ^ 1], d * 4);
+    case ADACGD_F_GI: return put(c->gi, n * d * 4);
+    case ADACGD_F_PREV_GRAD:
+    case ADACGD_F_GRAD:
+      if (c->grad_mode == ADACGD_DIFF_EXTERNAL) return put(nullptr, n * d * 4);
+      if (c->y_ext) {               // the caller's retained array is replaced by the engine's own buffer
+        c->y_ext = nullptr;
+        c->ycur = 0;
+      }
+      return put(c->yb[c->ycur], n * d * 4);
+    case ADACGD_F_STEP: {
+      if (src_bytes != 8) { set_err(c->err, "field %d holds 8 bytes, source has %lld", field, (long long)src_bytes); return ADACGD_ERR_FIELD; }
+      int64_t v = 0;
+      if (src_on_device) HIPCHK(c, hipMemcpy(&v, src, 8, hipMemcpyDeviceToHost));
+      else std::memcpy(&v, src, 8);
+      if (v < 0) { set_err(c->err, "step count is negative"); return ADACGD_ERR_ARG; }
+      c->step = v;
+      return ADACGD_OK;
+    }
+    case ADACGD_F_LEVEL_HIST: return put(c->W.level_hist, (int64_t)(c->W.lv.m + 1) * 8);
+    case ADACGD_F_M_LEVEL_HIST: return put(c->has_master ? c->M.level_hist : nullptr, (int64_t)(c->M.lv.m + 1) * 8);
+    default:
+      set_err(c->err, "field %d cannot be set", field);
+      return ADACGD_ERR_FIELD;
+  }
+}
+
 int adacgd_destroy(adacgd_ctx* c) {
   if (!c) return ADACGD_OK;
   if (c->wst) {

@@ -30,8 +30,8 @@ KERNELS = ["xupdate", "grad_margin", "grad_cols", "aggregate",
            "w_sample", "w_scan", "w_filter", "w_gather", "w_select", "w_tally", "w_compact", "w_qapply",
            "m_sample", "m_scan", "m_filter", "m_gather", "m_select", "m_tally", "m_compact", "m_qapply"]
 
-EXPORTS = ["adacgd_workspace_bytes", "adacgd_init", "adacgd_step", "adacgd_state", "adacgd_destroy",
-           "adacgd_last_error"]
+EXPORTS = ["adacgd_workspace_bytes", "adacgd_init", "adacgd_step", "adacgd_state", "adacgd_set_state",
+           "adacgd_destroy", "adacgd_last_error"]
 
 
 class Level(C.Structure):
@@ -85,6 +85,8 @@ def load_library():
         lib.adacgd_step.restype = C.c_int
         lib.adacgd_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_int32]
         lib.adacgd_state.restype = C.c_int
+        lib.adacgd_set_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_int32]
+        lib.adacgd_set_state.restype = C.c_int
         lib.adacgd_destroy.argtypes = [C.c_void_p]
         lib.adacgd_destroy.restype = C.c_int
         lib.adacgd_last_error.argtypes = [C.c_void_p]
@@ -186,6 +188,15 @@ def adacgd_state(ctx, field, out: np.ndarray):
     return out
 
 
+def adacgd_set_state(ctx, field, src: np.ndarray):
+    """Restores a persistent field from the host array `src` (whose size must match exactly)."""
+    lib = load_library()
+    src = np.ascontiguousarray(src)
+    rc = lib.adacgd_set_state(ctx, int(field), src.ctypes.data_as(C.c_void_p), src.nbytes, 0)
+    if rc:
+        raise AdaCGDError(rc, lib.adacgd_last_error(ctx).decode())
+
+
 def adacgd_destroy(ctx):
     lib = load_library()
     rc = lib.adacgd_destroy(ctx)
@@ -276,6 +287,26 @@ class AdaCGD:
         if field == F_KERNEL_MS:
             return self._get(field, (2, len(KERNELS)), f64)
         raise ValueError(field)
+
+    CHECKPOINT_FIELDS = (F_X, F_G, F_GTILDE, F_GTILDE_PREV, F_GI, F_PREV_GRAD, F_STEP, F_LEVEL_HIST, F_M_LEVEL_HIST)
+
+    def set_state(self, field, array):
+        adacgd_set_state(self.ctx, field, array)
+
+    def checkpoint(self):
+        """{field: host array} of everything a restored run needs (fields this mode does not keep are left out)."""
+        out = {}
+        for f in self.CHECKPOINT_FIELDS:
+            if f in (F_G, F_M_LEVEL_HIST) and not self.master_levels:
+                continue
+            if f == F_PREV_GRAD and self.grad_mode == DIFF_EXTERNAL:
+                continue
+            out[f] = self.state(f)
+        return out
+
+    def restore(self, ckpt):
+        for f, a in ckpt.items():
+            self.set_state(f, a)
 
     def messages(self):
         """Per-worker (indices, values) of the last step's Top-K messages."""

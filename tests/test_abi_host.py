@@ -73,6 +73,7 @@ def test_init_rejects_missing_pointers_without_touching_the_device():
     assert b"x0" in lib.adacgd_last_error(None)
     assert lib.adacgd_destroy(None) == 0
     assert lib.adacgd_step(None, None, None, 1) == 1
+    assert lib.adacgd_set_state(None, 0, None, 0, 0) == 1
 
 
 def test_logistic_shards_validated():

@@ -842,3 +842,46 @@ def test_overlap_mode_short_vectors(n, master):
             compare_step(eng, orc, res, rm, (n, master, t))
     assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
     eng.close()
+
+
+@pytest.mark.parametrize("n,d,flags", [(4, 900, 0), (3, 3 * 8192 + 516, 0), (2, 130 * 8192, 0), (3, 20000, "retain")])
+def test_checkpoint_and_restore_continue_bit_for_bit(n, d, flags):
+    """State copied out after three steps and restored into a context that was initialised from other
+    data continues exactly like the uninterrupted run (mixed level set: the Philox counter is part of it)."""
+    E = _eng()
+    rng = np.random.default_rng(d)
+    wl = W.sort_levels([(O.TOPK, max(1, d // 300)), (O.QUANT, 4), (O.TOPK, max(2, d // 10))], d)
+    if d >= 130 * 8192:
+        wl = [(O.TOPK, d // 300), (O.TOPK, d // 10)]              # one-pass sequence
+    ml = [(O.TOPK, max(1, d // 50))]
+    grads = [make_vectors(rng, n, d, "normal") for _ in range(7)]
+    for t in range(1, 7):
+        grads[t] = (grads[t - 1] + grads[t] * np.float32(0.3)).astype(np.float32)
+    arrs = [_cuda(g) for g in grads]
+    x0 = rng.standard_normal(d).astype(np.float32)
+    fl = E.FLAG_RETAIN_EXT if flags == "retain" else 0
+    kw = dict(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0, master_levels=ml, zeta_master=0.3,
+              grad_mode=E.GRAD_EXTERNAL, seed=9, flags=fl)
+    a = E.AdaCGD(x0=_cuda(x0), grad0=arrs[0], **kw)
+    for t in range(1, 4):
+        a.step(arrs[t])
+    ck = a.checkpoint()
+    for t in range(4, 7):
+        a.step(arrs[t])
+    b = E.AdaCGD(x0=_cuda(np.zeros(d, dtype=np.float32)), grad0=arrs[5], **kw)
+    b.step(arrs[6])                                                # some unrelated history
+    b.restore(ck)
+    assert int(b.state(E.F_STEP)[0]) == 3
+    for t in range(4, 7):
+        b.step(arrs[t])
+    for f in E.AdaCGD.CHECKPOINT_FIELDS + (E.F_LEVEL, E.F_MSG_IDX, E.F_MSG_VAL, E.F_ERR, E.F_COMM):
+        fa, fb = a.state(f), b.state(f)
+        assert np.array_equal(np.ascontiguousarray(fa).view(np.uint8), np.ascontiguousarray(fb).view(np.uint8)), f
+    with pytest.raises(E.AdaCGDError) as ei:
+        b.set_state(E.F_LEVEL, np.zeros(n, dtype=np.int32))
+    assert ei.value.code == 6
+    with pytest.raises(E.AdaCGDError) as ei:
+        b.set_state(E.F_X, np.zeros(d + 1, dtype=np.float32))
+    assert ei.value.code == 6
+    a.close()
+    b.close()
