@@ -126,7 +126,7 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.kmax = c.take<uint32_t>(nn);
   ns.agg_done = ns.AS > 1 ? c.take<uint32_t>((size_t)ns.groups * (kArriveFan + 1) * kCounterStride) : nullptr;
   ns.level_hist = c.take<unsigned long long>(m + 2);
-  ns.repairs = ns.level_hist + m + 1;
+  ns.repairs = ns.level_hist ? ns.level_hist + m + 1 : nullptr;   // (null when only measuring)
   // everything up to here must start at zero
   ns.prefix = c.take<uint32_t>(nn * p);
   ns.rank = c.take<uint32_t>(nn * p);
