@@ -1015,8 +1015,8 @@ int adacgd_destroy(adacgd_ctx* c) {
     (void)hipEventDestroy(c->ev_agg);
   }
   hipError_t e = hipStreamSynchronize(c->st);
-  for (auto& s : c->spans) { hipEventDestroy(s.a); hipEventDestroy(s.b); }
-  for (auto ev : c->pool) hipEventDestroy(ev);
+  for (auto& s : c->spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
+  for (auto ev : c->pool) (void)hipEventDestroy(ev);
   delete c;
   return e == hipSuccess ? ADACGD_OK : ADACGD_ERR_DEVICE;
 }
