@@ -885,3 +885,28 @@ def test_checkpoint_and_restore_continue_bit_for_bit(n, d, flags):
     assert ei.value.code == 6
     a.close()
     b.close()
+
+
+def test_stored_trajectory_from_the_engine():
+    """The stored trajectory (tests/golden, written from the oracle) out of the HIP path."""
+    import importlib.util
+    import os
+    E = _eng()
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_trajectory_golden", os.path.join(here, "make_trajectory_golden.py"))
+    G = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(G)
+    stored = open(os.path.join(here, "trajectory_tiny_external.txt")).read().splitlines()
+    x0, grads = G.inputs()
+    eng = E.AdaCGD(n=G.N, d=G.D, gamma=G.GAMMA, worker_levels=G.WORKER_LEVELS, zeta_worker=G.ZETA_W,
+                   master_levels=G.MASTER_LEVELS, zeta_master=G.ZETA_M, seed=G.SEED, grad_mode=E.GRAD_EXTERNAL,
+                   x0=_cuda(x0), grad0=_cuda(grads[0]), flags=E.FLAG_ANY_LEVEL_ORDER)   # the 4-bit level sits before Top-25
+    for t in range(1, G.STEPS + 1):
+        eng.step(_cuda(grads[t]))
+        msgs = ";".join(",".join(str(int(i)) for i in m[0]) for m in eng.messages())
+        line = "%d | %s | %d | %s | %s %s %s %s" % (
+            t, " ".join(str(int(v)) for v in eng.state(E.F_LEVEL)), int(eng.state(E.F_M_LEVEL)[0]), msgs,
+            G.digest(eng.state(E.F_X)), G.digest(eng.state(E.F_G)), G.digest(eng.state(E.F_GTILDE)),
+            G.digest(eng.state(E.F_GI)))
+        assert line == stored[t], t
+    eng.close()

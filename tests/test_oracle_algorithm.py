@@ -383,3 +383,18 @@ def test_compressed_start_is_topk_of_the_first_gradients():
         want = h[i].copy()
         want[order] = h[i][order] + v[order]
         assert np.array_equal(orc.gi[i], want)
+
+
+def test_stored_trajectory_is_reproduced():
+    """tests/golden/trajectory_tiny_external.txt (written by make_trajectory_golden.py from the oracle
+    alone) still comes out of the oracle: level choices, supports and every state vector, bit for bit."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_trajectory_golden", os.path.join(here, "make_trajectory_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = open(os.path.join(here, "trajectory_tiny_external.txt")).read().splitlines()
+    assert mod.lines() == stored
+    levels = {int(v) for line in stored[1:] for v in line.split("|")[1].split()}
+    assert levels == {0, 1, 2, 3, 4}                      # the stored run visits every branch of the cascade
