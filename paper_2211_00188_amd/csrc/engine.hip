@@ -190,12 +190,19 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
                 4 * (int64_t)ns.Kcap <= d) ? 1 : 0;
   ns.small = (!force_two_pass && d <= kSmallMax) ? 1 : 0;
   // streaming kernels: about 5120 blocks in all for the fused scan (several short blocks per CU
-  // interleave better with kernels of another stream than few long ones), about 2560 for the
+  // interleave better with kernels of another stream than few long ones), about 2048 for the
   // two-pass scan (whose blocks each flush a full histogram); at most 640 per node
-  int want = ((ns.onepass ? 5120 : 2560) + nn - 1) / nn;
+  int want = ((ns.onepass ? 5120 : 2048) + nn - 1) / nn;
   if (want > 640) want = 640;
   ns.G = ns.tiles < want ? ns.tiles : want;
   if (ns.G < 1) ns.G = 1;
+  if (!ns.onepass) {
+    // The two-pass kernels are short: 2048 blocks are resident at once, and a launch that needs a
+    // second round of blocks, or whose blocks own unequal numbers of tiles, waits for its stragglers.
+    // Hence at most one round, every block with the same number of tiles (the last one may have fewer).
+    const int per_block = (ns.tiles + ns.G - 1) / ns.G;
+    ns.G = (ns.tiles + per_block - 1) / per_block;
+  }
   // select kernels: up to 8 blocks per (Top-K size, node) share a long list (most lists are
   // short and all but a few blocks exit at once, so the launch should stay small)
   // aggregation: one block per group of 2048 coordinates adds every worker's share; short vectors

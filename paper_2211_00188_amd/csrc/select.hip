@@ -96,6 +96,7 @@ __device__ __forceinline__ void store4(float* __restrict__ p, int64_t l0, int64_
 
 // Walks a histogram of this launch from its top bin down and finds, for each of nr
 // ranks, the bin where the running count reaches the rank.  Zeroes the histogram.
+__device__ __forceinline__ uint32_t hist0_slot(uint32_t bin) { return ((bin & 31u) << 7) | (bin >> 5); }
 template <int NB>
 __device__ void locate(uint32_t* hist, int nr, const uint32_t* rank, uint32_t* out_bin, uint32_t* out_rank,
                        uint32_t* out_cnt, uint32_t* lds4) {
@@ -104,9 +105,10 @@ __device__ void locate(uint32_t* hist, int nr, const uint32_t* rank, uint32_t* o
   uint32_t sum = 0;
   const int top = NB - 1 - (int)threadIdx.x * PER;
 #pragma unroll
+  for (int q = 0; q < PER; ++q) loc[q] = ld_coherent(&hist[hist0_slot((uint32_t)(top - q))]);
+#pragma unroll
   for (int q = 0; q < PER; ++q) {
-    loc[q] = ld_coherent(&hist[top - q]);
-    hist[top - q] = 0;
+    hist[hist0_slot((uint32_t)(top - q))] = 0;
     sum += loc[q];
   }
   uint32_t total;
@@ -245,7 +247,7 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
   uint32_t* gh = ns.hist0 + (size_t)node * kBins0;
   for (int b = tid; b < kBins0; b += kBlock) {
     const uint32_t c = hist[b];
-    if (c) atomicAdd(&gh[b], c);
+    if (c) atomicAdd(&gh[hist0_slot((uint32_t)b)], c);
   }
 
   if (!arrive_last(&ns.done[(size_t)node * (kArriveFan + 1) * kCounterStride], gridDim.x, blockIdx.x, &s_flag)) return;
@@ -510,7 +512,7 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
   uint32_t* gh = ns.hist0 + (size_t)node * kBins0;
   for (int b = tid; b < kBins0; b += kBlock) {
     const uint32_t c = hist[b];
-    if (c) atomicAdd(&gh[b], c);
+    if (c) atomicAdd(&gh[hist0_slot((uint32_t)b)], c);
   }
 
   if (!arrive_last(&ns.done[(size_t)node * (kArriveFan + 1) * kCounterStride], gridDim.x, blockIdx.x, &s_flag)) return;
