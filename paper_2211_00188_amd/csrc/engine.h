@@ -65,12 +65,11 @@ struct NodeSet {
   uint32_t* rank;       // [nn][p]                rank of the K_s-th element inside the prefix
   uint32_t* eqcnt;      // [nn][p]                count of keys equal to T_s
   uint32_t* bmin;       // [nn]                   lowest first-digit bin that holds candidates
-  uint32_t* ncand;      // [nn] (one per 64 bytes) candidates found by the fused scan; zero between launches
   uint32_t* best;       // [nn]                   candidate cut (a key) estimated from the sample
   uint32_t* redo;       // [nn]                   1 = fewer candidates than the largest K: the repair passes run
   uint32_t* skip;       // [nn]                   1 = ||x-h||^2 <= zeta ||x-y||^2: h is kept, no selection work
   uint32_t* done;       // [nn][kArriveFan+1]     arrival counters of the last-block epilogues
-  uint32_t* kmax;       // [nn]                   running max magnitude key of the current scan; zero between launches
+  uint32_t* partU;      // [nn][G]                per block: largest key (two-pass scan) or candidates found (fused scan)
   uint32_t* amax;       // [nn]                   max magnitude key of the last scan (quantiser scale a)
   double* partS;        // [nn][G]
   double* partD;        // [nn][G]

@@ -121,9 +121,7 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.gcur = c.take<uint32_t>(nn * 64);   // one cursor per 256 bytes
   ns.sel_hist = c.take<uint32_t>(nn * p * kBins1);
   ns.sel_done = c.take<uint32_t>(nn * p * (kArriveFan + 1) * kCounterStride);
-  ns.ncand = c.take<uint32_t>(nn * kCounterStride);
   ns.done = c.take<uint32_t>(nn * (kArriveFan + 1) * kCounterStride);
-  ns.kmax = c.take<uint32_t>(nn);
   ns.agg_done = ns.AS > 1 ? c.take<uint32_t>((size_t)ns.groups * (kArriveFan + 1) * kCounterStride) : nullptr;
   ns.level_hist = c.take<unsigned long long>(m + 2);
   ns.repairs = ns.level_hist ? ns.level_hist + m + 1 : nullptr;   // (null when only measuring)
@@ -136,6 +134,7 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.best = c.take<uint32_t>(nn);
   ns.redo = c.take<uint32_t>(nn);
   ns.skip = c.take<uint32_t>(nn);
+  ns.partU = c.take<uint32_t>(nn * ns.G);
   ns.partS = c.take<double>(nn * ns.G);
   ns.partD = c.take<double>(nn * ns.G);
   ns.partEb = c.take<double>(nn * ns.G);

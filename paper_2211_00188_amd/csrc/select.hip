@@ -190,6 +190,7 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
   __shared__ uint32_t lds4[4];
   __shared__ int s_flag;
   __shared__ uint32_t s_rank[kMaxLevels], s_bin[kMaxLevels], s_rk[kMaxLevels], s_cnt[kMaxLevels];
+  __shared__ uint32_t s_kmax;
 
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int64_t d = ns.d;
@@ -239,9 +240,14 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
     st_coherent(&ns.partS[(size_t)node * ns.G + blockIdx.x], S);
     st_coherent(&ns.partD[(size_t)node * ns.G + blockIdx.x], D);
   }
-  if (ns.lv.nq > 0) {
+  if (ns.lv.nq > 0) {       // the block's largest key, as one more partial result (no shared counter)
     kmax = wave_max(kmax);
-    if (lane == 0) atomicMax(&ns.kmax[node], kmax);
+    if (lane == 0) lds4[w] = kmax;
+    __syncthreads();
+    if (tid == 0) {
+      const uint32_t a01 = lds4[0] > lds4[1] ? lds4[0] : lds4[1], a23 = lds4[2] > lds4[3] ? lds4[2] : lds4[3];
+      st_coherent(&ns.partU[(size_t)node * ns.G + blockIdx.x], a01 > a23 ? a01 : a23);
+    }
   }
   __syncthreads();
   uint32_t* gh = ns.hist0 + (size_t)node * kBins0;
@@ -261,6 +267,21 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
   }
   s = block_sum(s, red);
   dd = block_sum(dd, red);
+  if (ns.lv.nq > 0) {
+    uint32_t km = 0;
+    for (int b = tid; b < (int)gridDim.x; b += kBlock) {
+      const uint32_t v = ld_coherent(&ns.partU[(size_t)node * ns.G + b]);
+      km = v > km ? v : km;
+    }
+    km = wave_max(km);
+    __syncthreads();
+    if (lane == 0) lds4[w] = km;
+    __syncthreads();
+    if (tid == 0) {
+      const uint32_t a01 = lds4[0] > lds4[1] ? lds4[0] : lds4[1], a23 = lds4[2] > lds4[3] ? lds4[2] : lds4[3];
+      s_kmax = a01 > a23 ? a01 : a23;
+    }
+  }
   if (tid < kMaxLevels) {
     s_rank[tid] = tid < p ? ns.lv.K[tid] : 0;
     s_bin[tid] = 0; s_rk[tid] = 1; s_cnt[tid] = 0;
@@ -279,10 +300,7 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
     // to do for the node (the tally kernel takes the same decision from the same two numbers)
     ns.skip[node] = s <= trigger_bound(ns.lv, 0, s, dnode) ? 1u : 0u;
     ns.bmin[node] = p > 0 ? s_bin[p - 1] : (uint32_t)kBins0;   // largest K reaches lowest
-    if (ns.lv.nq > 0) {
-      ns.amax[node] = ld_coherent(&ns.kmax[node]);
-      ns.kmax[node] = 0;
-    }
+    if (ns.lv.nq > 0) ns.amax[node] = s_kmax;
   }
 }
 
@@ -502,8 +520,12 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
   S = block_sum(S, red);
   D = block_sum(D, red);
   El = block_sum(El, red);
-  if (lane == 0 && ncand) atomicAdd(&ns.ncand[(size_t)node * kCounterStride], ncand);
+  ncand = __builtin_amdgcn_readfirstlane(ncand);      // (the same in every lane of a wavefront)
+  __syncthreads();
+  if (lane == 0) lds4[w] = ncand;
+  __syncthreads();
   if (tid == 0) {
+    st_coherent(&ns.partU[(size_t)node * ns.G + blockIdx.x], (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]));
     st_coherent(&ns.partS[(size_t)node * ns.G + blockIdx.x], S);
     st_coherent(&ns.partD[(size_t)node * ns.G + blockIdx.x], D);
     st_coherent(&ns.partEb[(size_t)node * ns.G + blockIdx.x], El);
@@ -519,14 +541,21 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
 
   const int p = ns.lv.p;
   double s = 0.0, dd = 0.0, el = 0.0;
+  uint32_t found = 0;
   for (int b = tid; b < (int)gridDim.x; b += kBlock) {
     s += ld_coherent(&ns.partS[(size_t)node * ns.G + b]);
     dd += ld_coherent(&ns.partD[(size_t)node * ns.G + b]);
     el += ld_coherent(&ns.partEb[(size_t)node * ns.G + b]);
+    found += ld_coherent(&ns.partU[(size_t)node * ns.G + b]);
   }
   s = block_sum(s, red);
   dd = block_sum(dd, red);
   el = block_sum(el, red);
+  found = wave_sum(found);
+  __syncthreads();
+  if (lane == 0) lds4[w] = found;
+  __syncthreads();
+  found = (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
   if (tid < kMaxLevels) {
     s_rank[tid] = tid < p ? ns.lv.K[tid] : 0;
     s_bin[tid] = 0; s_rk[tid] = 1; s_cnt[tid] = 0;
@@ -547,8 +576,7 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
     ns.skip[node] = skip ? 1u : 0u;
     ns.Eb[node] = el;
     // the K largest all have keys >= cut  <=>  at least K candidates were found
-    const uint32_t total = ld_coherent(&ns.ncand[(size_t)node * kCounterStride]);
-    ns.ncand[(size_t)node * kCounterStride] = 0;
+    const uint32_t total = found;
     const bool redo = total < ns.lv.K[p - 1];           // estimate too high: the repair pass runs
     ns.redo[node] = redo ? 1u : 0u;
     if (redo && !skip) atomicAdd(ns.repairs, 1ull);
