@@ -215,6 +215,9 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
   }
   int gz = (int)((d + 262143) / 262144);
   ns.GZ = gz < 1 ? 1 : (gz > 8 ? 8 : gz);
+  // one 1024-thread select block is resident per compute unit: keep the launch within one round
+  const int one_round = 256 / (nn * (ns.lv.p > 0 ? ns.lv.p : 1));
+  if (ns.GZ > one_round) ns.GZ = one_round < 1 ? 1 : one_round;
 }
 
 }  // namespace
