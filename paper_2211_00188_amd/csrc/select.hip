@@ -458,8 +458,8 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
       const uint32_t rot = group_rot((int)grp, d);
       for (uint32_t e = begin + lane; e < end; e += 64) {
         const uint32_t at = (gbase + (e - begin) + rot) & (uint32_t)(kWaveTile - 1);
-        sval[at] = st_val[w][e];
-        soff[at] = st_off[w][e];
+        __builtin_nontemporal_store(st_val[w][e], &sval[at]);
+        __builtin_nontemporal_store(st_off[w][e], &soff[at]);
       }
       if (closed && lane == 0 && (int)grp < ns.groups) ns.grp_count[(size_t)node * ns.groups + grp] = gbase + (end - begin);
       if (!closed) open_base = gbase + (end - begin);
