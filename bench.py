@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/model_sized_n16_d11200000_hbm_traffic.md
 # (reads scaled by 2.0, writes by 1.0, as calibrated there).  Valid only for the default
 # arguments and for the kernels as they were when the counters were taken.
-MEASURED_TRAFFIC_BYTES = 3085.9e6
+MEASURED_TRAFFIC_BYTES = 3086.4e6
 MEASURED_TRAFFIC_KERNELS = "w_sample+w_scan+w_filter+w_gather+w_select+w_tally+w_compact"
 
 
