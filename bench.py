@@ -165,6 +165,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--federated-n", type=int, default=1000,
                     help="workers of the secondary federated workload (1000 = the full configuration, 8.4 GB of features)")
+    ap.add_argument("--secondary", choices=["kernel_stress", "federated", "sparse_features"],
+                    help="run only this secondary workload and print its record (for profiling it on its own)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="run the worker and server chains on one stream (the kernel-timing pass always does)")
     args = ap.parse_args()
@@ -178,6 +180,12 @@ def main():
     from paper_2211_00188_amd import workloads as W
 
     torch.cuda.set_device(0)
+    if args.secondary:
+        rec = {"kernel_stress": lambda: extra_kernel_stress(E, W, torch),
+               "federated": lambda: extra_federated(E, W, torch, args.federated_n),
+               "sparse_features": lambda: extra_sparse_features(E, W, torch)}[args.secondary]()
+        print(json.dumps({"secondary_workload": rec}))
+        return
     wk = W.model_sized(n=args.n, d=args.d, zeta=args.zeta)
     n, d = wk.n, wk.d
     gen = W.ModelSizedGrads(wk)

@@ -297,7 +297,19 @@ __global__ __launch_bounds__(kBlock) void k_csr_margins(LogisticData ld, const f
   const bool live = l < ld.rows;
   const int64_t b = live ? ld.rp[l] : 0, e = live ? ld.rp[l + 1] : 0;
   double acc = 0.0;
-  for (int64_t k = b + sub; k < e; k += LPR) {
+  int64_t k = b + sub;
+  for (; k + 3 * LPR < e; k += 4 * LPR) {          // four entries at a time: their gathers overlap
+    int32_t c[4];
+    float a[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      c[u] = ld.ci[k + u * LPR];
+      a[u] = ld.binary ? 1.f : ld.cv[k + u * LPR];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc = fma((double)a[u], (double)x[c[u]], acc);
+  }
+  for (; k < e; k += LPR) {
     const double a = ld.binary ? 1.0 : (double)ld.cv[k];
     acc = fma(a, (double)x[ld.ci[k]], acc);
   }
@@ -329,6 +341,48 @@ __global__ __launch_bounds__(kBlock) void k_csr_cols(LogisticData ld, const floa
 #pragma unroll
   for (int o = LPC >> 1; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
   if (live && sub == 0) grads[(size_t)node * d + j] = (float)(acc + reg_grad(ld.lambda, (double)x[j]));
+}
+
+// Short columns (a few entries per worker-column): one thread owns four columns, 64 apart, and walks
+// them side by side, so that four independent chains of gathers (row of the entry, then its margin)
+// are in flight instead of one.  Same order of summation per column as k_csr_cols<1>.
+__global__ __launch_bounds__(kBlock) void k_csr_cols4(LogisticData ld, const float* __restrict__ x,
+                                                       float* __restrict__ grads, int64_t d) {
+  const int node = blockIdx.y, w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t j0 = ((int64_t)blockIdx.x * 4 + w) * 256 + lane;      // columns j0, j0+64, j0+128, j0+192
+  const uint32_t* __restrict__ cp = ld.cptr + (size_t)node * (size_t)(d + 1);
+  const int64_t w0 = ld.wbase[node];
+  int64_t b[4], e[4];
+  double acc[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int64_t j = j0 + 64 * c;
+    const bool live = j < d;
+    b[c] = live ? w0 + cp[j] : 0;
+    e[c] = live ? w0 + cp[j + 1] : 0;
+    acc[c] = 0.0;
+  }
+  int64_t longest = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) longest = max(longest, e[c] - b[c]);
+  for (int64_t t = 0; t < longest; ++t) {
+    int32_t r[4];
+    float a[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bool on = b[c] + t < e[c];
+      r[c] = on ? ld.trow[b[c] + t] : -1;
+      a[c] = (on && !ld.binary) ? ld.tval[b[c] + t] : 1.f;
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (r[c] >= 0) acc[c] = fma(ld.margins[r[c]], (double)a[c], acc[c]);
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int64_t j = j0 + 64 * c;
+    if (j < d) grads[(size_t)node * d + j] = (float)(acc[c] + reg_grad(ld.lambda, (double)x[j]));
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -413,7 +467,7 @@ hipError_t launch_grad_cols(const LogisticData& ld, const float* x, float* grads
     const dim3 grid((unsigned)((d * lpc + kBlock - 1) / kBlock), n);
     if (lpc == 64) hipLaunchKernelGGL((k_csr_cols<64>), grid, dim3(kBlock), 0, st, ld, x, grads, d);
     else if (lpc == 16) hipLaunchKernelGGL((k_csr_cols<16>), grid, dim3(kBlock), 0, st, ld, x, grads, d);
-    else hipLaunchKernelGGL((k_csr_cols<1>), grid, dim3(kBlock), 0, st, ld, x, grads, d);
+    else hipLaunchKernelGGL(k_csr_cols4, dim3((unsigned)((d + 1023) / 1024), n), dim3(kBlock), 0, st, ld, x, grads, d);
     return hipGetLastError();
   }
   const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(ld.A) & 15u) == 0);
