@@ -620,8 +620,13 @@ __device__ __forceinline__ float quant_one(float v, float a, float s, float c, f
 // ---------------------------------------------------------------------------
 // filter
 // ---------------------------------------------------------------------------
-template <bool DIFF, bool VEC, bool QUANT>
+// NQ: 0 = no quantiser level; 1..3 = exactly that many (the loops over them carry no run-time test);
+// kMaxLevels = any number.
+template <bool DIFF, bool VEC, int NQ>
 __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
+  constexpr bool QUANT = NQ > 0;
+  constexpr bool EXACT = NQ < kMaxLevels;          // ns.lv.nq == NQ
+  constexpr int NQA = NQ > 0 ? NQ : 1;
   __shared__ double red[4];
   __shared__ int s_flag;
 
@@ -639,13 +644,13 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
 
   // quantiser constants of this node
   float qa = 0.f;
-  float qc[kMaxLevels];
-  double qacc[kMaxLevels];
+  float qc[NQA];
+  double qacc[NQA];
   if (QUANT) {
     qa = __uint_as_float(ns.amax[node]);
 #pragma unroll
-    for (int q = 0; q < kMaxLevels; ++q) {
-      qc[q] = (q < nq && qa > 0.f) ? (float)((double)qa / ns.lv.qdenom[q]) : 0.f;
+    for (int q = 0; q < NQA; ++q) {
+      qc[q] = ((EXACT || q < nq) && qa > 0.f) ? (float)((double)qa / ns.lv.qdenom[q]) : 0.f;
       qacc[q] = 0.0;
     }
   }
@@ -693,8 +698,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
             }
             const float u = dither_of(word);
 #pragma unroll
-            for (int q = 0; q < kMaxLevels; ++q) {
-              if (q < nq) {
+            for (int q = 0; q < NQA; ++q) {
+              if (EXACT || q < nq) {
                 int code;
                 const float cq = qa > 0.f ? quant_one(vv[c], qa, ns.lv.qs[q], qc[q], u, &code) : 0.f;
                 const double e = dv - (double)cq;
@@ -713,8 +718,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   if (tid == 0) st_coherent(&ns.partEb[(size_t)node * ns.G + blockIdx.x], Eb);
   if (QUANT) {
 #pragma unroll
-    for (int q = 0; q < kMaxLevels; ++q) {
-      if (q < nq) {
+    for (int q = 0; q < NQA; ++q) {
+      if (EXACT || q < nq) {
         const double e = block_sum(qacc[q], red);
         if (tid == 0) st_coherent(&ns.partQ[((size_t)node * ns.G + blockIdx.x) * nq + q], e);
       }
@@ -1601,8 +1606,12 @@ hipError_t launch_scan(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
 template <bool DIFF, bool VEC>
 static void launch_filter_q(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   const dim3 grid(ns.G, ns.nn), block(kBlock);
-  if (ns.lv.nq > 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, true>), grid, block, 0, st, ns, a);
-  else hipLaunchKernelGGL((k_filter<DIFF, VEC, false>), grid, block, 0, st, ns, a);
+  const int nq = ns.lv.nq;
+  if (nq == 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, 0>), grid, block, 0, st, ns, a);
+  else if (VEC && nq == 1) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 1 : kMaxLevels>), grid, block, 0, st, ns, a);
+  else if (VEC && nq == 2) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 2 : kMaxLevels>), grid, block, 0, st, ns, a);
+  else if (VEC && nq == 3) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 3 : kMaxLevels>), grid, block, 0, st, ns, a);
+  else hipLaunchKernelGGL((k_filter<DIFF, VEC, kMaxLevels>), grid, block, 0, st, ns, a);
 }
 
 hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
