@@ -1326,7 +1326,7 @@ __device__ __forceinline__ double small_sum(double v, double* red, int nw) {
   return t;
 }
 
-template <bool DIFF>
+template <bool DIFF, bool QUANT>      // QUANT: the level set holds quantisers (otherwise their code is left out)
 __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
   __shared__ uint64_t ck[kSmallMax];       // (key << 32) | ~index, sorted descending
   __shared__ float sv[kSmallMax];          // v by coordinate
@@ -1412,7 +1412,7 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
       if (tid == 0) s_slot_err[s] = e;
     }
     // ---- realised error of every quantiser level ----
-    if (nq > 0) {
+    if (QUANT && nq > 0) {
       const float qa = __uint_as_float(kmax);
       const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
       const uint32_t ctr1 = (uint32_t)node | a.node_flag;
@@ -1532,7 +1532,7 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
       if (ns.groups == 2) go[1] = (uint32_t)lowsum;
       go[ns.groups] = (uint32_t)K;
     }
-  } else if (q >= 0) {
+  } else if (QUANT && q >= 0) {
     // ---- dense update and codes of the chosen quantiser level ----
     const float qa = __uint_as_float(kmax);
     const float qs = lv.qs[q];
@@ -1633,8 +1633,14 @@ hipError_t launch_small(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   while (dp < ns.d) dp <<= 1;
   int nt = dp / 2;                       // one compare-exchange per thread and sort stage
   nt = nt < 64 ? 64 : (nt > 1024 ? 1024 : nt);
-  if (a.diff) hipLaunchKernelGGL((k_small<true>), dim3(ns.nn), dim3(nt), 0, st, ns, a);
-  else hipLaunchKernelGGL((k_small<false>), dim3(ns.nn), dim3(nt), 0, st, ns, a);
+  const dim3 grid(ns.nn), block(nt);
+  if (ns.lv.nq > 0) {
+    if (a.diff) hipLaunchKernelGGL((k_small<true, true>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_small<false, true>), grid, block, 0, st, ns, a);
+  } else {
+    if (a.diff) hipLaunchKernelGGL((k_small<true, false>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_small<false, false>), grid, block, 0, st, ns, a);
+  }
   return hipGetLastError();
 }
 
