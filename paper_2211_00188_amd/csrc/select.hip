@@ -21,7 +21,8 @@
 //             histogram and count, the energy below the cut
 //             epilogue: first digit (bin) and in-bin rank of each Top-K size; marks the node
 //             for repair if fewer candidates than the largest K were found, and as skipping
-//             if the first trigger holds, S <= zeta D in the AdaCGD definition (then every later kernel returns at once for that node)
+//             if the first trigger holds, S <= zeta D in the AdaCGD definition (then every
+//             later kernel returns at once for that node)
 //   scanx (repair variant): idle unless a node is marked; then it redoes the node with the
 //             cut at zero (every coordinate a candidate)
 // Two-pass sequence (level sets with quantisers, short vectors):
@@ -37,6 +38,13 @@
 //             epilogue: err of every level, the cascade, message layout per block
 //   compact : writes the chosen level's message in ascending coordinate and updates h
 //   qapply  : dense update and codes for nodes whose chosen level is a quantiser
+// Short vectors (d <= 4096): k_small, one block per node, does all of the above in one launch and,
+// when asked, the server aggregation (its last block) and the next iterate update.
+//
+// What one block leaves for another block of the same launch (partial sums, its largest key, its
+// candidate count, histogram counts) goes through agent-scope atomic accesses on distinct
+// addresses; nothing is accumulated on one address per node, because read-modify-writes by many
+// blocks on one address are served one after the other.
 #include <type_traits>
 
 #include "devutil.h"
