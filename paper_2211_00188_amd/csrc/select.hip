@@ -43,8 +43,9 @@
 //
 // What one block leaves for another block of the same launch (partial sums, its largest key, its
 // candidate count, histogram counts) goes through agent-scope atomic accesses on distinct
-// addresses; nothing is accumulated on one address per node, because read-modify-writes by many
-// blocks on one address are served one after the other.
+// addresses.  Read-modify-writes by many blocks on one address are served one after the other, so
+// only two things are accumulated that way: the first-digit histogram (spread over 4096 bins) and
+// the gather cursor (one reservation per block).
 #include <type_traits>
 
 #include "devutil.h"
