@@ -910,3 +910,27 @@ def test_stored_trajectory_from_the_engine():
             G.digest(eng.state(E.F_GI)))
         assert line == stored[t], t
     eng.close()
+
+
+@pytest.mark.parametrize("bits_", [(4,), (2, 8), (2, 4, 8), (2, 3, 4, 6, 8)])
+def test_one_to_five_quantiser_levels_bit_exact(bits_):
+    """Level sets with one, two, three (kernels specialised on the count) and five (general kernel)
+    quantiser levels next to two Top-K sizes, on the 16-byte vector path."""
+    E = _eng()
+    n, d = 4, 3 * 8192 + 516
+    rng = np.random.default_rng(len(bits_))
+    wl = W.sort_levels([(O.TOPK, 50), (O.TOPK, 3000)] + [(O.QUANT, b) for b in bits_], d)
+    grads = [make_vectors(rng, n, d, "heavy") for _ in range(5)]
+    for t in range(1, 5):
+        grads[t] = (grads[t - 1] + grads[t] * np.float32(10.0 ** rng.uniform(-2, 0))).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    kw = dict(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=0.05, master_levels=[(O.TOPK, 500)], zeta_master=0.0,
+              seed=77)
+    orc = O.AdaCGDOracle(**kw)
+    orc.init(x0, grads[0], O.INIT_ZERO)
+    eng = E.AdaCGD(grad_mode=E.GRAD_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), grad0=_cuda(grads[0]), **kw)
+    for t in range(1, 5):
+        res, rm = orc.step(grads=grads[t])
+        eng.step(_cuda(grads[t]))
+        compare_step(eng, orc, res, rm, (bits_, t))       # includes the realised error of every quantiser level
+    eng.close()
