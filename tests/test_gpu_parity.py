@@ -934,3 +934,39 @@ def test_one_to_five_quantiser_levels_bit_exact(bits_):
         eng.step(_cuda(grads[t]))
         compare_step(eng, orc, res, rm, (bits_, t))       # includes the realised error of every quantiser level
     eng.close()
+
+
+def test_two_contexts_interleaved_on_two_streams():
+    """Two engines with different shapes, each on a stream of its own, stepped alternately without
+    synchronisation in between: each matches its own oracle (the library keeps no state outside a context)."""
+    E = _eng()
+    import torch
+    specs = [(5, 900, [(O.TOPK, 9), (O.TOPK, 300)], 11), (3, 2 * 8192 + 516, [(O.TOPK, 40), (O.QUANT, 4), (O.TOPK, 5000)], 12)]
+    runs = []
+    for n, d, wl, seed in specs:
+        rng = np.random.default_rng(seed)
+        wl = W.sort_levels(wl, d)
+        grads = [make_vectors(rng, n, d, "normal") for _ in range(6)]
+        for t in range(1, 6):
+            grads[t] = (grads[t - 1] + grads[t] * np.float32(0.3)).astype(np.float32)
+        x0 = rng.standard_normal(d).astype(np.float32)
+        kw = dict(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0, master_levels=[(O.TOPK, max(1, d // 40))],
+                  zeta_master=0.2, seed=seed)
+        orc = O.AdaCGDOracle(**kw)
+        orc.init(x0, grads[0], O.INIT_FULLGRAD)
+        st = torch.cuda.Stream()
+        arrs = [_cuda(g) for g in grads]
+        torch.cuda.synchronize()
+        eng = E.AdaCGD(grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=arrs[0], stream=st.cuda_stream, **kw)
+        runs.append((eng, orc, grads, arrs))
+    for t in range(1, 6):
+        for eng, orc, grads, arrs in runs:
+            eng.step(arrs[t])
+    for eng, orc, grads, arrs in runs:
+        for t in range(1, 6):
+            res, rm = orc.step(grads=grads[t])
+        if min_margin(res + [rm]) < 1e-12:
+            pytest.skip("a trigger comparison is within 1e-12 of equality")
+        compare_step(eng, orc, res, rm, ("interleaved", orc.d))
+        assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+        eng.close()
