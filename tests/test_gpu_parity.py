@@ -970,3 +970,48 @@ def test_two_contexts_interleaved_on_two_streams():
         compare_step(eng, orc, res, rm, ("interleaved", orc.d))
         assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
         eng.close()
+
+
+def test_kernel_stress_full_size_sampled_workers():
+    """The kernel-stress configuration at full size (n = 32, d = 2^20, Top-K and 2/4/8-bit levels, difference
+    mode) for two steps, in the launch configuration the benchmark's secondary run uses: the oracle checks
+    a sample of workers coordinate by coordinate, quantiser codes and scale included; level counts and
+    message sizes are checked for every worker."""
+    E = _eng()
+    wk = W.kernel_stress()
+    n, d = wk.n, wk.d
+    x0 = np.zeros(d, dtype=np.float32)
+    eng = E.AdaCGD(n=n, d=d, gamma=0.1, worker_levels=wk.worker_levels, zeta_worker=wk.zeta_worker,
+                   master_levels=wk.master_levels, zeta_master=0.0, grad_mode=E.DIFF_EXTERNAL,
+                   init_mode=E.INIT_ZERO, x0=_cuda(x0), seed=wk.seed)
+    h = {i: np.zeros(d, dtype=np.float32) for i in (0, 13, 31)}
+    kinds = set()
+    for t in range(2):
+        v, D = W.kernel_stress_diffs(wk, t)
+        eng.step(_cuda(v), _cuda(D))
+        lev = eng.state(E.F_LEVEL)
+        gi = eng.state(E.F_GI)
+        msgs = eng.messages()
+        S, err = eng.state(E.F_SQNORM), eng.state(E.F_ERR)
+        codes, scale = eng.state(E.F_QCODES), eng.state(E.F_QSCALE)
+        for i in h:
+            r = O.adacgd_compress(h[i], None, None, wk.worker_levels, wk.zeta_worker, seed=wk.seed, node=i, step=t,
+                                  D_given=D[i], v_given=v[i])
+            if min(r.margins) < 1e-12:
+                pytest.skip("a trigger comparison is within 1e-12 of equality")
+            assert lev[i] == r.level, (t, i)
+            assert abs(S[i] - r.S) <= RED_RTOL * r.S
+            if r.level > 0:
+                for j, e in enumerate(r.err):
+                    assert abs(err[i, j] - e) <= RED_RTOL * max(e, r.S * 1e-6), (t, i, j)
+                kinds.add(wk.worker_levels[r.level - 1][0])
+            assert np.array_equal(msgs[i][0], r.msg_idx) and np.array_equal(bits(msgs[i][1]), bits(r.msg_val))
+            assert np.array_equal(bits(gi[i]), bits(r.h_new)), (t, i)
+            if r.codes is not None:
+                assert np.array_equal(codes[i].astype(np.int32), r.codes) and scale[i] == np.float32(r.scale)
+            h[i] = r.h_new
+        for i in range(n):
+            want = 0 if lev[i] == 0 or wk.worker_levels[lev[i] - 1][0] != O.TOPK else wk.worker_levels[lev[i] - 1][1]
+            assert len(msgs[i][0]) == want and np.all(np.diff(msgs[i][0]) > 0)
+    assert kinds, "no sampled worker sent anything"
+    eng.close()
