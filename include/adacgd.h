@@ -221,7 +221,8 @@ enum adacgd_field {
  * scan + filter as two passes.  Vectors of at most 4096 coordinates are handled by one kernel
  * that does the whole compression step of a node, timed in the scan slot; with at most 64 workers
  * and Top-K levels only that launch also aggregates (the aggregate slot stays empty), and the
- * launch that finishes g also writes the next iterate (the xupdate slot stays empty). */
+ * launch that finishes g also writes the next iterate (the xupdate slot stays empty); so does the
+ * aggregation of any vector length when there is no master compressor (g is g~ then). */
 enum adacgd_kernel {
   ADACGD_K_XUPDATE = 0,
   ADACGD_K_GRAD_MARGIN = 1,

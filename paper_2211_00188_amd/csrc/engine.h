@@ -172,7 +172,14 @@ hipError_t launch_qapply(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 
 hipError_t launch_xupdate(float* x, const float* g, double gamma, int64_t d, hipStream_t st);
 hipError_t launch_mean(const float* gi, float* out0, float* out1, float* out2, int n, int64_t d, hipStream_t st);
-hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_new, hipStream_t st);
+// optional extra of a kernel that finishes g: x_next = fl(x - gamma g) (out == nullptr: not asked for)
+struct IterateUpdate {
+  const float* x = nullptr;
+  float* out = nullptr;
+  double gamma = 0.0;
+};
+hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_new, const IterateUpdate& xu,
+                            hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* p, uint32_t v, size_t count, hipStream_t st);
 hipError_t launch_copy_f32(float* dst, const float* src, size_t count, hipStream_t st);
 hipError_t launch_grad_margins(const LogisticData& ld, const float* x, int64_t d, hipStream_t st);

@@ -349,7 +349,7 @@ size_t carve_all(char* base, const adacgd_config* cfg, NodeSet& W, NodeSet& M, L
     L.m_zero = base ? (size_t)((char*)M.prefix - (char*)M.hist0) : 0;
   }
   L.x = c.take<float>(d);
-  L.x_next = W.small ? c.take<float>(d) : nullptr;
+  L.x_next = (W.small || M.lv.m == 0) ? c.take<float>(d) : nullptr;
   L.g_own = M.lv.m > 0 ? c.take<float>(d) : nullptr;
   L.gt0 = c.take<float>(d);
   L.gt1 = c.take<float>(d);
@@ -546,8 +546,16 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
     else c->ycur ^= 1;
   }
   // g~^{t+1} = g~^t + (1/n) sum_i messages
-  if (!serve && (rc = timed(c, ADACGD_K_AGGREGATE, [&] { return launch_aggregate(c->W, gt_old, gt_new, c->cs); })))
-    return rc;
+  if (!serve) {
+    IterateUpdate xu{};
+    if (!c->has_master) {           // g is g~: the aggregation also writes the next iterate
+      xu.x = c->x;
+      xu.out = c->x_next;
+      xu.gamma = c->gamma;
+      c->x_next_valid = true;
+    }
+    if ((rc = timed(c, ADACGD_K_AGGREGATE, [&] { return launch_aggregate(c->W, gt_old, gt_new, xu, c->cs); }))) return rc;
+  }
   if (ov) {
     HIPCHK(c, hipEventRecord(c->ev_agg, c->st));
     c->agg_recorded = true;

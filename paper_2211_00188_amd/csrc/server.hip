@@ -49,9 +49,11 @@ __global__ __launch_bounds__(kBlock) void k_copy_f32(float* __restrict__ dst, co
 // ---------------------------------------------------------------------------
 // DENSE_LATER (level sets with quantisers): the fp64 sums of the sparse messages go to ws.accbuf and
 // k_aggregate_dense adds the dense messages and finishes.
+// `xu`: with the identity master g is g~, so the kernel that finishes g~_new can also write the next
+// iterate x_next = fl(x - gamma g~_new) (xu.out null = not asked for).
 template <bool DENSE_LATER>
 __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* __restrict__ gt_old,
-                                                       float* __restrict__ gt_new) {
+                                                       float* __restrict__ gt_new, IterateUpdate xu) {
   __shared__ double acc[kWaveTile];
   __shared__ uint32_t s_lo[kBlock], s_pre[kBlock + 1];
   __shared__ uint32_t lds4[4];
@@ -108,8 +110,13 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
     return;
   }
   const double n = (double)ws.nn;
-  for (int c = tid; c < kWaveTile; c += kBlock)
-    if (base + c < d) gt_new[base + c] = (float)((double)gt_old[base + c] + acc[c] / n);
+  for (int c = tid; c < kWaveTile; c += kBlock) {
+    if (base + c < d) {
+      const float gn = (float)((double)gt_old[base + c] + acc[c] / n);
+      gt_new[base + c] = gn;
+      if (xu.out) xu.out[base + c] = (float)((double)xu.x[base + c] - xu.gamma * (double)gn);
+    }
+  }
 }
 
 // Dense (quantised) messages: a block owns 128 coordinates, each lane two of them (one 4-byte
@@ -119,7 +126,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
 constexpr int kDenseCols = 128;
 constexpr int kDenseWaves = 8;
 __global__ __launch_bounds__(64 * kDenseWaves) void k_aggregate_dense(NodeSet ws, const float* __restrict__ gt_old,
-                                                                      float* __restrict__ gt_new) {
+                                                                      float* __restrict__ gt_new, IterateUpdate xu) {
   __shared__ double part[kDenseWaves][kDenseCols];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int64_t d = ws.d;
@@ -167,7 +174,9 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_aggregate_dense(NodeSet ws
       double tot = ws.accbuf[c];
 #pragma unroll
       for (int j = 0; j < kDenseWaves; ++j) tot += part[j][tid];
-      gt_new[c] = (float)((double)gt_old[c] + tot / (double)ws.nn);
+      const float gn = (float)((double)gt_old[c] + tot / (double)ws.nn);
+      gt_new[c] = gn;
+      if (xu.out) xu.out[c] = (float)((double)xu.x[c] - xu.gamma * (double)gn);
     }
   }
 }
@@ -406,17 +415,18 @@ hipError_t launch_mean(const float* gi, float* o0, float* o1, float* o2, int n, 
   return hipGetLastError();
 }
 
-hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_new, hipStream_t st) {
+hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_new, const IterateUpdate& xu,
+                            hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
   if (ws.lv.nq == 0) {
-    hipLaunchKernelGGL((k_aggregate<false>), dim3(ws.groups, ws.AS), dim3(kBlock), 0, st, ws, gt_old, gt_new);
+    hipLaunchKernelGGL((k_aggregate<false>), dim3(ws.groups, ws.AS), dim3(kBlock), 0, st, ws, gt_old, gt_new, xu);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL((k_aggregate<true>), dim3(ws.groups, ws.AS), dim3(kBlock), 0, st, ws, gt_old, gt_new);
+  hipLaunchKernelGGL((k_aggregate<true>), dim3(ws.groups, ws.AS), dim3(kBlock), 0, st, ws, gt_old, gt_new, IterateUpdate{});
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_aggregate_dense, dim3((unsigned)((ws.d + kDenseCols - 1) / kDenseCols)), dim3(64 * kDenseWaves), 0, st, ws,
-                     gt_old, gt_new);
+                     gt_old, gt_new, xu);
   return hipGetLastError();
 }
 
