@@ -64,19 +64,20 @@ def ratio_K(ratio: float, d: int) -> int:
     return max(1, min(d, math.ceil(ratio * d - 1e-9)))
 
 
-def quant_alpha(d: int, b: int) -> float:
-    """Contraction parameter the library assigns to a b-bit level (used only to
-    order mixed level sets)."""
-    s = 2 ** (b - 1) - 1
-    w = min(d / (4.0 * s * s), math.sqrt(d) / s)
-    return 1.0 / (1.0 + w)
+def federated_levels(d: int) -> list:
+    """Mixed level set of the federated configuration, listed in the order the cascade walks it at
+    the configuration's full size d = 65536 (strongest compression first).  At other sizes the
+    caller orders the set itself, or lets the library accept any order."""
+    lv = [(TOPK, min(d, 16)), (TOPK, min(d, 256)), (QUANT, 4), (TOPK, min(d, 4096)), (QUANT, 8)]
+    return list(dict.fromkeys(lv))
 
 
-def sort_levels(levels, d):
-    """Order a mixed level set by contraction parameter, ascending (stable)."""
-    def alpha(lv):
-        return lv[1] / d if lv[0] == TOPK else quant_alpha(d, lv[1])
-    return sorted(levels, key=alpha)
+def kernel_stress_levels(d: int) -> list:
+    """Mixed level set of the kernel-stress configuration, in the cascade's order at d = 2^20
+    (see federated_levels for other sizes)."""
+    lv = [(QUANT, 2), (TOPK, ratio_K(0.001, d)), (QUANT, 4), (TOPK, ratio_K(0.01, d)), (TOPK, ratio_K(0.1, d)),
+          (QUANT, 8)]
+    return list(dict.fromkeys(lv))
 
 
 def _planted_labels(rng, A, w):
@@ -134,8 +135,7 @@ def federated(seed=5, n=1000, d=65536, N=32, T=200, zeta=1.0, clusters=10) -> Lo
     labels = np.empty(n * N, dtype=np.float32)
     for i in range(n):
         labels[i * N:(i + 1) * N] = _planted_labels(rng, A[i * N:(i + 1) * N], W[i % clusters])
-    lv = [(TOPK, min(d, 16)), (TOPK, min(d, 256)), (TOPK, min(d, 4096)), (QUANT, 4), (QUANT, 8)]
-    lv = sort_levels(list(dict.fromkeys(lv)), d)
+    lv = federated_levels(d)
     return LogisticWorkload("federated", n, d, A, labels, np.arange(n + 1, dtype=np.int64) * N, 0.1, 0.1,
                             lv, [(TOPK, min(d, 4096))], zeta, 0.0, T)
 
@@ -162,8 +162,7 @@ def sparse_features(seed=6, n=200, d=65536, N=1000, per_row=64, T=50, zeta=1.0) 
 
 def kernel_stress(seed=3, n=32, d=1 << 20, T=50, zeta=1.0) -> VectorWorkload:
     """Heavy-tailed difference vectors with a mixed Top-K / b-bit level set."""
-    lv = [(TOPK, ratio_K(r, d)) for r in (0.001, 0.01, 0.1)] + [(QUANT, b) for b in (2, 4, 8)]
-    lv = sort_levels(list(dict.fromkeys(lv)), d)
+    lv = kernel_stress_levels(d)
     return VectorWorkload("kernel_stress", n, d, lv, [(TOPK, ratio_K(0.01, d))], zeta, 0.0, T, seed)
 
 
@@ -181,8 +180,7 @@ def kernel_stress_diffs(wl: VectorWorkload, step: int):
 
 def model_sized(seed=4, n=16, d=11_200_000, T=20, zeta=1.0) -> VectorWorkload:
     """Model-sized gradient vectors; Top-K levels at fractions {1e-4,1e-3,1e-2,5e-2} of d."""
-    lv = [(TOPK, ratio_K(r, d)) for r in (1e-4, 1e-3, 1e-2, 5e-2)]
-    lv = sort_levels(list(dict.fromkeys(lv)), d)
+    lv = list(dict.fromkeys((TOPK, ratio_K(r, d)) for r in (1e-4, 1e-3, 1e-2, 5e-2)))    # ascending K
     return VectorWorkload("model_sized", n, d, lv, [(TOPK, ratio_K(1e-2, d))], zeta, 0.0, T, seed)
 
 

@@ -29,6 +29,12 @@ def bits(a):
     return np.ascontiguousarray(a).view(np.uint32)
 
 
+def by_alpha(levels, d):
+    """A mixed level set in the order of the AdaCGD definition (contraction parameter ascending,
+    stable), with the oracle's contraction parameters."""
+    return sorted(levels, key=lambda lv: O.level_alpha(lv, d))
+
+
 def assert_close_rel(a, b, rtol, what):
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
@@ -170,6 +176,7 @@ def test_difference_mode_with_quantiser_levels_bit_exact(n, d):
     b-bit levels ordered by contraction parameter; every branch of the cascade occurs."""
     E = _eng()
     wk = W.kernel_stress(seed=3, n=n, d=d)
+    wk.worker_levels = by_alpha(wk.worker_levels, d)
     seed = 0x1234ABCD5678
     orc = O.AdaCGDOracle(n=n, d=d, gamma=0.1, worker_levels=wk.worker_levels, zeta_worker=1.0,
                          master_levels=wk.master_levels, zeta_master=0.0, seed=seed)
@@ -252,6 +259,7 @@ def test_trajectory_sparse_logreg():
 
 def test_trajectory_federated_reduced():
     wl = W.federated(n=24, d=8192 + 512, N=32, T=20)
+    wl.worker_levels = by_alpha(wl.worker_levels, wl.d)
     orc, hist, _ = run_trajectory(wl, wl.T, check_every=1, seed=77)
     assert hist.tolist() == orc.level_hist_w.tolist()
 
@@ -853,7 +861,7 @@ def test_checkpoint_and_restore_continue_bit_for_bit(n, d, flags):
     data continues exactly like the uninterrupted run (mixed level set: the Philox counter is part of it)."""
     E = _eng()
     rng = np.random.default_rng(d)
-    wl = W.sort_levels([(O.TOPK, max(1, d // 300)), (O.QUANT, 4), (O.TOPK, max(2, d // 10))], d)
+    wl = by_alpha([(O.TOPK, max(1, d // 300)), (O.QUANT, 4), (O.TOPK, max(2, d // 10))], d)
     if d >= 130 * 8192:
         wl = [(O.TOPK, d // 300), (O.TOPK, d // 10)]              # one-pass sequence
     ml = [(O.TOPK, max(1, d // 50))]
@@ -922,7 +930,7 @@ def test_one_to_five_quantiser_levels_bit_exact(bits_):
     E = _eng()
     n, d = 4, 3 * 8192 + 516
     rng = np.random.default_rng(len(bits_))
-    wl = W.sort_levels([(O.TOPK, 50), (O.TOPK, 3000)] + [(O.QUANT, b) for b in bits_], d)
+    wl = by_alpha([(O.TOPK, 50), (O.TOPK, 3000)] + [(O.QUANT, b) for b in bits_], d)
     grads = [make_vectors(rng, n, d, "heavy") for _ in range(5)]
     for t in range(1, 5):
         grads[t] = (grads[t - 1] + grads[t] * np.float32(10.0 ** rng.uniform(-2, 0))).astype(np.float32)
@@ -948,7 +956,7 @@ def test_two_contexts_interleaved_on_two_streams():
     runs = []
     for n, d, wl, seed in specs:
         rng = np.random.default_rng(seed)
-        wl = W.sort_levels(wl, d)
+        wl = by_alpha(wl, d)
         grads = [make_vectors(rng, n, d, "normal") for _ in range(6)]
         for t in range(1, 6):
             grads[t] = (grads[t - 1] + grads[t] * np.float32(0.3)).astype(np.float32)

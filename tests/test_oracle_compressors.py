@@ -201,3 +201,14 @@ def test_level_order_check():
     lv = [(O.QUANT, 2), (O.TOPK, 1049), (O.QUANT, 4), (O.TOPK, 10486), (O.TOPK, 104858), (O.QUANT, 8)]
     assert O.check_levels(lv, d)
     assert not O.check_levels(lv[::-1], d)
+
+
+def test_configuration_level_sets_are_listed_in_cascade_order():
+    """The input generators list the mixed level sets of the kernel-stress and federated
+    configurations in a fixed order (they hold none of the method's arithmetic): at the
+    configurations' full sizes that order is the one the AdaCGD definition asks for."""
+    from paper_2211_00188_amd import workloads as W
+    for lv, d in ((W.kernel_stress_levels(1 << 20), 1 << 20), (W.federated_levels(65536), 65536)):
+        assert O.check_levels(lv, d), lv
+        al = [O.level_alpha(l, d) for l in lv]
+        assert all(a < b for a, b in zip(al, al[1:]))        # strictly: the order is the only valid one
