@@ -382,12 +382,10 @@ class AdaCGDOracle:
         elif init_mode == INIT_ZERO:
             self.gi = np.zeros((self.n, self.d), dtype=dt)
         elif init_mode == INIT_COMPRESSED:
-            # Eq. (7) from a zero estimator: g~_i^0 = 0 + C_m(grad f_i(x^0) - 0), C_m the last level
+            # g~_i^0 = C_m(grad f_i(x^0)), C_m the last level: the start of CLAG and EF21 (Section 2.3)
             kind, param = self.wl[-1]
             assert kind == TOPK
-            zero = np.zeros(self.d, dtype=dt)
-            self.gi = np.stack([(zero + topk((self.y[i] - zero).astype(dt), param)).astype(dt)
-                                for i in range(self.n)])
+            self.gi = np.stack([topk(self.y[i], param) for i in range(self.n)])
         else:
             raise ValueError(init_mode)
         acc = np.zeros(self.d, dtype=np.float64)

@@ -120,6 +120,8 @@ struct PassArgs {
   uint64_t seed;       // Philox key
   uint32_t step;       // Philox counter word 2
   uint32_t node_flag;  // OR-ed into counter word 1 (0 for workers, 2^31 for the master)
+  int assign;          // 1 = the compressed start g~_i^0 = C_m(grad f_i(x^0)) (Section 2.3): h holds zeros and receives
+                       // the selected values themselves, h[l] = C(v)[l], instead of fl(h[l] + C(v)[l]) (Top-K only)
   // Server work that the one-block kernel for short vectors can take over (each part optional):
   // the block that finishes last adds every node's message to the server vector, g~_new =
   // fl(g~_old + sum / nn); and the iterate update that opens the next step, x_next = fl(x - gamma g),

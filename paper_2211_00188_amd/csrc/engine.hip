@@ -755,8 +755,10 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
   if (cfg->init_mode == ADACGD_INIT_FULLGRAD) INITCHK(launch_copy_f32(c->gi, c->yb[0], nd, c->st));
   else INITCHK(launch_fill_u32((uint32_t*)c->gi, 0u, nd, c->st));
   if (cfg->init_mode == ADACGD_INIT_COMPRESSED) {
-    // g~_i^0 = C_m(grad f_i(x^0)): one application of the compressor with the last level as the only
-    // one, h = 0 and a zero trigger (kept only if the gradient is zero, and then h = 0 is the answer)
+    // g~_i^0 = C_m(grad f_i(x^0)) (the CLAG / EF21 start, Section 2.3): one application of the compressor
+    // with the last level as the only one, h = 0 (so v is the gradient, bit for bit), a zero trigger (h is
+    // kept only if the gradient is zero, and then h = 0 is the answer) and the selected values stored as
+    // they are, so that a selected -0 stays -0
     NodeSet one = c->W;
     const LevelTable& lv = c->W.lv;
     one.lv.m = 1;
@@ -769,6 +771,7 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
     a.y = c->yb[0];
     a.h = c->gi;
     a.seed = c->seed;
+    a.assign = 1;
     const bool timing = c->timing;
     c->timing = false;
     const int rc1 = compress(c, one, a, ADACGD_K_W_SAMPLE, nullptr);

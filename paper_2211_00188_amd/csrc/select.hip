@@ -749,7 +749,6 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
       s = block_sum(s, red);
       if (tid == 0) ns.qerr[node * nq + q] = s;
     }
-    if (tid == 0) ns.qscale[node] = 0.f;
   }
 }
 
@@ -1166,6 +1165,9 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
     ns.sel_slot[node] = slot;
     ns.sel_q[node] = q;
     ns.msg_count[node] = slot >= 0 ? lv.K[slot] : 0u;
+    // (the message tables, this scale among them, are read by the previous step's aggregation: the first
+    // kernel that may write them is this one, which in overlap mode is ordered behind that aggregation)
+    if (lv.nq > 0) ns.qscale[node] = 0.f;       // the apply kernel sets it if the chosen level is a quantiser
     if (slot >= 0) {
       ns.sel_T[node] = ns.prefix[node * p + slot];
       ns.sel_r[node] = ns.rank[node * p + slot];
@@ -1254,7 +1256,7 @@ __global__ __launch_bounds__(kBlock) void k_compact(NodeSet ns, PassArgs a) {
           const uint32_t l = gbase + off;
           midx[pos] = (int32_t)l;
           mval[pos] = val;
-          h[l] = h[l] + val;
+          h[l] = a.assign ? val : h[l] + val;
         }
         eqb += popc64(beq);
         out += popc64(bt);
@@ -1529,7 +1531,7 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
           midx[pos] = i;
           mval[pos] = v;
         }
-        h[i] = h[i] + v;
+        h[i] = a.assign ? v : h[i] + v;
         ++pos;
       }
     }

@@ -454,7 +454,7 @@ def test_long_vectors_one_pass_selection_bit_exact(kind):
     eng.close()
 
 
-@pytest.mark.parametrize("mode", ["grad", "diff"])
+@pytest.mark.parametrize("mode", ["grad", "diff", "diff_quant"])
 def test_overlap_mode_gives_identical_results(mode):
     """Worker compression on the library's own stream, overlapped with the previous step's
     server work: every state vector and message must equal the single-stream run bit for bit,
@@ -464,6 +464,8 @@ def test_overlap_mode_gives_identical_results(mode):
     n, d = 4, 140 * 8192 + 64
     rng = np.random.default_rng(123)
     wl = [(O.TOPK, 100), (O.TOPK, 5000), (O.TOPK, d // 25)]
+    if mode == "diff_quant":       # dense quantised messages: their scales and codes are message tables too
+        wl = by_alpha([(O.TOPK, 100), (O.QUANT, 2), (O.QUANT, 4), (O.TOPK, d // 25), (O.QUANT, 8)], d)
     ml = [(O.TOPK, d // 100)]
     steps = 6
     x0 = _cuda(np.zeros(d, dtype=np.float32))
@@ -497,6 +499,10 @@ def test_overlap_mode_gives_identical_results(mode):
                      eng.state(E.F_MSG_IDX), eng.state(E.F_MSG_VAL), eng.state(E.F_LEVEL_HIST)))
         eng.close()
     assert outs[0][0] == outs[1][0]
+    if mode == "diff_quant":
+        hist = outs[1][7]
+        assert sum(int(hist[j]) for j in range(1, len(wl) + 1) if wl[j - 1][0] == O.QUANT) > 0, hist   # dense messages were aggregated
+        assert sum(int(hist[j]) for j in range(1, len(wl) + 1) if wl[j - 1][0] == O.TOPK) > 0, hist
     for a, b in zip(outs[0][1:], outs[1][1:]):
         assert np.array_equal(np.ascontiguousarray(a).view(np.uint8), np.ascontiguousarray(b).view(np.uint8))
     if mode == "grad":
@@ -779,6 +785,9 @@ def test_compressed_initial_estimators_bit_exact(n, d):
     wl = [(O.TOPK, max(1, d // 200)), (O.TOPK, max(2, d // 20))]
     grads = [make_vectors(rng, n, d, "heavy") for _ in range(4)]
     grads[0][0, : d // 2] = 0.0                        # a gradient with many zeros
+    grads[0][1] = 0.0                                  # fewer non-zeros than K: zeros of both signs are selected,
+    grads[0][1, ::3] = -0.0                            # and g~_i^0 = C(grad) keeps the sign of each
+    grads[0][1, min(5, d - 1)] = 1.0
     if n > 2:
         grads[0][2] = 0.0                              # ... and one that is zero
     for t in range(1, 4):

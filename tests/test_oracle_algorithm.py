@@ -359,20 +359,26 @@ def test_per_level_zeta_is_first_condition_that_holds():
 
 
 def test_compressed_start_is_topk_of_the_first_gradients():
-    """INIT_COMPRESSED: g~_i^0 = C_m(grad f_i(x^0)), here against a sort of (|value|, index) pairs,
-    and the run that follows with zeta = 0 and one level is EF21 from that start."""
+    """INIT_COMPRESSED: g~_i^0 = C_m(grad f_i(x^0)) (the CLAG / EF21 start, Section 2.3), here against a
+    sort of (|value|, index) pairs, compared as bit patterns: a selected coordinate keeps the gradient's
+    value exactly, the sign of a selected zero included.  The run that follows with zeta = 0 and one level
+    is EF21 from that start."""
     rng = np.random.default_rng(21)
     n, d, K = 3, 40, 7
     g0 = rng.standard_normal((n, d)).astype(np.float32)
     g0[0, ::2] = 0.0
     g0[0, 1] = -0.0
+    g0[1, :] = 0.0                   # fewer non-zeros than K: zeros are selected by ascending index ...
+    g0[1, [1, 3]] = -0.0             # ... and these two are among them
+    g0[1, [20, 30, 35]] = (1.5, -2.5, 0.5)
     orc = O.AdaCGDOracle(n=n, d=d, gamma=0.1, worker_levels=[(T, 2), (T, K)], zeta_worker=0.0)
     orc.init(np.zeros(d, dtype=np.float32), g0, O.INIT_COMPRESSED)
     for i in range(n):
         order = sorted(range(d), key=lambda l: (-abs(float(g0[i, l])), l))[:K]
         want = np.zeros(d, dtype=np.float32)
         want[order] = g0[i, order]
-        assert np.array_equal(orc.gi[i], want)              # (-0 == +0 here: the sign of a zero is not fixed)
+        assert np.array_equal(orc.gi[i].view(np.uint32), want.view(np.uint32))
+    assert orc.gi[1].view(np.uint32)[[0, 1, 2, 3]].tolist() == [0, 0x80000000, 0, 0x80000000]
     assert np.allclose(orc.gt, orc.gi.astype(np.float64).mean(0), rtol=1e-7, atol=0)
     h = orc.gi.copy()
     g1 = (g0 + 0.1 * rng.standard_normal((n, d))).astype(np.float32)
@@ -382,7 +388,7 @@ def test_compressed_start_is_topk_of_the_first_gradients():
         order = sorted(range(d), key=lambda l: (-abs(float(v[l])), l))[:K]
         want = h[i].copy()
         want[order] = h[i][order] + v[order]
-        assert np.array_equal(orc.gi[i], want)
+        assert np.array_equal(orc.gi[i].view(np.uint32), want.view(np.uint32))
 
 
 def test_stored_trajectory_is_reproduced():
