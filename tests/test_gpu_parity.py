@@ -3,6 +3,8 @@ on the same seeded inputs.  Compression step: chosen level, selected coordinates
 message values and updated estimators are compared bit for bit; the fp64 reductions
 (||x-h||^2, ||x-y||^2, err_j) to 1e-12 relative (both sides accumulate in fp64 or
 wider, only the summation order differs).  Iterates and gradients: 1e-5 relative."""
+import contextlib
+
 import numpy as np
 import pytest
 
@@ -35,11 +37,21 @@ def by_alpha(levels, d):
     return sorted(levels, key=lambda lv: O.level_alpha(lv, d))
 
 
+ELT_FLOOR_UNITS = 16      # absolute floor of the element-wise check, in units of 2^-24 max|b|
+
+
 def assert_close_rel(a, b, rtol, what):
+    """Max-norm check |a - b|_inf <= rtol |b|_inf, and element by element
+    |a_l - b_l| <= rtol |b_l| + floor with floor = ELT_FLOOR_UNITS 2^-24 |b|_inf: coordinates far below
+    the largest one inherit absolute errors of that size through the coupling of the coordinates
+    (a gradient coordinate depends on every coordinate of the iterate), so a purely relative bound
+    cannot hold for them; the floor is a few units in the last place of the largest element."""
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
     scale = max(np.abs(b).max(), 1e-300)
     assert np.abs(a - b).max() <= rtol * scale, (what, np.abs(a - b).max() / scale)
+    excess = np.abs(a - b) - (rtol * np.abs(b) + ELT_FLOOR_UNITS * 2.0 ** -24 * scale)
+    assert excess.max() <= 0, (what, "element-wise", int(np.argmax(excess)), float(excess.max() / scale))
 
 
 def min_margin(res):
@@ -47,13 +59,38 @@ def min_margin(res):
     return min(ms) if ms else 1.0
 
 
+class NearTie(Exception):
+    """A trigger comparison of this step is within 1e-12 (relative) of equality.  The two sides of the
+    comparison are fp64 sums whose order of summation differs between the oracle and the kernels, so
+    either decision is correct there, and the two runs may continue on different branches."""
+
+
+NEAR_TIE_RUNS = []          # runs whose comparison was cut short at a near tie, over the whole session
+MAX_NEAR_TIE_RUNS = 3       # expected: none
+
+
+@contextlib.contextmanager
+def until_near_tie(tag):
+    """Wraps the comparison loop of one engine / oracle pair.  A near tie ends the comparison of that
+    pair at the step where it occurs (everything before it has been compared); the test is never
+    skipped, and the number of such cuts is bounded over the session."""
+    try:
+        yield
+    except NearTie as e:
+        NEAR_TIE_RUNS.append((tag, str(e)))
+        print("near tie, comparison of this run ends here:", tag, e)
+        assert len(NEAR_TIE_RUNS) <= MAX_NEAR_TIE_RUNS, NEAR_TIE_RUNS
+
+
 def compare_step(eng, orc, res, rm, tag, check_master=True):
-    """Bit-exact comparison of one step's compression outputs."""
+    """Bit-exact comparison of one step's compression outputs.  Raises NearTie (after the reductions
+    have been compared) if a trigger comparison of the step is too close to equality to be decided
+    by sums that differ in their order of summation."""
     E = _eng()
     n = orc.n
     lev = eng.state(E.F_LEVEL)
     S, D, err = eng.state(E.F_SQNORM), eng.state(E.F_D), eng.state(E.F_ERR)
-    near_tie = min_margin(res) < 1e-12
+    near_tie = min_margin(res + ([rm] if (check_master and rm is not None) else [])) < 1e-12
     for i, r in enumerate(res):
         assert abs(S[i] - r.S) <= RED_RTOL * max(r.S, 1e-300), (tag, i, "S")
         assert abs(D[i] - r.D) <= RED_RTOL * max(r.D, 1e-300), (tag, i, "D")
@@ -66,7 +103,7 @@ def compare_step(eng, orc, res, rm, tag, check_master=True):
                 continue
             assert abs(err[i, j] - e) <= RED_RTOL * max(e, r.S * 1e-6, 1e-300), (tag, i, j, "err", err[i, j], e)
     if near_tie:
-        pytest.skip("a trigger comparison is within 1e-12 of equality: either level is correct")
+        raise NearTie(repr(tag))
     assert lev.tolist() == [r.level for r in res], (tag, "levels")
     msgs = eng.messages()
     for i, r in enumerate(res):
@@ -141,13 +178,14 @@ def test_compression_step_bit_exact_external_gradients(n, d, kind, general):
                        init_mode=E.INIT_ZERO if zeta == 0.6 else E.INIT_FULLGRAD, x0=_cuda(x0),
                        grad0=_cuda(grads[0]), flags=E.FLAG_TWO_PASS if general else 0)
         assert np.array_equal(bits(eng.state(E.F_GTILDE)), bits(orc.gt))
-        for t in range(1, steps + 1):
-            res, rm = orc.step(grads=grads[t])
-            eng.step(_cuda(grads[t]))
-            compare_step(eng, orc, res, rm, (n, d, kind, zeta, t))
-            assert np.array_equal(bits(eng.state(E.F_PREV_GRAD)), bits(grads[t]))
-        hist = eng.state(E.F_LEVEL_HIST)
-        assert hist.tolist() == orc.level_hist_w.tolist()
+        with until_near_tie((n, d, kind, zeta)):
+            for t in range(1, steps + 1):
+                res, rm = orc.step(grads=grads[t])
+                eng.step(_cuda(grads[t]))
+                compare_step(eng, orc, res, rm, (n, d, kind, zeta, t))
+                assert np.array_equal(bits(eng.state(E.F_PREV_GRAD)), bits(grads[t]))
+            hist = eng.state(E.F_LEVEL_HIST)
+            assert hist.tolist() == orc.level_hist_w.tolist()
         eng.close()
 
 
@@ -186,19 +224,20 @@ def test_difference_mode_with_quantiser_levels_bit_exact(n, d):
                    master_levels=wk.master_levels, zeta_master=0.0, grad_mode=E.DIFF_EXTERNAL,
                    init_mode=E.INIT_ZERO, x0=_cuda(x0), seed=seed)
     seen = set()
-    for t in range(8):
-        v, D = W.kernel_stress_diffs(wk, t)
-        res, rm = orc.step(diffs=v, D=D)
-        eng.step(_cuda(v), _cuda(D))
-        seen.update(r.level for r in res)
-        compare_step(eng, orc, res, rm, ("diff", n, d, t))
-        for i, r in enumerate(res):
-            if r.dense is not None:
-                codes = eng.state(E.F_QCODES)[i]
-                assert np.array_equal(codes.astype(np.int32), r.codes), ("codes", t, i)
-                assert eng.state(E.F_QSCALE)[i] == np.float32(r.scale)
-    kinds = {wk.worker_levels[j - 1][0] for j in seen if j > 0}
-    assert 0 in seen and kinds == {O.TOPK, O.QUANT}, seen
+    with until_near_tie(("diff", n, d)):
+        for t in range(8):
+            v, D = W.kernel_stress_diffs(wk, t)
+            res, rm = orc.step(diffs=v, D=D)
+            eng.step(_cuda(v), _cuda(D))
+            seen.update(r.level for r in res)
+            compare_step(eng, orc, res, rm, ("diff", n, d, t))
+            for i, r in enumerate(res):
+                if r.dense is not None:
+                    codes = eng.state(E.F_QCODES)[i]
+                    assert np.array_equal(codes.astype(np.int32), r.codes), ("codes", t, i)
+                    assert eng.state(E.F_QSCALE)[i] == np.float32(r.scale)
+        kinds = {wk.worker_levels[j - 1][0] for j in seen if j > 0}
+        assert 0 in seen and kinds == {O.TOPK, O.QUANT}, seen
     eng.close()
 
 
@@ -248,13 +287,47 @@ def test_trajectory_tiny_logistic(zeta):
 
 
 def test_trajectory_sparse_logreg():
+    """The full sparse-logreg configuration (T = 1000, 20000 level decisions): iterate, gradients and g
+    within 1e-5 at every step.  The two sides' gradients agree to about one fp32 unit, not bit for bit
+    (the order of the fp64 summation differs), so a trigger comparison that close to equality may fall
+    either way.  Every decision that differs must be explained that way: the two sides of the
+    comparison, as norms, are 1-Lipschitz in the vectors they are formed from (||v - TopK(v)|| is the
+    distance of v to the K-sparse vectors), so a decision can differ only if the oracle's gap
+    | sqrt(lhs) - sqrt(zeta D) | is at most what the measured difference of the inputs (gradient,
+    previous gradient, estimator) allows, plus the rounding of the two subtractions."""
+    E = _eng()
     wl = W.sparse_logreg()                 # the full configuration: T = 1000
-    orc, hist, _ = run_trajectory(wl, wl.T, check_every=25)
-    # 20000 level decisions on gradients that agree to one fp32 unit, not bit for bit (the summation
-    # order differs): a trigger comparison that close to equality may fall either way, and the iterates
-    # still agree to 1e-5 afterwards (checked above).  Nearly all decisions must coincide.
-    assert np.abs(hist - orc.level_hist_w).sum() <= 6, (hist.tolist(), orc.level_hist_w.tolist())
-    assert (hist > 0).sum() >= 3          # the cascade used several levels
+    orc = _logistic_oracle(wl)
+    eng = _logistic_engine(wl)
+    zeta = float(np.float32(wl.zeta_worker))
+    assert_close_rel(eng.state(E.F_GRAD), orc.y, TRAJ_RTOL, "grad0")
+    nrm = lambda a: float(np.sqrt(np.sum(np.asarray(a, dtype=np.float64) ** 2)))
+    flips = []
+    for t in range(wl.T):
+        y_o, y_e = orc.y.copy(), eng.state(E.F_GRAD)
+        h_o, h_e = orc.gi.copy(), eng.state(E.F_GI)
+        res, rm = orc.step()
+        eng.step()
+        x_e = eng.state(E.F_GRAD)
+        assert_close_rel(eng.state(E.F_X), orc.x, TRAJ_RTOL, ("x", t))
+        assert_close_rel(x_e, orc.y, TRAJ_RTOL, ("grad", t))
+        assert_close_rel(eng.state(E.F_G), orc.g, TRAJ_RTOL, ("g", t))
+        lev = eng.state(E.F_LEVEL)
+        for i, r in enumerate(res):
+            if lev[i] == r.level:
+                continue
+            pos = min(int(lev[i]), r.level)          # cascade position that one side accepted and the other did not
+            lhs = r.S if pos == 0 else r.err[pos - 1]
+            dx, dy, dh = nrm(x_e[i] - orc.y[i]), nrm(y_e[i] - y_o[i]), nrm(h_e[i] - h_o[i])
+            gap = abs(np.sqrt(lhs) - np.sqrt(zeta * r.D))
+            allowed = (dx + dh) + np.sqrt(zeta) * (dx + dy) + 2.0 ** -23 * (np.sqrt(r.S) + np.sqrt(zeta * r.D))
+            assert gap <= allowed, (t, i, int(lev[i]), r.level, gap, allowed)
+            flips.append((t, i, int(lev[i]), r.level, gap / max(np.sqrt(lhs), 1e-300)))
+    hist = eng.state(E.F_LEVEL_HIST).astype(np.int64)
+    eng.close()
+    print("decisions that differ (step, worker, engine level, oracle level, relative gap):", flips)
+    assert len(flips) <= 10, flips            # of 20000; one when first measured
+    assert (hist > 0).sum() >= 3              # the cascade used several levels
 
 
 def test_trajectory_federated_reduced():
@@ -393,8 +466,8 @@ def test_trajectory_with_oracle_gradients_is_bit_exact():
     for t in range(wl.T):
         res, rm = orc.step()
         eng.step(_cuda(orc.y))
-        if min_margin(res + [rm]) < 1e-12:
-            pytest.skip("a trigger comparison is within 1e-12 of equality")
+        # 150 steps x 11 nodes of comparisons on this fixed input: none is within 1e-12 of equality
+        assert min_margin(res + [rm]) >= 1e-12, t
         assert eng.state(E.F_LEVEL).tolist() == [r.level for r in res], t
         assert np.array_equal(bits(eng.state(E.F_X)), bits(orc.x)), t
         assert np.array_equal(bits(eng.state(E.F_G)), bits(orc.g)), t
@@ -442,10 +515,11 @@ def test_long_vectors_one_pass_selection_bit_exact(kind):
     eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zeta, master_levels=ml, zeta_master=0.0,
                    grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=_cuda(grads[0]),
                    flags=E.FLAG_TWO_PASS if kind == "two_pass_flag" else 0)
-    for t in range(1, steps + 1):
-        res, rm = orc.step(grads=grads[t])
-        eng.step(_cuda(grads[t]))
-        compare_step(eng, orc, res, rm, ("long", kind, t))
+    with until_near_tie(("long", kind)):
+        for t in range(1, steps + 1):
+            res, rm = orc.step(grads=grads[t])
+            eng.step(_cuda(grads[t]))
+            compare_step(eng, orc, res, rm, ("long", kind, t))
     repairs = eng.state(E.F_REPAIRS)
     if kind == "adversarial":
         assert repairs[0] > 0                    # the second scan did run
@@ -529,17 +603,20 @@ def _run_external(n, d, wl, zw, ml, zm, steps, seed, tag):
     eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zw, master_levels=ml, zeta_master=zm,
                    grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=_cuda(grads[0]))
     mlev = []
-    for t in range(1, steps + 1):
+    with until_near_tie(tag):
+        for t in range(1, steps + 1):
+            res, rm = orc.step(grads=grads[t])
+            if rm is not None:
+                mlev.append(rm.level)
+            eng.step(_cuda(grads[t]))
+            compare_step(eng, orc, res, rm, (tag, t))
+        hist_w = eng.state(E.F_LEVEL_HIST)
+        assert hist_w.tolist() == orc.level_hist_w.tolist()
+    eng.close()
+    for t in range(orc.t + 1, steps + 1):        # (a run cut short at a near tie: the oracle finishes alone)
         res, rm = orc.step(grads=grads[t])
-        eng.step(_cuda(grads[t]))
-        if rm is not None and rm.margins and min(rm.margins) < 1e-12:
-            pytest.skip("a master trigger comparison is within 1e-12 of equality")
-        compare_step(eng, orc, res, rm, (tag, t))
         if rm is not None:
             mlev.append(rm.level)
-    hist_w = eng.state(E.F_LEVEL_HIST)
-    assert hist_w.tolist() == orc.level_hist_w.tolist()
-    eng.close()
     return orc, mlev
 
 
@@ -679,13 +756,14 @@ def test_general_triggers_bit_exact(n, d, quant):
         orc.init(x0, grads[0], O.INIT_ZERO)
         eng = E.AdaCGD(grad_mode=E.GRAD_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), grad0=_cuda(grads[0]),
                        flags=E.FLAG_ANY_LEVEL_ORDER, **kw)
-        for t in range(1, steps + 1):
-            res, rm = orc.step(grads=grads[t])
-            eng.step(_cuda(grads[t]))
-            compare_step(eng, orc, res, rm, (n, d, trial, t))
-            seen.update(r.level for r in res)
-        assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
-        assert eng.state(E.F_M_LEVEL_HIST).tolist() == orc.level_hist_m.tolist()
+        with until_near_tie((n, d, trial)):
+            for t in range(1, steps + 1):
+                res, rm = orc.step(grads=grads[t])
+                eng.step(_cuda(grads[t]))
+                compare_step(eng, orc, res, rm, (n, d, trial, t))
+                seen.update(r.level for r in res)
+            assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+            assert eng.state(E.F_M_LEVEL_HIST).tolist() == orc.level_hist_m.tolist()
         eng.close()
     assert len(seen) >= 3, seen
 
@@ -801,11 +879,12 @@ def test_compressed_initial_estimators_bit_exact(n, d):
     assert np.array_equal(bits(eng.state(E.F_GTILDE)), bits(orc.gt))
     assert np.array_equal(bits(eng.state(E.F_G)), bits(orc.g))
     assert eng.state(E.F_LEVEL_HIST).sum() == 0 and eng.state(E.F_MSG_COUNT).sum() == 0
-    for t in range(1, 4):
-        res, rm = orc.step(grads=grads[t])
-        eng.step(_cuda(grads[t]))
-        compare_step(eng, orc, res, rm, (n, d, t))
-    assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+    with until_near_tie(("compressed start", n, d)):
+        for t in range(1, 4):
+            res, rm = orc.step(grads=grads[t])
+            eng.step(_cuda(grads[t]))
+            compare_step(eng, orc, res, rm, (n, d, t))
+        assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
     eng.close()
 
 
@@ -853,14 +932,15 @@ def test_overlap_mode_short_vectors(n, master):
     arrs = [_cuda(g) for g in grads]
     eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0, master_levels=ml, zeta_master=0.5,
                    grad_mode=E.GRAD_EXTERNAL, x0=_cuda(x0), grad0=arrs[0], flags=E.FLAG_OVERLAP | E.FLAG_RETAIN_EXT)
-    for t in range(1, 9):
-        res, rm = orc.step(grads=grads[t])
-        eng.step(arrs[t])
-        if t % 3 == 0 or t == 8:
-            if rm is not None and rm.margins and min(rm.margins) < 1e-12:
-                pytest.skip("a master trigger comparison is within 1e-12 of equality")
-            compare_step(eng, orc, res, rm, (n, master, t))
-    assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+    with until_near_tie(("overlap, short", n, master)):
+        for t in range(1, 9):
+            res, rm = orc.step(grads=grads[t])
+            eng.step(arrs[t])
+            if min_margin(res + ([rm] if rm is not None else [])) < 1e-12:
+                raise NearTie(repr((n, master, t)))      # also at the steps that are not compared
+            if t % 3 == 0 or t == 8:
+                compare_step(eng, orc, res, rm, (n, master, t))
+        assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
     eng.close()
 
 
@@ -949,10 +1029,11 @@ def test_one_to_five_quantiser_levels_bit_exact(bits_):
     orc = O.AdaCGDOracle(**kw)
     orc.init(x0, grads[0], O.INIT_ZERO)
     eng = E.AdaCGD(grad_mode=E.GRAD_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), grad0=_cuda(grads[0]), **kw)
-    for t in range(1, 5):
-        res, rm = orc.step(grads=grads[t])
-        eng.step(_cuda(grads[t]))
-        compare_step(eng, orc, res, rm, (bits_, t))       # includes the realised error of every quantiser level
+    with until_near_tie(("quantiser levels", bits_)):
+        for t in range(1, 5):
+            res, rm = orc.step(grads=grads[t])
+            eng.step(_cuda(grads[t]))
+            compare_step(eng, orc, res, rm, (bits_, t))       # includes the realised error of every quantiser level
     eng.close()
 
 
@@ -983,12 +1064,13 @@ def test_two_contexts_interleaved_on_two_streams():
         for eng, orc, grads, arrs in runs:
             eng.step(arrs[t])
     for eng, orc, grads, arrs in runs:
-        for t in range(1, 6):
-            res, rm = orc.step(grads=grads[t])
-        if min_margin(res + [rm]) < 1e-12:
-            pytest.skip("a trigger comparison is within 1e-12 of equality")
-        compare_step(eng, orc, res, rm, ("interleaved", orc.d))
-        assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+        with until_near_tie(("interleaved", orc.d)):
+            for t in range(1, 6):
+                res, rm = orc.step(grads=grads[t])
+                if min_margin(res + [rm]) < 1e-12:
+                    raise NearTie(repr(("interleaved", orc.d, t)))
+            compare_step(eng, orc, res, rm, ("interleaved", orc.d))
+            assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
         eng.close()
 
 

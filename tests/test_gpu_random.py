@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import adacgd_oracle as O
-from test_gpu_parity import _cuda, _eng, compare_step, make_vectors
+from test_gpu_parity import NearTie, _cuda, _eng, compare_step, make_vectors
 
 pytestmark = pytest.mark.gpu
 
@@ -69,11 +69,9 @@ def test_random_configurations_bit_exact(seed):
                 else:
                     res, rm = orc.step(grads=grads[t])
                     eng.step(_cuda(grads[t]))
-                if rm is not None and rm.margins and min(rm.margins) < 1e-12:
-                    raise pytest.skip.Exception("a master trigger comparison is within 1e-12 of equality")
                 compare_step(eng, orc, res, rm, tag + (t,))
-        except pytest.skip.Exception:
-            near_ties += 1          # either decision is correct there: the case is left out, not the test
+        except NearTie:
+            near_ties += 1          # either decision is correct there: the rest of the case is left out, not the test
         finally:
             eng.close()
     assert near_ties <= 5
