@@ -160,6 +160,24 @@ int adacgd_workspace_bytes(const adacgd_config* cfg, int64_t* bytes);
  * g^0 = g~^0, and y_i = grad f_i(x^0).  On success *out is a new context. */
 int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out);
 
+/* adacgd_init for callers that cannot allocate device memory or have none to pass: code that runs
+ * where hipMalloc is not allowed (under HIP graph capture, in tight serving loops, in harnesses that
+ * forbid it).  The workspace is a static device array inside the library, ADACGD_STATIC_WORKSPACE_BYTES
+ * long, that every device the library is used on holds until the process ends; the context object lives
+ * in static host memory.  This call allocates nothing, on the device or on the host, and creates no
+ * stream or event.  cfg->workspace and cfg->workspace_bytes are ignored; everything else is as in
+ * adacgd_init, with these limits:
+ *  - grad_mode is GRAD_EXTERNAL or DIFF_EXTERNAL, and neither FLAG_OVERLAP nor FLAG_KERNEL_TIMING is
+ *    set (ADACGD_ERR_STATE otherwise);
+ *  - adacgd_workspace_bytes(cfg) <= ADACGD_STATIC_WORKSPACE_BYTES, else ADACGD_ERR_ALLOC with a message
+ *    that gives both numbers (about 26 bytes per worker-coordinate: n d up to about 2.5 million);
+ *  - one such context per device at a time: a second call on the current device before the first
+ *    context is destroyed returns ADACGD_ERR_STATE (all of them would share the one array).
+ * The array keeps what the previous context left in it; this call clears what has to start at zero.
+ * The context is used and destroyed like any other (adacgd_step, adacgd_state, adacgd_destroy). */
+#define ADACGD_STATIC_WORKSPACE_BYTES (64ll << 20)
+int adacgd_init_static(const adacgd_config* cfg, adacgd_ctx** out);
+
 /* Runs nsteps iterations of Algorithm 2 (all of: iterate update, local gradients,
  * worker compression with level choice, server aggregation, master compression).
  *   LOGISTIC, LOGISTIC_CSR   ext = ext_D = NULL.

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -84,18 +85,19 @@ int build_levels(const adacgd_level* in, int m, float zeta, const adacgd_trigger
       return ADACGD_ERR_LEVELS;
     }
   }
-  // distinct Top-K sizes ascending -> slots
-  std::vector<uint32_t> ks;
+  // distinct Top-K sizes ascending -> slots (no heap memory: this also runs for adacgd_init_static)
+  uint32_t ks[kMaxLevels];
+  int nk = 0;
   for (int j = 0; j < m; ++j)
-    if (in[j].kind == ADACGD_TOPK) ks.push_back((uint32_t)in[j].param);
-  std::sort(ks.begin(), ks.end());
-  ks.erase(std::unique(ks.begin(), ks.end()), ks.end());
-  lt->p = (int)ks.size();
+    if (in[j].kind == ADACGD_TOPK) ks[nk++] = (uint32_t)in[j].param;
+  std::sort(ks, ks + nk);
+  nk = (int)(std::unique(ks, ks + nk) - ks);
+  lt->p = nk;
   for (int s = 0; s < lt->p; ++s) lt->K[s] = ks[s];
   for (int j = 0; j < m; ++j) {
     lt->kind[j] = in[j].kind == ADACGD_TOPK ? kTopK : kQuant;
     if (in[j].kind == ADACGD_TOPK) {
-      lt->ref[j] = (int)(std::lower_bound(ks.begin(), ks.end(), (uint32_t)in[j].param) - ks.begin());
+      lt->ref[j] = (int)(std::lower_bound(ks, ks + nk, (uint32_t)in[j].param) - ks);
     } else {
       const int b = (int)in[j].param;
       int q = -1;
@@ -257,6 +259,7 @@ struct adacgd_ctx {
   std::vector<hipEvent_t> pool;
   double ms_sum[ADACGD_NUM_KERNELS];
   double ms_cnt[ADACGD_NUM_KERNELS];
+  int static_dev = -1;   // >= 0: made by adacgd_init_static on this device (context and workspace are the library's)
 
   const float* g() const { return has_master ? g_own : gt[cur]; }
   const float* ycurp() const { return y_ext ? y_ext : yb[ycur]; }
@@ -609,7 +612,44 @@ void comm_of(const NodeSet& ns, const unsigned long long* hist, uint64_t copies,
   }
 }
 
+// ---------------------------------------------------------------------------
+// adacgd_init_static: workspace and context in memory the library owns from load time.
+// `scratch` is the device array; in host code its name is only a handle for
+// hipGetSymbolAddress, never a device address.  Each device has its own copy at its own
+// address, resolved once per device (with that device current) and kept in its slot; all
+// host code below uses slot.ptr.  (The compiler gives the device-side symbol of a static variable
+// global binding because host code names it; the runtime finds it by that name.  A `used`
+// attribute would keep the symbol local, and the lookup would then fail.)
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[ADACGD_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+struct StaticSlot {
+  void* ptr = nullptr;      // device address of `scratch` on this device
+  bool in_use = false;      // a context made by adacgd_init_static is alive on this device
+  alignas(adacgd_ctx) unsigned char ctx_mem[sizeof(adacgd_ctx)];
+};
+StaticSlot g_slots[kMaxDevices];
+std::mutex g_slots_mu;
+
+// Ends a context: the heap object of adacgd_init, or the one in the static slot of adacgd_init_static
+// (`free_slot`: also hand the device's static workspace back; a failing adacgd_init_static does that itself).
+void release_ctx(adacgd_ctx* c, bool free_slot) {
+  if (c->static_dev >= 0) {
+    StaticSlot& sl = g_slots[c->static_dev];
+    c->~adacgd_ctx();
+    if (free_slot) {
+      std::lock_guard<std::mutex> lk(g_slots_mu);
+      sl.in_use = false;
+    }
+  } else {
+    delete c;
+  }
+}
+
 }  // namespace
+
+static int init_impl(const adacgd_config* cfg, adacgd_ctx** out, int static_dev);
 
 extern "C" {
 
@@ -629,7 +669,55 @@ int adacgd_workspace_bytes(const adacgd_config* cfg, int64_t* bytes) {
   return ADACGD_OK;
 }
 
-int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
+int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) { return init_impl(cfg, out, -1); }
+
+int adacgd_init_static(const adacgd_config* cfg, adacgd_ctx** out) {
+  if (!cfg) { set_err(g_err, "config is null"); return ADACGD_ERR_ARG; }
+  if (!out) { set_err(g_err, "out is null"); return ADACGD_ERR_ARG; }
+  *out = nullptr;
+  if (cfg->grad_mode != ADACGD_GRAD_EXTERNAL && cfg->grad_mode != ADACGD_DIFF_EXTERNAL) {
+    set_err(g_err, "adacgd_init_static takes GRAD_EXTERNAL or DIFF_EXTERNAL only (the logistic modes build host tables)");
+    return ADACGD_ERR_STATE;
+  }
+  if (cfg->flags & (ADACGD_FLAG_OVERLAP | ADACGD_FLAG_KERNEL_TIMING)) {
+    set_err(g_err, "adacgd_init_static does not take FLAG_OVERLAP or FLAG_KERNEL_TIMING (they create a stream and events)");
+    return ADACGD_ERR_STATE;
+  }
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { set_err(g_err, "hipGetDevice failed: %s", hipGetErrorString(e)); return ADACGD_ERR_DEVICE; }
+  if (dev < 0 || dev >= kMaxDevices) { set_err(g_err, "device index %d out of range", dev); return ADACGD_ERR_DEVICE; }
+  {
+    std::lock_guard<std::mutex> lk(g_slots_mu);
+    StaticSlot& sl = g_slots[dev];
+    if (sl.in_use) {
+      set_err(g_err, "device %d: the static workspace is in use by another context (destroy it first)", dev);
+      return ADACGD_ERR_STATE;
+    }
+    if (!sl.ptr) {        // once per device, with that device current
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p) {
+        set_err(g_err, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+        return ADACGD_ERR_DEVICE;
+      }
+      sl.ptr = p;
+    }
+    sl.in_use = true;
+  }
+  const int rc = init_impl(cfg, out, dev);
+  if (rc != ADACGD_OK) {
+    std::lock_guard<std::mutex> lk(g_slots_mu);
+    g_slots[dev].in_use = false;
+  }
+  return rc;
+}
+
+}  // extern "C"
+
+// Input line of Algorithm 1.  static_dev < 0: the caller's workspace and a heap context; otherwise the
+// static workspace and context slot of that device (no memory is allocated on either side).
+static int init_impl(const adacgd_config* cfg, adacgd_ctx** out, int static_dev) {
   LevelTable wl, ml;
   int rc = validate(cfg, &wl, &ml, g_err);
   if (rc) return rc;
@@ -648,15 +736,18 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
     set_err(g_err, "grad0 is required in GRAD_EXTERNAL mode");
     return ADACGD_ERR_ARG;
   }
-  if (!cfg->workspace || (reinterpret_cast<uintptr_t>(cfg->workspace) & 255u)) {
+  void* const workspace = static_dev >= 0 ? g_slots[static_dev].ptr : cfg->workspace;
+  const int64_t workspace_bytes = static_dev >= 0 ? (int64_t)ADACGD_STATIC_WORKSPACE_BYTES : cfg->workspace_bytes;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) {
     set_err(g_err, "workspace is null or not 256-byte aligned");
     return ADACGD_ERR_ALLOC;
   }
-  adacgd_ctx* c = new (std::nothrow) adacgd_ctx();
+  adacgd_ctx* c = static_dev >= 0 ? new (g_slots[static_dev].ctx_mem) adacgd_ctx() : new (std::nothrow) adacgd_ctx();
   if (!c) { set_err(g_err, "out of host memory"); return ADACGD_ERR_ALLOC; }
+  c->static_dev = static_dev;
   c->n = cfg->n; c->d = cfg->d; c->grad_mode = cfg->grad_mode; c->flags = cfg->flags;
   c->gamma = (double)cfg->gamma; c->seed = cfg->seed; c->st = (hipStream_t)cfg->stream;
-  c->ws_base = (char*)cfg->workspace;
+  c->ws_base = (char*)workspace;
   c->has_master = cfg->m_master > 0;
   c->timing = (cfg->flags & ADACGD_FLAG_KERNEL_TIMING) != 0;
   c->step = 0; c->cur = 0; c->ycur = 0; c->y_ext = nullptr; c->err[0] = 0;
@@ -670,9 +761,13 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
   shape_logistic(cfg, c->ld);
   Layout L{};
   const size_t need = carve_all(c->ws_base, cfg, c->W, c->M, c->ld, L);
-  if ((int64_t)need > cfg->workspace_bytes) {
-    set_err(g_err, "workspace too small: need %zu bytes, got %lld", need, (long long)cfg->workspace_bytes);
-    delete c;
+  if ((int64_t)need > workspace_bytes) {
+    if (static_dev >= 0)
+      set_err(g_err, "configuration needs %zu bytes of workspace, the static workspace holds %lld: use adacgd_init",
+              need, (long long)workspace_bytes);
+    else
+      set_err(g_err, "workspace too small: need %zu bytes, got %lld", need, (long long)workspace_bytes);
+    release_ctx(c, false);
     return ADACGD_ERR_ALLOC;
   }
   c->x = L.x; c->x_next = L.x_next; c->x_next_valid = false; c->g_own = L.g_own; c->gt[0] = L.gt0; c->gt[1] = L.gt1; c->gi = L.gi;
@@ -684,7 +779,7 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
     c->ld.cv = L.cv; c->ld.tval = L.tval;
   }
 
-  auto fail = [&](int code) { std::memcpy(g_err, c->err, sizeof(g_err)); delete c; return code; };
+  auto fail = [&](int code) { std::memcpy(g_err, c->err, sizeof(g_err)); release_ctx(c, false); return code; };
 #define INITCHK(call)                                                                       \
   do {                                                                                      \
     hipError_t e_ = (call);                                                                 \
@@ -802,6 +897,8 @@ int adacgd_init(const adacgd_config* cfg, adacgd_ctx** out) {
   *out = c;
   return ADACGD_OK;
 }
+
+extern "C" {
 
 int adacgd_step(adacgd_ctx* c, const float* ext, const double* ext_D, int32_t nsteps) {
   if (!c) return ADACGD_ERR_ARG;
@@ -1037,7 +1134,7 @@ int adacgd_destroy(adacgd_ctx* c) {
   hipError_t e = hipStreamSynchronize(c->st);
   for (auto& s : c->spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
   for (auto ev : c->pool) (void)hipEventDestroy(ev);
-  delete c;
+  release_ctx(c, true);
   return e == hipSuccess ? ADACGD_OK : ADACGD_ERR_DEVICE;
 }
 

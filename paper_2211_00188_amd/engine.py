@@ -30,7 +30,7 @@ KERNELS = ["xupdate", "grad_margin", "grad_cols", "aggregate",
            "w_sample", "w_scan", "w_filter", "w_gather", "w_select", "w_tally", "w_compact", "w_qapply",
            "m_sample", "m_scan", "m_filter", "m_gather", "m_select", "m_tally", "m_compact", "m_qapply"]
 
-EXPORTS = ["adacgd_workspace_bytes", "adacgd_init", "adacgd_step", "adacgd_state", "adacgd_set_state",
+EXPORTS = ["adacgd_workspace_bytes", "adacgd_init", "adacgd_init_static", "adacgd_step", "adacgd_state", "adacgd_set_state",
            "adacgd_destroy", "adacgd_last_error"]
 
 
@@ -81,6 +81,8 @@ def load_library():
         lib.adacgd_workspace_bytes.restype = C.c_int
         lib.adacgd_init.argtypes = [C.POINTER(Config), C.POINTER(C.c_void_p)]
         lib.adacgd_init.restype = C.c_int
+        lib.adacgd_init_static.argtypes = [C.POINTER(Config), C.POINTER(C.c_void_p)]
+        lib.adacgd_init_static.restype = C.c_int
         lib.adacgd_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
         lib.adacgd_step.restype = C.c_int
         lib.adacgd_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_int32]
@@ -172,6 +174,18 @@ def adacgd_init(cfg: Config) -> C.c_void_p:
     return ctx
 
 
+STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def adacgd_init_static(cfg: Config) -> C.c_void_p:
+    lib = load_library()
+    ctx = C.c_void_p(None)
+    rc = lib.adacgd_init_static(C.byref(cfg), C.byref(ctx))
+    if rc:
+        raise AdaCGDError(rc, lib.adacgd_last_error(None).decode())
+    return ctx
+
+
 def adacgd_step(ctx, ext=None, ext_D=None, nsteps=1):
     lib = load_library()
     rc = lib.adacgd_step(ctx, _ptr(ext), _ptr(ext_D), int(nsteps))
@@ -208,7 +222,8 @@ class AdaCGD:
     """Convenience owner of one context: allocates the workspace with torch, keeps the
     borrowed tensors alive, and shapes the outputs of adacgd_state."""
 
-    def __init__(self, **kw):
+    def __init__(self, static_workspace=False, **kw):
+        """static_workspace: adacgd_init_static instead of adacgd_init (no workspace tensor is made)."""
         import torch
         self.torch = torch
         if not torch.cuda.is_available():
@@ -219,11 +234,16 @@ class AdaCGD:
         self.master_levels = list(kw.get("master_levels", ()))
         self.grad_mode = kw.get("grad_mode", GRAD_EXTERNAL)
         self.cfg, self._keep = make_config(**kw)
-        nbytes = adacgd_workspace_bytes(self.cfg)
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-        self.cfg.workspace = C.c_void_p(self.workspace.data_ptr())
-        self.cfg.workspace_bytes = nbytes
-        self.ctx = adacgd_init(self.cfg)
+        self.ctx = None
+        if static_workspace:
+            self.workspace = None
+            self.ctx = adacgd_init_static(self.cfg)
+        else:
+            nbytes = adacgd_workspace_bytes(self.cfg)
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            self.cfg.workspace = C.c_void_p(self.workspace.data_ptr())
+            self.cfg.workspace_bytes = nbytes
+            self.ctx = adacgd_init(self.cfg)
         self._ext_keep = None
 
     def step(self, ext=None, ext_D=None, nsteps=1):
