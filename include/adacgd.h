@@ -228,6 +228,9 @@ enum adacgd_field {
   ADACGD_F_REPAIRS = 28,     /* uint64 [2]     node-steps (workers, master) on which the sampled candidate cut
                                 of the one-pass selection was too high and the vector was scanned a
                                 second time; a diagnostic: the results do not depend on it           */
+  ADACGD_F_CANDIDATES = 30,  /* uint64 [2]     coordinates (workers, master) that the last step's one-pass scan kept as
+                                candidates for the largest Top-K size, summed over the nodes (0 where the
+                                one-pass sequence is not in use); a diagnostic of the sampled cut         */
   ADACGD_F_ESTIMATOR_ERR = 29  /* double [1]   G = (1/n) sum_i ||grad f_i(x^t) - g~_i^t||^2 after the last step, the
                                 quantity whose contraction drives the convergence proofs (from the
                                 realised errors of the chosen levels; needs at least one step)  */

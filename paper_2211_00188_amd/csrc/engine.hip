@@ -1018,6 +1018,20 @@ int adacgd_state(adacgd_ctx* c, int32_t field, void* dst, int64_t dst_bytes, int
       HIPCHK(c, hipStreamSynchronize(c->st));
       return host_out(o, 16);
     }
+    case ADACGD_F_CANDIDATES: {
+      uint64_t o[2] = {0, 0};
+      const NodeSet* sets[2] = {&W, hm ? &M : nullptr};
+      for (int k = 0; k < 2; ++k) {
+        const NodeSet* ns = sets[k];
+        if (!ns || !ns->onepass || c->step == 0) continue;
+        std::vector<uint32_t> part((size_t)ns->nn * ns->G);
+        HIPCHK(c, hipMemcpyAsync(part.data(), ns->partU, part.size() * 4, hipMemcpyDeviceToHost, c->st));
+        HIPCHK(c, hipStreamSynchronize(c->st));
+        for (int i = 0; i < ns->nn; ++i)
+          for (int b = 0; b < ns->G; ++b) o[k] += part[(size_t)i * ns->G + b];
+      }
+      return host_out(o, 16);
+    }
     case ADACGD_F_ESTIMATOR_ERR: {
       if (c->step == 0) { set_err(c->err, "no step has run yet"); return ADACGD_ERR_STATE; }
       const int m = W.lv.m;

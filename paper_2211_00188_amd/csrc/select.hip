@@ -317,10 +317,10 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
 // sample: one block per node histograms (top 13 key bits) a sample of R = min(tiles, 256)
 // rows of 256 consecutive coordinates, one row from each of R evenly spaced tiles (row = hash
 // of the tile index), each row read by one wavefront as a single 16-byte load per lane.
-// Result: the candidate cut = lowest key of the bin that holds the sample's rank
-// ceil(m K/d) + 6 sqrt(m K/d) + 8 from the top, K the largest Top-K size and m the sample
-// size, so that with overwhelming probability at least K coordinates of the full vector have
-// keys >= cut.  scanx counts them and the repair passes cover a miss.
+// Result: the candidate cut = the key at the sample's rank ceil(m K/d) + 6 sqrt(m K/d) + 8 from
+// the top (interpolated inside the histogram bin that holds that rank), K the largest Top-K size
+// and m the sample size, so that with overwhelming probability at least K coordinates of the
+// full vector have keys >= cut.  scanx counts them and the repair passes cover a miss.
 // ---------------------------------------------------------------------------
 constexpr int kSampleShift = 18, kSampleBins = 8192, kSampleBlock = 1024, kSampleRows = 256;
 __device__ __forceinline__ int sample_row(int t) { return (int)(((uint32_t)t * 2654435761u) >> 27); }
@@ -398,11 +398,20 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample(NodeSet ns, PassArgs a)
   for (int i = 0; i < w; ++i) cum += wsum16[i];
 #pragma unroll
   for (int q = 0; q < PER; ++q) {
-    if (loc[q] && cum < rank && rank <= cum + loc[q]) res[0] = (uint32_t)(top - q);
+    if (loc[q] && cum < rank && rank <= cum + loc[q]) {
+      // The rank falls inside this bin, `need` of its `loc` samples from the top.  The cut is placed
+      // at that fraction of the bin's key range (samples taken as evenly spread inside one bin, whose
+      // width is 3 % of the value), rounded down.  It only has to be good, not safe: scanx counts the
+      // candidates and the repair pass covers a cut that turns out too high.
+      const uint32_t need = rank - cum;
+      const uint32_t span = 1u << kSampleShift;
+      const uint32_t down = (uint32_t)(((uint64_t)span * need) / loc[q]);       // <= span
+      res[0] = (((uint32_t)(top - q) + 1u) << kSampleShift) - down;
+    }
     cum += loc[q];
   }
   __syncthreads();
-  if (tid == 0) ns.best[node] = res[0] << kSampleShift;     // lowest key of that bin
+  if (tid == 0) ns.best[node] = res[0];
 }
 
 // ---------------------------------------------------------------------------
@@ -1665,7 +1674,8 @@ hipError_t launch_sample(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
 
 hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, bool repair, hipStream_t st) {
   (void)hipGetLastError();
-  const dim3 grid(ns.G, ns.nn), block(kBlock);
+  // the repair pass almost never has work: a quarter of the blocks keeps its idle launch short
+  const dim3 grid(repair ? (ns.G + 3) / 4 : ns.G, ns.nn), block(kBlock);
   if (repair) {
     if (a.diff) hipLaunchKernelGGL((k_scanx<true, true>), grid, block, 0, st, ns, a);
     else hipLaunchKernelGGL((k_scanx<false, true>), grid, block, 0, st, ns, a);

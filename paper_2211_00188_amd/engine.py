@@ -24,7 +24,8 @@ MAX_LEVELS = 16
 
 (F_X, F_G, F_GTILDE, F_GTILDE_PREV, F_GI, F_PREV_GRAD, F_LEVEL, F_SQNORM, F_D, F_ERR, F_MSG_COUNT, F_MSG_IDX,
  F_MSG_VAL, F_M_LEVEL, F_M_SQNORM, F_M_D, F_M_ERR, F_M_MSG_COUNT, F_M_MSG_IDX, F_M_MSG_VAL, F_STEP, F_LEVEL_HIST,
- F_M_LEVEL_HIST, F_COMM, F_QCODES, F_QSCALE, F_KERNEL_MS, F_GRAD, F_REPAIRS, F_ESTIMATOR_ERR) = range(30)
+ F_M_LEVEL_HIST, F_COMM, F_QCODES, F_QSCALE, F_KERNEL_MS, F_GRAD, F_REPAIRS, F_ESTIMATOR_ERR,
+ F_CANDIDATES) = range(31)
 
 KERNELS = ["xupdate", "grad_margin", "grad_cols", "aggregate",
            "w_sample", "w_scan", "w_filter", "w_gather", "w_select", "w_tally", "w_compact", "w_qapply",
@@ -298,7 +299,7 @@ class AdaCGD:
             return self._get(field, (4,), u64)
         if field == F_ESTIMATOR_ERR:
             return self._get(field, (1,), f64)
-        if field == F_REPAIRS:
+        if field in (F_REPAIRS, F_CANDIDATES):
             return self._get(field, (2,), u64)
         if field == F_QCODES:
             return self._get(field, (n, d), np.int16)
