@@ -359,13 +359,16 @@ class AdaCGDOracle:
         self.shards = shards            # list of (A_i, labels_i) or None
         self.lam = float(np.float64(self.dt.type(lam)))
         self.t = 0
+        # how the independent per-worker compressions of a step are evaluated: the built-in map, or for
+        # instance a thread pool's map at large sizes (the results do not depend on it)
+        self.worker_map = map
         self.level_hist_w = np.zeros(len(self.wl) + 1, dtype=np.int64)
         self.level_hist_m = np.zeros(len(self.ml) + 1, dtype=np.int64)
         self.last = None
 
     # -- gradients ---------------------------------------------------------
     def local_grads(self, x):
-        return np.stack([logistic_grad(A, yl, x, self.lam, self.dt) for A, yl in self.shards])
+        return np.stack(list(self.worker_map(lambda sh: logistic_grad(sh[0], sh[1], x, self.lam, self.dt), self.shards)))
 
     # -- input line of Algorithm 1 ----------------------------------------
     def init(self, x0, grads0=None, init_mode=INIT_FULLGRAD):
@@ -407,16 +410,17 @@ class AdaCGDOracle:
             if grads is None:
                 grads = self.local_grads(self.x)
             grads = np.asarray(grads, dtype=dt)
-        res = []
-        acc = np.zeros(d, dtype=np.float64)
-        for i in range(n):
+        # "for all devices in parallel" (Algorithm 1): the n compressions are independent of each other
+        def one(i):
             if diffs is not None:
-                r = adacgd_compress(self.gi[i], None, None, self.wl, self.zw, seed=self.seed, node=i, step=self.t,
-                                    D_given=D[i], v_given=diffs[i], triggers=self.tw)
-            else:
-                r = adacgd_compress(self.gi[i], self.y[i], grads[i], self.wl, self.zw, seed=self.seed, node=i,
-                                    step=self.t, triggers=self.tw)
-            res.append(r)
+                return adacgd_compress(self.gi[i], None, None, self.wl, self.zw, seed=self.seed, node=i, step=self.t,
+                                       D_given=D[i], v_given=diffs[i], triggers=self.tw)
+            return adacgd_compress(self.gi[i], self.y[i], grads[i], self.wl, self.zw, seed=self.seed, node=i,
+                                   step=self.t, triggers=self.tw)
+        res = list(self.worker_map(one, range(n)))
+        acc = np.zeros(d, dtype=np.float64)
+        for i in range(n):                        # messages are added in ascending worker index
+            r = res[i]
             self.gi[i] = r.h_new
             if r.level > 0:
                 if r.dense is not None:

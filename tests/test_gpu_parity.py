@@ -367,71 +367,6 @@ def test_communication_counters():
     eng.close()
 
 
-def test_model_sized_full_dimension_sampled_workers():
-    """d = 11.2 M, n = 16, the launch configuration the benchmark times.  The oracle
-    checks a sample of workers coordinate by coordinate (each worker's step depends only
-    on its own inputs); the server aggregate is checked through the identity
-    g~_new = fl(g~_old + (sum of messages)/n) on the engine's own messages."""
-    E = _eng()
-    import torch
-    wk = W.model_sized()
-    n, d = wk.n, wk.d
-    gen = W.ModelSizedGrads(wk)
-    g0 = gen.next().copy()
-    g1 = gen.next().copy()
-    x0 = np.zeros(d, dtype=np.float32)
-    for init_mode, zeta, sample in ((E.INIT_ZERO, 11.9, (0, 7)), (E.INIT_FULLGRAD, 0.5, (15,))):
-        eng = E.AdaCGD(n=n, d=d, gamma=0.1, worker_levels=wk.worker_levels, zeta_worker=zeta,
-                       master_levels=wk.master_levels, zeta_master=0.0, grad_mode=E.GRAD_EXTERNAL,
-                       init_mode=init_mode, x0=_cuda(x0), grad0=_cuda(g0), flags=E.FLAG_RETAIN_EXT)
-        gt_old = eng.state(E.F_GTILDE)
-        d1 = _cuda(g1)
-        eng.step(d1)
-        lev = eng.state(E.F_LEVEL)
-        msgs = eng.messages()
-        gi = eng.state(E.F_GI)
-        S, D, err = eng.state(E.F_SQNORM), eng.state(E.F_D), eng.state(E.F_ERR)
-        for i in sample:
-            h = np.zeros(d, dtype=np.float32) if init_mode == E.INIT_ZERO else g0[i]
-            r = O.adacgd_compress(h, g0[i], g1[i], wk.worker_levels, zeta)
-            assert min(r.margins) > 1e-12
-            assert lev[i] == r.level
-            assert abs(S[i] - r.S) <= RED_RTOL * r.S and abs(D[i] - r.D) <= RED_RTOL * r.D
-            if r.level == 0:
-                assert np.isnan(err[i]).all()
-            else:
-                for j, e in enumerate(r.err):
-                    assert abs(err[i, j] - e) <= RED_RTOL * e
-            assert np.array_equal(msgs[i][0], r.msg_idx)
-            assert np.array_equal(bits(msgs[i][1]), bits(r.msg_val))
-            assert np.array_equal(bits(gi[i]), bits(r.h_new))
-        # properties that hold for every worker
-        for i in range(n):
-            idx, val = msgs[i]
-            K = 0 if lev[i] == 0 else wk.worker_levels[lev[i] - 1][1]
-            assert len(idx) == K and np.all(np.diff(idx) > 0)
-            v = g1[i] - (0 if init_mode == E.INIT_ZERO else g0[i])
-            assert np.array_equal(bits(val), bits(v[idx].astype(np.float32)))
-            if K:
-                rest = np.abs(v)
-                thr = np.abs(val).min()
-                rest[idx] = 0
-                assert rest.max() <= thr
-        acc = np.zeros(d, dtype=np.float64)
-        for i in range(n):
-            acc[msgs[i][0]] += msgs[i][1].astype(np.float64)
-        expect = (gt_old.astype(np.float64) + acc / n).astype(np.float32)
-        assert np.array_equal(bits(eng.state(E.F_GTILDE)), bits(expect))
-        # master: one worker-style step on (g, g~_old, g~_new)
-        rm = O.adacgd_compress(gt_old, gt_old, expect, wk.master_levels, 0.0)
-        assert int(eng.state(E.F_M_LEVEL)[0]) == rm.level
-        assert np.array_equal(eng.state(E.F_M_MSG_IDX), rm.msg_idx)
-        assert np.array_equal(bits(eng.state(E.F_G)), bits(rm.h_new))
-        eng.close()
-        del eng, d1
-        torch.cuda.empty_cache()
-
-
 @pytest.mark.parametrize("n,d,N", [(4, 100, 64), (3, 101, 50), (5, 8192 + 12, 7), (2, 300, 2500)])
 def test_gradient_kernel_matches_oracle(n, d, N):
     """grad f_i(x) of the logistic objective with the nonconvex regulariser at several
@@ -1072,89 +1007,3 @@ def test_two_contexts_interleaved_on_two_streams():
             compare_step(eng, orc, res, rm, ("interleaved", orc.d))
             assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
         eng.close()
-
-
-def test_kernel_stress_full_size_sampled_workers():
-    """The kernel-stress configuration at full size (n = 32, d = 2^20, Top-K and 2/4/8-bit levels, difference
-    mode) for two steps, in the launch configuration the benchmark's secondary run uses: the oracle checks
-    a sample of workers coordinate by coordinate, quantiser codes and scale included; level counts and
-    message sizes are checked for every worker."""
-    E = _eng()
-    wk = W.kernel_stress()
-    n, d = wk.n, wk.d
-    x0 = np.zeros(d, dtype=np.float32)
-    eng = E.AdaCGD(n=n, d=d, gamma=0.1, worker_levels=wk.worker_levels, zeta_worker=wk.zeta_worker,
-                   master_levels=wk.master_levels, zeta_master=0.0, grad_mode=E.DIFF_EXTERNAL,
-                   init_mode=E.INIT_ZERO, x0=_cuda(x0), seed=wk.seed)
-    h = {i: np.zeros(d, dtype=np.float32) for i in (0, 13, 31)}
-    kinds = set()
-    for t in range(2):
-        v, D = W.kernel_stress_diffs(wk, t)
-        eng.step(_cuda(v), _cuda(D))
-        lev = eng.state(E.F_LEVEL)
-        gi = eng.state(E.F_GI)
-        msgs = eng.messages()
-        S, err = eng.state(E.F_SQNORM), eng.state(E.F_ERR)
-        codes, scale = eng.state(E.F_QCODES), eng.state(E.F_QSCALE)
-        for i in h:
-            r = O.adacgd_compress(h[i], None, None, wk.worker_levels, wk.zeta_worker, seed=wk.seed, node=i, step=t,
-                                  D_given=D[i], v_given=v[i])
-            if min(r.margins) < 1e-12:
-                pytest.skip("a trigger comparison is within 1e-12 of equality")
-            assert lev[i] == r.level, (t, i)
-            assert abs(S[i] - r.S) <= RED_RTOL * r.S
-            if r.level > 0:
-                for j, e in enumerate(r.err):
-                    assert abs(err[i, j] - e) <= RED_RTOL * max(e, r.S * 1e-6), (t, i, j)
-                kinds.add(wk.worker_levels[r.level - 1][0])
-            assert np.array_equal(msgs[i][0], r.msg_idx) and np.array_equal(bits(msgs[i][1]), bits(r.msg_val))
-            assert np.array_equal(bits(gi[i]), bits(r.h_new)), (t, i)
-            if r.codes is not None:
-                assert np.array_equal(codes[i].astype(np.int32), r.codes) and scale[i] == np.float32(r.scale)
-            h[i] = r.h_new
-        for i in range(n):
-            want = 0 if lev[i] == 0 or wk.worker_levels[lev[i] - 1][0] != O.TOPK else wk.worker_levels[lev[i] - 1][1]
-            assert len(msgs[i][0]) == want and np.all(np.diff(msgs[i][0]) > 0)
-    assert kinds, "no sampled worker sent anything"
-    eng.close()
-
-
-def test_federated_full_size_sampled_workers():
-    """The federated configuration at full size (n = 1000 workers, d = 65536, 32 dense samples each, 8.4 GB of
-    features; Top-K and 4/8-bit levels, Top-K master) for two steps.  For a sample of workers the
-    gradient kernel is compared with the oracle's gradient at the engine's iterate (1e-5 relative), and
-    the compression step with the oracle's on the engine's own gradients (bit for bit)."""
-    E = _eng()
-    import torch
-    wl = W.federated()
-    n, d = wl.n, wl.d
-    A, labels = torch.from_numpy(wl.A).cuda(), torch.from_numpy(wl.labels).cuda()
-    eng = E.AdaCGD(n=n, d=d, gamma=wl.gamma, lam=wl.lam, worker_levels=wl.worker_levels, zeta_worker=wl.zeta_worker,
-                   master_levels=wl.master_levels, zeta_master=wl.zeta_master, grad_mode=E.GRAD_LOGISTIC, A=A,
-                   labels=labels, shard_offsets=wl.shard_offsets, x0=_cuda(np.zeros(d, dtype=np.float32)), seed=5)
-    sample = (0, 499, 999)
-    off = wl.shard_offsets
-    lam = np.float64(np.float32(wl.lam))
-    prev_grad = eng.state(E.F_GRAD)
-    prev_gi = eng.state(E.F_GI)
-    for t in range(2):
-        eng.step()
-        x = eng.state(E.F_X)
-        grad = eng.state(E.F_GRAD)
-        gi = eng.state(E.F_GI)
-        lev = eng.state(E.F_LEVEL)
-        msgs = eng.messages()
-        for i in sample:
-            ref = O.logistic_grad(wl.A[off[i]:off[i + 1]], wl.labels[off[i]:off[i + 1]], x, lam, np.float32)
-            assert_close_rel(grad[i], ref, TRAJ_RTOL, ("grad", t, i))
-            r = O.adacgd_compress(prev_gi[i], prev_grad[i], grad[i], wl.worker_levels, wl.zeta_worker, seed=5, node=i, step=t)
-            if min(r.margins) < 1e-12:
-                pytest.skip("a trigger comparison is within 1e-12 of equality")
-            assert lev[i] == r.level, (t, i)
-            assert np.array_equal(msgs[i][0], r.msg_idx) and np.array_equal(bits(msgs[i][1]), bits(r.msg_val))
-            assert np.array_equal(bits(gi[i]), bits(r.h_new)), (t, i)
-        prev_grad, prev_gi = grad, gi
-    assert eng.state(E.F_LEVEL_HIST).sum() == 2 * n
-    eng.close()
-    del A, labels, eng
-    torch.cuda.empty_cache()
