@@ -29,7 +29,10 @@ are pinned only through those special cases and per-step invariants.
 The b-bit quantiser is not defined by the paper: its definition here is a
 reading (scaled stochastic uniform dithering with max-norm scale); it is
 pinned against its own closed-form conditional expectation and the contractive
-inequality of Definition 1, not against a paper value.
+inequality of Definition 1, not against a paper value.  The block-wise variant
+(one max-norm scale per block of B consecutive coordinates) is the same quantiser
+applied to every block on its own; it is pinned against the plain one (block by
+block, and B = d), the same closed form summed over the blocks, and Definition 1.
 """
 from __future__ import annotations
 
@@ -40,6 +43,7 @@ import numpy as np
 
 TOPK = 0
 QUANT = 1
+QUANT_BLOCK = 2      # level = (QUANT_BLOCK, (b, B)): b bits, one scale per block of B consecutive coordinates
 
 INIT_FULLGRAD = 0
 INIT_ZERO = 1
@@ -195,12 +199,72 @@ def quant_expected_sqerr(v: np.ndarray, b: int) -> float:
     return float(np.sum(delta * delta * p * (1 - p)) / (1 + w) ** 2 + (w / (1 + w)) ** 2 * np.sum(v * v))
 
 
+def quantize_block(v: np.ndarray, b: int, B: int, u: np.ndarray):
+    """Block-wise C_b: the vector is cut into blocks of B consecutive coordinates (the last one may be
+    shorter) and every block k is quantised on its own with the scale a_k = max |v| over the block:
+         r = (|v| / a_k) * s,  xi = floor(r) + [u < r - floor(r)],  C(v) = sign(v) * fl(xi * c_k),
+         c_k = fl(a_k / (s (1 + omega_B))),   omega_B = min(B / (4 s^2), sqrt(B) / s)
+    i.e. the quantiser above with the block length in place of d (also for a shorter last block: omega
+    grows with the length, so the nominal B keeps the block contractive).  A block of zeros gives zeros.
+    Every block is then contractive in expectation with alpha_B = 1 / (1 + omega_B), and so is the whole.
+    The dither u_l is the one of coordinate l (not restarted per block).
+    Returns (C(v), signed codes xi as int32, scales c_k as an array of ceil(d / B) values)."""
+    dt = v.dtype.type
+    d = v.shape[0]
+    s = 2 ** (b - 1) - 1
+    nb = (d + B - 1) // B
+    out = np.zeros_like(v)
+    codes = np.zeros(d, dtype=np.int32)
+    scales = np.zeros(nb, dtype=v.dtype)
+    denom = s * (1.0 + quant_omega(B, b))
+    for k in range(nb):
+        lo, hi = k * B, min(d, (k + 1) * B)
+        vb = v[lo:hi]
+        av = np.abs(vb)
+        a = av.max()
+        if not (a > 0):
+            continue
+        r = (av / a) * dt(s)
+        fl = np.floor(r)
+        xi = fl + (u[lo:hi].astype(v.dtype) < (r - fl))
+        c = dt(float(a) / denom)
+        out[lo:hi] = np.copysign((xi.astype(v.dtype) * c).astype(v.dtype), vb)
+        codes[lo:hi] = np.where(np.signbit(vb), -xi, xi).astype(np.int32)
+        scales[k] = c
+    return out, codes, scales
+
+
+def quant_block_expected_sqerr(v: np.ndarray, b: int, B: int) -> float:
+    """E ||C(v) - v||^2 of the block-wise quantiser over the dither: the closed form of the plain
+    quantiser (with omega_B) summed over the blocks."""
+    v = np.asarray(v, dtype=np.float64)
+    d = v.shape[0]
+    s = 2 ** (b - 1) - 1
+    w = quant_omega(B, b)
+    total = 0.0
+    for lo in range(0, d, B):
+        vb = v[lo:lo + B]
+        a = np.abs(vb).max()
+        if a == 0:
+            continue
+        r = np.abs(vb) / a * s
+        p = r - np.floor(r)
+        delta = a / s
+        total += float(np.sum(delta * delta * p * (1 - p)) / (1 + w) ** 2 + (w / (1 + w)) ** 2 * np.sum(vb * vb))
+    return total
+
+
 # --------------------------------------------------------------------------
 # level sets
 # --------------------------------------------------------------------------
 def level_alpha(level, d: int) -> float:
     kind, param = level
-    return param / d if kind == TOPK else quant_alpha(d, param)
+    if kind == TOPK:
+        return param / d
+    if kind == QUANT:
+        return quant_alpha(d, param)
+    b, B = param
+    return quant_alpha(B, b)          # every block is contractive with the parameter of a length-B vector
 
 
 def check_levels(levels, d: int):
@@ -224,6 +288,7 @@ class CompressResult:
     dense: np.ndarray | None   # C_b(v) when a quantiser level is applied
     codes: np.ndarray | None = None
     scale: float = 0.0
+    scales: np.ndarray | None = None   # block-wise quantiser level: one scale per block
     margins: list = field(default_factory=list)   # |lhs - tau| / max(tau, tiny) of every comparison made
 
 
@@ -271,7 +336,10 @@ def adacgd_compress(h, y, x, levels, zeta, *, seed=0, node=0, step=0, D_given=No
         else:
             if u is None:
                 u = dither_uniforms(d, seed, node, step)
-            c, codes, scale = quantize(v, param, u)
+            if kind == QUANT:
+                c, codes, scale = quantize(v, param, u)
+            else:
+                c, codes, scale = quantize_block(v, param[0], param[1], u)      # scale: one per block
             cands.append(("quant", c, codes, scale))
         err.append(sum_sq_diff(v, c))
 
@@ -308,7 +376,9 @@ def adacgd_compress(h, y, x, levels, zeta, *, seed=0, node=0, step=0, D_given=No
         return CompressResult(level, S, D, err, h_new, idx.astype(np.int32), v[idx].copy(), None, margins=margins)
     c = cand[1]
     h_new = (h + c).astype(dt)
-    return CompressResult(level, S, D, err, h_new, empty_i, empty_v, c, codes=cand[2], scale=float(cand[3]),
+    blockwise = np.ndim(cand[3]) > 0
+    return CompressResult(level, S, D, err, h_new, empty_i, empty_v, c, codes=cand[2],
+                          scale=0.0 if blockwise else float(cand[3]), scales=cand[3] if blockwise else None,
                           margins=margins)
 
 
@@ -451,7 +521,7 @@ class AdaCGDOracle:
     @staticmethod
     def message_bits(level, levels, d):
         """Bits of one message: level id + payload.  Top-K: K (value, index)
-        pairs; b-bit: d codes plus one float scale; skip: the id only."""
+        pairs; b-bit: d codes plus one float scale (block-wise: one per block); skip: the id only."""
         m = len(levels)
         idb = max(1, math.ceil(math.log2(m + 1)))
         if level == 0:
@@ -459,7 +529,10 @@ class AdaCGDOracle:
         kind, param = levels[level - 1]
         if kind == TOPK:
             return idb + param * (32 + max(1, math.ceil(math.log2(d))))
-        return idb + d * param + 32
+        if kind == QUANT:
+            return idb + d * param + 32
+        b, B = param
+        return idb + d * b + 32 * ((d + B - 1) // B)      # one float scale per block
 
     @staticmethod
     def message_values(level, levels, d):

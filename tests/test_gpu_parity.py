@@ -1007,3 +1007,46 @@ def test_two_contexts_interleaved_on_two_streams():
             compare_step(eng, orc, res, rm, ("interleaved", orc.d))
             assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
         eng.close()
+
+
+@pytest.mark.parametrize("dense", [False, True])
+def test_aggregation_with_wide_exponent_spread(dense):
+    """Messages that put values more than 2^30 apart in magnitude on the same coordinate (per-worker scales
+    from 1e-12 to 1e+12).  The oracle adds the messages of a coordinate in ascending worker index in fp64;
+    the aggregation kernels add them in another order, which can differ in the last place of the fp64 sum
+    once the exponents spread over more than 53 - 24 bits.  The aggregate is that sum divided by n, added to
+    the old value and rounded to fp32, 29 bits coarser: the results must still agree bit for bit, for Top-K
+    messages (every coordinate sent) and for dense quantised ones."""
+    E = _eng()
+    n, d = 12, 3 * 8192 + 516
+    rng = np.random.default_rng(2030)
+    scales = (10.0 ** rng.permutation(np.linspace(-12, 12, n))).astype(np.float32)
+    wl = [(O.QUANT, 8)] if dense else [(O.TOPK, d)]
+    steps = 4
+    x0 = np.zeros(d, dtype=np.float32)
+    if dense:
+        orc = O.AdaCGDOracle(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=0.0, master_levels=[], seed=17)
+        orc.init(x0, None, O.INIT_ZERO)
+        eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=0.0, master_levels=[],
+                       grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), seed=17)
+    else:
+        g0 = np.zeros((n, d), dtype=np.float32)
+        orc = O.AdaCGDOracle(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=0.0, master_levels=[])
+        orc.init(x0, g0, O.INIT_ZERO)
+        eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=0.0, master_levels=[],
+                       grad_mode=E.GRAD_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), grad0=_cuda(g0))
+    with until_near_tie(("wide spread", dense)):
+        for t in range(1, steps + 1):
+            v = (rng.standard_normal((n, d)) * scales[:, None]).astype(np.float32)
+            if dense:
+                D = np.ones(n)
+                res, rm = orc.step(diffs=v, D=D)
+                eng.step(_cuda(v), _cuda(D))
+            else:
+                res, rm = orc.step(grads=v)
+                eng.step(_cuda(v))
+            assert all(r.level == 1 for r in res)
+            compare_step(eng, orc, res, rm, ("wide spread", dense, t), check_master=False)
+    lo, hi = np.abs(orc.gt[orc.gt != 0]).min(), np.abs(orc.gt).max()
+    assert hi > 1e9                                   # the large workers dominate the aggregate
+    eng.close()

@@ -212,3 +212,99 @@ def test_configuration_level_sets_are_listed_in_cascade_order():
         assert O.check_levels(lv, d), lv
         al = [O.level_alpha(l, d) for l in lv]
         assert all(a < b for a, b in zip(al, al[1:]))        # strictly: the order is the only valid one
+
+
+# ---------------------------------------------------------------- block-wise quantiser
+@pytest.mark.parametrize("d,B,b", [(256, 256, 4), (1000, 64, 4), (3 * 256 + 70, 256, 8), (130, 128, 2), (2048, 2048, 3)])
+def test_block_quantizer_is_the_plain_quantizer_block_by_block(d, B, b):
+    """Every full block equals the plain quantiser of a length-B vector holding that block (values, codes
+    and scale bit for bit, with the dither of the block's own coordinates); B = d is the plain quantiser;
+    a shorter last block uses the nominal block length in omega."""
+    rng = np.random.default_rng(d + B + b)
+    v = (rng.standard_t(3, size=d) * np.exp(rng.standard_normal(d) * 0.3)).astype(np.float32)
+    u = O.dither_uniforms(d, 99, 5, 7)
+    c, codes, scales = O.quantize_block(v, b, B, u)
+    s = 2 ** (b - 1) - 1
+    nb = (d + B - 1) // B
+    assert scales.shape == (nb,)
+    for k in range(nb):
+        lo, hi = k * B, min(d, (k + 1) * B)
+        if hi - lo == B:
+            cp, codesp, scalep = O.quantize(v[lo:hi].copy(), b, u[lo:hi])
+            assert np.array_equal(cp.view(np.uint32), c[lo:hi].view(np.uint32))
+            assert np.array_equal(codesp, codes[lo:hi])
+            assert np.float32(scalep) == scales[k]
+        else:                               # ragged tail: the scale by hand
+            a = float(np.abs(v[lo:hi]).max())
+            want = np.float32(a / (s * (1.0 + min(B / (4.0 * s * s), math.sqrt(B) / s))))
+            assert scales[k] == want
+            l = lo + int(np.argmax(np.abs(v[lo:hi])))
+            assert abs(codes[l]) == s and c[l] == np.copysign(np.float32(s) * want, v[l])
+    if B == d:
+        cp, codesp, scalep = O.quantize(v, b, u)
+        assert np.array_equal(cp.view(np.uint32), c.view(np.uint32)) and np.array_equal(codesp, codes)
+    assert np.all(np.abs(codes) <= s)
+
+
+def test_block_quantizer_zero_block_and_independence_of_blocks():
+    rng = np.random.default_rng(3)
+    d, B, b = 4 * 64, 64, 4
+    v = rng.standard_normal(d).astype(np.float32)
+    v[64:128] = 0.0
+    u = O.dither_uniforms(d, 1, 0, 0)
+    c, codes, scales = O.quantize_block(v, b, B, u)
+    assert not c[64:128].any() and not codes[64:128].any() and scales[1] == 0
+    w = v.copy()
+    w[128:192] *= np.float32(1000.0)        # another block changes: this one's output does not
+    c2, codes2, scales2 = O.quantize_block(w, b, B, u)
+    for sl in (slice(0, 64), slice(192, 256)):
+        assert np.array_equal(c[sl].view(np.uint32), c2[sl].view(np.uint32)) and np.array_equal(codes[sl], codes2[sl])
+    assert scales2[2] == np.float32(float(np.abs(w[128:192]).max()) / (7 * (1.0 + O.quant_omega(B, b))))
+
+
+def test_block_quantizer_unbiased_after_rescaling_and_contractive_in_expectation():
+    rng = np.random.default_rng(10)
+    d, B, b = 200, 64, 4
+    v = (rng.standard_normal(d) * np.repeat([1.0, 30.0, 0.01, 5.0], 50)).astype(np.float32)   # scales differ per block
+    w = O.quant_omega(B, b)
+    trials = 4000
+    acc = np.zeros(d)
+    sq = 0.0
+    for t in range(trials):
+        c, _, _ = O.quantize_block(v, b, B, O.dither_uniforms(d, 78, 2, t))
+        acc += c.astype(np.float64)
+        sq += O.sum_sq_diff(v, c)
+    mean = acc / trials * (1 + w)
+    s = 2 ** (b - 1) - 1
+    for lo in range(0, d, B):
+        delta = np.abs(v[lo:lo + B]).max() / s
+        assert np.all(np.abs(mean[lo:lo + B] - v[lo:lo + B]) < 5 * (delta / 2) / math.sqrt(trials) + 1e-6 * delta)
+    expected = O.quant_block_expected_sqerr(v, b, B)
+    assert abs(sq / trials - expected) < 0.05 * expected
+    # Definition 1 with alpha_B = 1 / (1 + omega_B): block by block, hence in total
+    for lo in range(0, d, B):
+        vb = v[lo:lo + B]
+        assert O.quant_block_expected_sqerr(vb, b, B) <= (1 - O.quant_alpha(B, b)) * O.sum_squares(vb) * (1 + 1e-9)
+    assert expected <= (1 - O.level_alpha((O.QUANT_BLOCK, (b, B)), d)) * O.sum_squares(v) * (1 + 1e-9)
+    # the blocks' own scales make it far more accurate here than one scale for the whole vector
+    assert expected < 0.5 * O.quant_expected_sqerr(v, b)
+
+
+def test_block_quantizer_level_in_the_cascade_and_its_message_cost():
+    rng = np.random.default_rng(12)
+    d, B, b = 300, 128, 4
+    h = rng.standard_normal(d).astype(np.float32)
+    x = (h + rng.standard_normal(d) * 0.5).astype(np.float32)
+    y = (x + rng.standard_normal(d) * 0.1).astype(np.float32)
+    levels = [(O.TOPK, 3), (O.QUANT_BLOCK, (b, B)), (O.TOPK, d)]
+    assert O.check_levels(levels, d)
+    r = O.adacgd_compress(h, y, x, levels, 0.0, seed=5, node=2, step=9)
+    assert r.level == 3                                     # zeta = 0: the last level
+    r = O.adacgd_compress(h, y, x, levels[:2], 0.0, seed=5, node=2, step=9)
+    assert r.level == 2 and r.scales is not None and r.scales.shape == (3,) and r.codes is not None
+    v = (x - h).astype(np.float32)
+    c, codes, scales = O.quantize_block(v, b, B, O.dither_uniforms(d, 5, 2, 9))
+    assert np.array_equal(r.h_new.view(np.uint32), (h + c).astype(np.float32).view(np.uint32))
+    assert abs(r.err[1] - O.sum_sq_diff(v, c)) <= 1e-15 * r.err[1]
+    assert O.AdaCGDOracle.message_bits(2, levels[:2], d) == 2 + d * b + 32 * 3
+    assert O.AdaCGDOracle.message_values(2, levels[:2], d) == d
