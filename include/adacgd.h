@@ -54,11 +54,18 @@ enum adacgd_status {
 /* One compression level.  The AdaCGD definition orders levels from strongest to
  * weakest compression, alpha_1 <= ... <= alpha_m.  alpha = K/d for Top-K;
  * alpha = 1/(1+omega), omega = min(d/(4 s^2), sqrt(d)/s), s = 2^(b-1)-1 for b bits. */
-enum adacgd_level_kind { ADACGD_TOPK = 0, ADACGD_QUANT = 1 };
+enum adacgd_level_kind {
+  ADACGD_TOPK = 0,
+  ADACGD_QUANT = 1,      /* b-bit stochastic quantiser, one max-norm scale for the whole vector          */
+  ADACGD_QUANT_BLOCK = 2 /* the same quantiser applied to every block of B consecutive coordinates on its
+                            own (one max-norm scale per block; the last block may be shorter); omega, and
+                            with it alpha = 1/(1+omega), are those of a length-B vector; the message is the
+                            d codes plus one float per block                                              */
+};
 typedef struct {
   int32_t kind;  /* adacgd_level_kind                                   */
-  int32_t pad;   /* set to 0                                            */
-  int64_t param; /* TOPK: K in [1,d] (K = d is the identity); QUANT: b in [2,16] */
+  int32_t block; /* QUANT_BLOCK: block length B, a power of two in [64, 2048]; otherwise 0 */
+  int64_t param; /* TOPK: K in [1,d] (K = d is the identity); QUANT, QUANT_BLOCK: b in [2,16] */
 } adacgd_level;
 
 #define ADACGD_MAX_LEVELS 16
@@ -228,6 +235,10 @@ enum adacgd_field {
   ADACGD_F_REPAIRS = 28,     /* uint64 [2]     node-steps (workers, master) on which the sampled candidate cut
                                 of the one-pass selection was too high and the vector was scanned a
                                 second time; a diagnostic: the results do not depend on it           */
+  ADACGD_F_QBSCALE = 31,     /* float  [n x ceil(d/64)] scales of the last block-wise quantised message of each worker:
+                                entry k of a row is the scale of block k (the first ceil(d/B) entries; the rest
+                                and the rows of workers that chose another level are unspecified); only kept
+                                when the worker level set holds a block-wise quantiser                        */
   ADACGD_F_CANDIDATES = 30,  /* uint64 [2]     coordinates (workers, master) that the last step's one-pass scan kept as
                                 candidates for the largest Top-K size, summed over the nodes (0 where the
                                 one-pass sequence is not in use); a diagnostic of the sampled cut         */

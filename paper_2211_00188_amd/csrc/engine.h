@@ -22,6 +22,8 @@ constexpr int kBins2 = 512;
 constexpr int kMaxLevels = 16;
 constexpr int kSmallMax = 4096;         // largest d handled by the one-block-per-node kernel
 constexpr int kSmallServeMax = 64;      // ... which also aggregates when there are at most this many workers
+constexpr int kSeg = 64;                // block-wise quantiser scales are built from maxima over segments of 64 coordinates
+constexpr int kSegPerGroup = kWaveTile / kSeg;   // 32
 
 enum { kTopK = 0, kQuant = 1 };
 
@@ -34,8 +36,11 @@ struct LevelTable {
   uint32_t K[kMaxLevels];     // ascending
   int nq;                     // quantiser levels
   int qbits[kMaxLevels];
+  int qblock[kMaxLevels];     // 0: one scale for the whole vector; else block length B (a power of two, 64..2048):
+                              // one scale per block of B consecutive coordinates
+  int nqb;                    // how many of the nq quantisers are block-wise
   float qs[kMaxLevels];       // s = 2^(b-1) - 1 magnitude levels
-  double qdenom[kMaxLevels];  // s (1 + omega)
+  double qdenom[kMaxLevels];  // s (1 + omega), omega from d (whole vector) or from B (block-wise)
   // Trigger of cascade position j (0 = keep h, j = level j; the last level has none):
   //   err_j <= tz[j] ||x-y||^2 + te[j] ||x-h||^2,  err_0 = ||x-h||^2.  fp32 arguments widened.
   double tz[kMaxLevels];
@@ -71,6 +76,10 @@ struct NodeSet {
   uint32_t* done;       // [nn][kArriveFan+1]     arrival counters of the last-block epilogues
   uint32_t* partU;      // [nn][G]                per block: largest key (two-pass scan) or candidates found (fused scan)
   uint32_t* amax;       // [nn]                   max magnitude key of the last scan (quantiser scale a)
+  uint32_t* segmax;     // [nn][nseg]             max magnitude key of every 64-coordinate segment (only with block-wise
+                        //                        quantiser levels): a block's scale is the max over its segments
+  float* qbscale;       // [nn][nseg]             scales c_k of the last block-wise quantised message, entry k = block k
+  int nseg;             // ceil(d / 64)
   double* partS;        // [nn][G]
   double* partD;        // [nn][G]
   double* partEb;       // [nn][G]

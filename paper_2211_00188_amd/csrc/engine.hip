@@ -42,11 +42,15 @@ struct Carver {
   }
 };
 
+// omega of the b-bit quantiser on a vector (or block) of `len` coordinates
+double quant_omega(int b, double len) {
+  const double s = (double)((1 << (b - 1)) - 1);
+  return std::fmin(len / (4.0 * s * s), std::sqrt(len) / s);
+}
+
 double level_alpha(const adacgd_level& lv, int64_t d) {
   if (lv.kind == ADACGD_TOPK) return (double)lv.param / (double)d;
-  const double s = (double)((1 << (lv.param - 1)) - 1);
-  const double w = std::fmin((double)d / (4.0 * s * s), std::sqrt((double)d) / s);
-  return 1.0 / (1.0 + w);
+  return 1.0 / (1.0 + quant_omega((int)lv.param, lv.kind == ADACGD_QUANT_BLOCK ? (double)lv.block : (double)d));
 }
 
 int build_levels(const adacgd_level* in, int m, float zeta, const adacgd_trigger* trig, int64_t d, uint32_t flags,
@@ -71,9 +75,14 @@ int build_levels(const adacgd_level* in, int m, float zeta, const adacgd_trigger
         set_err(err, "level %d: Top-K needs 1 <= K <= d, got %lld", j + 1, (long long)in[j].param);
         return ADACGD_ERR_ARG;
       }
-    } else if (in[j].kind == ADACGD_QUANT) {
+    } else if (in[j].kind == ADACGD_QUANT || in[j].kind == ADACGD_QUANT_BLOCK) {
       if (in[j].param < 2 || in[j].param > 16) {
         set_err(err, "level %d: quantiser needs 2 <= b <= 16, got %lld", j + 1, (long long)in[j].param);
+        return ADACGD_ERR_ARG;
+      }
+      const int B = in[j].block;
+      if (in[j].kind == ADACGD_QUANT_BLOCK && (B < kSeg || B > kWaveTile || (B & (B - 1)) != 0)) {
+        set_err(err, "level %d: block length must be a power of two in [64, 2048], got %d", j + 1, B);
         return ADACGD_ERR_ARG;
       }
     } else {
@@ -95,21 +104,23 @@ int build_levels(const adacgd_level* in, int m, float zeta, const adacgd_trigger
   lt->p = nk;
   for (int s = 0; s < lt->p; ++s) lt->K[s] = ks[s];
   for (int j = 0; j < m; ++j) {
-    lt->kind[j] = in[j].kind == ADACGD_TOPK ? kTopK : kQuant;
+    lt->kind[j] = in[j].kind == ADACGD_TOPK ? kTopK : kQuant;      // (block-wise or not is a property of the quantiser entry)
     if (in[j].kind == ADACGD_TOPK) {
       lt->ref[j] = (int)(std::lower_bound(ks, ks + nk, (uint32_t)in[j].param) - ks);
     } else {
       const int b = (int)in[j].param;
+      const int B = in[j].kind == ADACGD_QUANT_BLOCK ? in[j].block : 0;
       int q = -1;
       for (int i = 0; i < lt->nq; ++i)
-        if (lt->qbits[i] == b) q = i;
+        if (lt->qbits[i] == b && lt->qblock[i] == B) q = i;
       if (q < 0) {
         q = lt->nq++;
         const double s = (double)((1 << (b - 1)) - 1);
-        const double w = std::fmin((double)d / (4.0 * s * s), std::sqrt((double)d) / s);
         lt->qbits[q] = b;
+        lt->qblock[q] = B;
+        lt->nqb += B ? 1 : 0;
         lt->qs[q] = (float)s;
-        lt->qdenom[q] = s * (1.0 + w);
+        lt->qdenom[q] = s * (1.0 + quant_omega(b, B ? (double)B : (double)d));
       }
       lt->ref[j] = q;
     }
@@ -168,6 +179,9 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.msg_val = c.take<float>(nn * (size_t)ns.Kcap);
   ns.qcodes = nq ? c.take<int16_t>(nn * (size_t)ns.d) : nullptr;
   ns.qscale = c.take<float>(nn);
+  ns.nseg = (int)((ns.d + kSeg - 1) / kSeg);
+  ns.segmax = ns.lv.nqb ? c.take<uint32_t>(nn * (size_t)ns.nseg) : nullptr;
+  ns.qbscale = ns.lv.nqb ? c.take<float>(nn * (size_t)ns.nseg) : nullptr;
   ns.accbuf = nq ? c.take<double>((size_t)ns.d) : nullptr;
   ns.agg_part = ns.AS > 1 ? c.take<double>((size_t)ns.AS * ns.groups * kWaveTile) : nullptr;
 }
@@ -603,8 +617,10 @@ void comm_of(const NodeSet& ns, const unsigned long long* hist, uint64_t copies,
         v = ns.lv.K[ns.lv.ref[j - 1]];
         b += v * (32 + ib);
       } else {
+        const int q = ns.lv.ref[j - 1];
         v = (uint64_t)ns.d;
-        b += (uint64_t)ns.d * ns.lv.qbits[ns.lv.ref[j - 1]] + 32;
+        const uint64_t nscales = ns.lv.qblock[q] ? ((uint64_t)ns.d + ns.lv.qblock[q] - 1) / ns.lv.qblock[q] : 1;
+        b += (uint64_t)ns.d * ns.lv.qbits[q] + 32 * nscales;
       }
     }
     *values += hist[j] * v * copies;
@@ -1065,6 +1081,7 @@ int adacgd_state(adacgd_ctx* c, int32_t field, void* dst, int64_t dst_bytes, int
     }
     case ADACGD_F_QCODES: return copy(W.qcodes, n * d * 2);
     case ADACGD_F_QSCALE: return copy(W.qscale, n * 4);
+    case ADACGD_F_QBSCALE: return copy(W.qbscale, n * (int64_t)W.nseg * 4);
     case ADACGD_F_KERNEL_MS: {
       int rc = drain_spans(c);
       if (rc) return rc;

@@ -212,6 +212,9 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
   for (int b = tid; b < kBins0; b += kBlock) hist[b] = 0;
   __syncthreads();
 
+  // block-wise quantiser levels: the largest key of every 64-coordinate segment (a block's scale is the
+  // maximum over its segments, so the result does not depend on how the blocks fall on the wavefronts)
+  uint32_t* __restrict__ segm = ns.segmax ? ns.segmax + (size_t)node * ns.nseg : nullptr;
   double S = 0.0, D = 0.0;
   uint32_t kmax = 0;
   for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
@@ -226,6 +229,7 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
         load4<VEC>(y, l0, d, yv);
         if (yc) store4<VEC>(yc, l0, d, xv);
       }
+      uint32_t kc[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         if (comp_index<VEC>(l0, c) < d) {
@@ -237,8 +241,24 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
             D = fma(dw, dw, D);
           }
           const uint32_t key = magkey(v);
+          kc[c] = key;
           kmax = key > kmax ? key : kmax;
           hist_add(hist, key >> kShift0);
+        }
+      }
+      if (segm) {
+        if (VEC) {        // 16 lanes x 4 consecutive coordinates = one segment
+          uint32_t m = max(max(kc[0], kc[1]), max(kc[2], kc[3]));
+#pragma unroll
+          for (int o = 1; o < 16; o <<= 1) m = max(m, (uint32_t)__shfl_xor(m, o, 64));
+          if ((lane & 15) == 0 && l0 < d) segm[l0 >> 6] = m;
+        } else {          // component c over the 64 lanes = one segment
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const uint32_t m = wave_max(kc[c]);
+            const int64_t start = l0 - lane + 64 * c;
+            if (lane == 0 && start < d) segm[start >> 6] = m;
+          }
         }
       }
     }
@@ -635,12 +655,27 @@ __device__ __forceinline__ float quant_one(float v, float a, float s, float c, f
   return copysignf(mag, v);
 }
 
+// Block-wise quantiser scales of one group of 2048 coordinates (one wavefront's share of a tile).
+// Lane j < 32 loads the largest key of the group's segment j; a block of B coordinates is B/64
+// neighbouring segments (blocks are aligned: B and the group length are powers of two), so its largest
+// key is a maximum over B/64 neighbouring lanes.  On return lane j holds, for the block that contains
+// segment j, the scale a (as a key) and c = fl(a / (s (1 + omega_B))).  Called by all 64 lanes.
+__device__ __forceinline__ void block_scales(const uint32_t* __restrict__ segm, int nseg, int grp, int B, double qdenom,
+                                             uint32_t lane, uint32_t* akey, float* c) {
+  const int64_t seg = (int64_t)grp * kSegPerGroup + lane;
+  uint32_t m = (lane < (uint32_t)kSegPerGroup && seg < nseg) ? segm[seg] : 0u;
+  for (int o = 1; o < B / kSeg; o <<= 1) m = max(m, (uint32_t)__shfl_xor(m, o, 64));
+  const float a = __uint_as_float(m);
+  *akey = m;
+  *c = a > 0.f ? (float)((double)a / qdenom) : 0.f;
+}
+
 // ---------------------------------------------------------------------------
 // filter
 // ---------------------------------------------------------------------------
 // NQ: 0 = no quantiser level; 1..3 = exactly that many (the loops over them carry no run-time test);
-// kMaxLevels = any number.
-template <bool DIFF, bool VEC, int NQ>
+// kMaxLevels = any number.  BLK: some of them are block-wise (their scales come from the segment maxima).
+template <bool DIFF, bool VEC, int NQ, bool BLK>
 __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
   constexpr bool QUANT = NQ > 0;
   constexpr bool EXACT = NQ < kMaxLevels;          // ns.lv.nq == NQ
@@ -683,6 +718,17 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
     uint16_t* __restrict__ soff = coff + (size_t)grp * kWaveTile;
     const uint32_t rot = group_rot(grp, d);
     uint32_t running = 0;
+    uint32_t bkey[NQA];       // block-wise levels: per lane < 32, scale (as a key) and c of the block of segment `lane`
+    float bcq[NQA];
+    if (BLK) {
+#pragma unroll
+      for (int q = 0; q < NQA; ++q) {
+        bkey[q] = 0u;
+        bcq[q] = 0.f;
+        if ((EXACT || q < nq) && ns.lv.qblock[q])
+          block_scales(ns.segmax + (size_t)node * ns.nseg, ns.nseg, grp, ns.lv.qblock[q], ns.lv.qdenom[q], lane, &bkey[q], &bcq[q]);
+      }
+    }
 #pragma unroll
     for (int k = 0; k < kIter; ++k) {
       const int64_t l0 = comp0<VEC>(base, w, lane, k);
@@ -696,6 +742,20 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
       for (int c = 0; c < 4; ++c) {
         vv[c] = DIFF ? xv[c] : xv[c] - hv[c];
         const int64_t l = comp_index<VEC>(l0, c);
+        // scale and c of every quantiser level at this coordinate (all lanes take part in the shuffles)
+        float qa_l[NQA], qc_l[NQA];
+        if (QUANT) {
+          const int sg = k * 4 + (VEC ? (int)(lane >> 4) : c);       // segment of the group this coordinate is in
+#pragma unroll
+          for (int q = 0; q < NQA; ++q) {
+            qa_l[q] = qa;
+            qc_l[q] = qc[q];
+            if (BLK && (EXACT || q < nq) && ns.lv.qblock[q]) {
+              qa_l[q] = __uint_as_float((uint32_t)__shfl(bkey[q], sg, 64));
+              qc_l[q] = __shfl(bcq[q], sg, 64);
+            }
+          }
+        }
         if (l < d) {
           const uint32_t key = magkey(vv[c]);
           const uint32_t bin = key >> kShift0;
@@ -719,7 +779,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
             for (int q = 0; q < NQA; ++q) {
               if (EXACT || q < nq) {
                 int code;
-                const float cq = qa > 0.f ? quant_one(vv[c], qa, ns.lv.qs[q], qc[q], u, &code) : 0.f;
+                const float cq = qa_l[q] > 0.f ? quant_one(vv[c], qa_l[q], ns.lv.qs[q], qc_l[q], u, &code) : 0.f;
                 const double e = dv - (double)cq;
                 qacc[q] = fma(e, e, qacc[q]);
               }
@@ -1080,7 +1140,8 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
   }
   const uint32_t* __restrict__ counts = ns.grp_count + (size_t)node * groups;
   const bool skip = ns.skip[node] != 0;         // the node keeps h: no candidates were extracted
-  for (int g = lo + w; g < (skip ? lo : hi); g += 4) {
+  // (a level set without any Top-K level has no candidate arrays at all: nothing to read either)
+  for (int g = lo + w; g < ((skip || p == 0) ? lo : hi); g += 4) {
     const GroupHead cur = group_load<false>(cval, coff, counts, g, ns.d, lane);
     uint32_t cg[P], ce[P];
 #pragma unroll
@@ -1289,14 +1350,25 @@ __global__ __launch_bounds__(kBlock) void k_qapply(NodeSet ns, PassArgs a) {
   const float* __restrict__ x = a.x + row;
   float* __restrict__ h = a.h + row;
   int16_t* __restrict__ codes = ns.qcodes + row;
-  const float qa = __uint_as_float(ns.amax[node]);
+  const int B = ns.lv.qblock[q];                    // 0: one scale for the whole vector
   const float qs = ns.lv.qs[q];
-  const float qc = qa > 0.f ? (float)((double)qa / ns.lv.qdenom[q]) : 0.f;
-  if (blockIdx.x == 0 && tid == 0) ns.qscale[node] = qc;
+  const float qa_node = B ? 0.f : __uint_as_float(ns.amax[node]);
+  const float qc_node = qa_node > 0.f ? (float)((double)qa_node / ns.lv.qdenom[q]) : 0.f;
+  if (blockIdx.x == 0 && tid == 0) ns.qscale[node] = qc_node;
   const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
   const uint32_t ctr1 = (uint32_t)node | a.node_flag;
   for (int t = blockIdx.x; t < ns.tiles; t += gridDim.x) {
     const int64_t base = (int64_t)t * kTile;
+    uint32_t bkey = 0u;
+    float bcq = 0.f;
+    if (B) {          // scales of this group's blocks; the first lane of every block stores the block's c
+      const int grp = t * 4 + w;
+      block_scales(ns.segmax + (size_t)node * ns.nseg, ns.nseg, grp, B, ns.lv.qdenom[q], lane, &bkey, &bcq);
+      const int64_t seg = (int64_t)grp * kSegPerGroup + lane;
+      const int per = B / kSeg;
+      if (lane < (uint32_t)kSegPerGroup && seg < ns.nseg && (lane % per) == 0)
+        ns.qbscale[(size_t)node * ns.nseg + seg / per] = bcq;
+    }
 #pragma unroll
     for (int k = 0; k < kIter; ++k) {
       const int64_t l0 = comp0<VEC>(base, w, lane, k);
@@ -1308,6 +1380,12 @@ __global__ __launch_bounds__(kBlock) void k_qapply(NodeSet ns, PassArgs a) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int64_t l = comp_index<VEC>(l0, c);
+        float qa = qa_node, qc = qc_node;
+        if (B) {
+          const int sg = k * 4 + (VEC ? (int)(lane >> 4) : c);
+          qa = __uint_as_float((uint32_t)__shfl(bkey, sg, 64));
+          qc = __shfl(bcq, sg, 64);
+        }
         if (l < d) {
           const float vv = DIFF ? xv[c] : xv[c] - hv[c];
           uint32_t word;
@@ -1354,6 +1432,7 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
   __shared__ double red[16];
   __shared__ uint32_t redu[16];
   __shared__ double s_slot_err[kMaxLevels], s_qerr[kMaxLevels];
+  __shared__ uint32_t segk[kSmallMax / kSeg];   // largest key of every 64-coordinate segment (block-wise quantiser scales)
   __shared__ int s_slot, s_q;
   __shared__ int s_flag;
   const bool serve = a.agg_new != nullptr;     // what the aggregation reads goes through coherent accesses
@@ -1373,6 +1452,18 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
   // ---- v, ||v||^2, ||x - y||^2, max |v|, sort keys ----
   double S = 0.0, D = 0.0;
   uint32_t kmax = 0;
+  const bool blockwise = QUANT && lv.nqb > 0;
+  if (blockwise) {
+    for (int i = tid; i < kSmallMax / kSeg; i += NT) segk[i] = 0u;
+    __syncthreads();
+  }
+  // scale a (as a float) of the block of B coordinates that holds coordinate i: the maximum over its segments
+  auto block_max = [&](int i, int B) {
+    const int per = B / kSeg, s0 = (i / B) * per;
+    uint32_t m = 0u;
+    for (int j = 0; j < per && (s0 + j) * kSeg < d; ++j) m = max(m, segk[s0 + j]);
+    return __uint_as_float(m);
+  };
   for (int i = tid; i < dp; i += NT) {
     if (i < d) {
       const float xv = x[i];
@@ -1386,6 +1477,7 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
       S = fma(dv, dv, S);
       const uint32_t key = magkey(v);
       kmax = key > kmax ? key : kmax;
+      if (blockwise) atomicMax(&segk[i >> 6], key);
       sv[i] = v;
       ck[i] = ((uint64_t)key << 32) | (uint64_t)(~(uint32_t)i);
     } else {
@@ -1447,9 +1539,10 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
 #pragma unroll
         for (int q = 0; q < kMaxLevels; ++q) {
           if (q < nq) {
-            const float qc = qa > 0.f ? (float)((double)qa / lv.qdenom[q]) : 0.f;
+            const float aq = lv.qblock[q] ? block_max(i, lv.qblock[q]) : qa;
+            const float qc = aq > 0.f ? (float)((double)aq / lv.qdenom[q]) : 0.f;
             int code;
-            const float cq = qa > 0.f ? quant_one(v, qa, lv.qs[q], qc, u, &code) : 0.f;
+            const float cq = aq > 0.f ? quant_one(v, aq, lv.qs[q], qc, u, &code) : 0.f;
             const double e = (double)v - (double)cq;
             qacc[q] = fma(e, e, qacc[q]);
           }
@@ -1554,16 +1647,23 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
     }
   } else if (QUANT && q >= 0) {
     // ---- dense update and codes of the chosen quantiser level ----
-    const float qa = __uint_as_float(kmax);
+    const int B = lv.qblock[q];
+    const float qa_node = B ? 0.f : __uint_as_float(kmax);
     const float qs = lv.qs[q];
-    const float qc = qa > 0.f ? (float)((double)qa / lv.qdenom[q]) : 0.f;
+    const float qc_node = qa_node > 0.f ? (float)((double)qa_node / lv.qdenom[q]) : 0.f;
     const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
     const uint32_t ctr1 = (uint32_t)node | a.node_flag;
     int16_t* __restrict__ codes = ns.qcodes + row;
-    if (tid == 0) ns.qscale[node] = qc;
+    if (tid == 0) ns.qscale[node] = qc_node;
     for (int i = tid; i < d; i += NT) {
       uint32_t r4[4];
       philox4x32_10((uint32_t)(i >> 2), ctr1, a.step, 0u, k0, k1, r4);
+      float qa = qa_node, qc = qc_node;
+      if (B) {
+        qa = block_max(i, B);
+        qc = qa > 0.f ? (float)((double)qa / lv.qdenom[q]) : 0.f;
+        if (i % B == 0) ns.qbscale[(size_t)node * ns.nseg + i / B] = qc;
+      }
       int code = 0;
       const float cq = qa > 0.f ? quant_one(sv[i], qa, qs, qc, dither_of(r4[i & 3]), &code) : 0.f;
       h[i] = h[i] + cq;
@@ -1627,11 +1727,16 @@ template <bool DIFF, bool VEC>
 static void launch_filter_q(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   const dim3 grid(ns.G, ns.nn), block(kBlock);
   const int nq = ns.lv.nq;
-  if (nq == 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, 0>), grid, block, 0, st, ns, a);
-  else if (VEC && nq == 1) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 1 : kMaxLevels>), grid, block, 0, st, ns, a);
-  else if (VEC && nq == 2) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 2 : kMaxLevels>), grid, block, 0, st, ns, a);
-  else if (VEC && nq == 3) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 3 : kMaxLevels>), grid, block, 0, st, ns, a);
-  else hipLaunchKernelGGL((k_filter<DIFF, VEC, kMaxLevels>), grid, block, 0, st, ns, a);
+  if (ns.lv.nqb > 0) {       // block-wise quantiser levels: the general kernel, or the one for a single level
+    if (VEC && nq == 1) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 1 : kMaxLevels, true>), grid, block, 0, st, ns, a);
+    else hipLaunchKernelGGL((k_filter<DIFF, VEC, kMaxLevels, true>), grid, block, 0, st, ns, a);
+    return;
+  }
+  if (nq == 0) hipLaunchKernelGGL((k_filter<DIFF, VEC, 0, false>), grid, block, 0, st, ns, a);
+  else if (VEC && nq == 1) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 1 : kMaxLevels, false>), grid, block, 0, st, ns, a);
+  else if (VEC && nq == 2) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 2 : kMaxLevels, false>), grid, block, 0, st, ns, a);
+  else if (VEC && nq == 3) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 3 : kMaxLevels, false>), grid, block, 0, st, ns, a);
+  else hipLaunchKernelGGL((k_filter<DIFF, VEC, kMaxLevels, false>), grid, block, 0, st, ns, a);
 }
 
 hipError_t launch_filter(const NodeSet& ns, const PassArgs& a, hipStream_t st) {

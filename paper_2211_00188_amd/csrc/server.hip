@@ -147,8 +147,10 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_aggregate_dense(NodeSet ws
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int ii = i + u;
-      const bool dense = ii < i1 && ws.sel_q[ii] >= 0;
-      sc[u] = dense ? ws.qscale[ii] : 0.f;
+      const int qi = ii < i1 ? ws.sel_q[ii] : -1;
+      const bool dense = qi >= 0;
+      const int B = dense ? ws.lv.qblock[qi] : 0;          // block-wise level: the scale of this coordinate pair's block
+      sc[u] = !dense ? 0.f : (B ? ws.qbscale[(size_t)ii * ws.nseg + (ok0 ? c0 / B : 0)] : ws.qscale[ii]);
       const int16_t* __restrict__ codes = ws.qcodes + (size_t)(dense ? ii : 0) * d;
       if (pair) {
         const uint32_t two = dense ? *reinterpret_cast<const uint32_t*>(codes + c0) : 0u;

@@ -1050,3 +1050,54 @@ def test_aggregation_with_wide_exponent_spread(dense):
     lo, hi = np.abs(orc.gt[orc.gt != 0]).min(), np.abs(orc.gt).max()
     assert hi > 1e9                                   # the large workers dominate the aggregate
     eng.close()
+
+
+@pytest.mark.parametrize("n,d,flags", [(4, 3 * 8192 + 516, 0), (3, 2 * 8192 + 517, 0), (5, 1000, 0), (2, 4095, 0),
+                                       (3, 1000, "two_pass"), (2, 130, 0), (2, 5 * 8192, 0)])
+@pytest.mark.parametrize("blocks", [((4, 256),), ((8, 64), (2, 2048)), ((4, 128), (4, 1024), (3, 512))])
+def test_block_wise_quantiser_levels_bit_exact(n, d, flags, blocks):
+    """Level sets with block-wise b-bit quantisers (one max-norm scale per block of B coordinates) next to
+    Top-K levels and a plain quantiser, on the 16-byte and the scalar path, the one-block kernel and the
+    general kernels, worker and master side: levels, errors, estimators, codes and per-block scales."""
+    E = _eng()
+    rng = np.random.default_rng(d + 7 * len(blocks))
+    wl = [(O.TOPK, max(1, d // 300)), (O.TOPK, max(2, d // 20))] + [(O.QUANT_BLOCK, bb) for bb in blocks]
+    if len(blocks) == 2:
+        wl.append((O.QUANT, 4))
+    wl = by_alpha(wl, d)
+    ml = by_alpha([(O.TOPK, max(1, d // 100)), (O.QUANT_BLOCK, (4, 64))], d)
+    steps = 4
+    grads = [make_vectors(rng, n, d, "heavy") for _ in range(steps + 1)]
+    for g in grads:                                   # blocks of very different size, one block of zeros
+        g[:, : min(d, 64)] *= np.float32(1e-6)
+        g[:, min(d, 64): min(d, 128)] = 0.0
+    for t in range(1, steps + 1):
+        grads[t] = (grads[t - 1] + grads[t] * np.float32(10.0 ** rng.uniform(-2, 0))).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    seen = set()
+    for zeta in (0.0, 0.05, 0.8):
+        kw = dict(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zeta, master_levels=ml, zeta_master=0.3, seed=41)
+        orc = O.AdaCGDOracle(**kw)
+        orc.init(x0, grads[0], O.INIT_ZERO)
+        eng = E.AdaCGD(grad_mode=E.GRAD_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), grad0=_cuda(grads[0]),
+                       flags=(E.FLAG_TWO_PASS if flags == "two_pass" else 0) | E.FLAG_ANY_LEVEL_ORDER, **kw)
+        with until_near_tie(("block-wise", n, d, blocks, zeta)):
+            for t in range(1, steps + 1):
+                res, rm = orc.step(grads=grads[t])
+                eng.step(_cuda(grads[t]))
+                compare_step(eng, orc, res, rm, ("block-wise", n, d, blocks, zeta, t))
+                codes = scales = None
+                for i, r in enumerate(res):
+                    if r.level > 0:
+                        seen.add(wl[r.level - 1])
+                    if r.scales is not None:
+                        if codes is None:
+                            codes, scales = eng.state(E.F_QCODES), eng.state(E.F_QBSCALE)
+                        assert np.array_equal(codes[i].astype(np.int32), r.codes), (t, i)
+                        assert np.array_equal(bits(scales[i][: len(r.scales)]), bits(r.scales)), (t, i)
+            assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+            assert eng.state(E.F_M_LEVEL_HIST).tolist() == orc.level_hist_m.tolist()
+            assert eng.state(E.F_COMM).tolist()[1] == sum(
+                int(orc.level_hist_w[j]) * O.AdaCGDOracle.message_bits(j, wl, d) for j in range(len(wl) + 1))
+        eng.close()
+    assert any(k == O.QUANT_BLOCK for k, _ in seen), seen
