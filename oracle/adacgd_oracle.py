@@ -33,6 +33,12 @@ inequality of Definition 1, not against a paper value.  The block-wise variant
 (one max-norm scale per block of B consecutive coordinates) is the same quantiser
 applied to every block on its own; it is pinned against the plain one (block by
 block, and B = d), the same closed form summed over the blocks, and Definition 1.
+Rank-K (Section 2.1 names it beside Top-K for matrix-shaped arguments) is the
+truncated singular value decomposition; how a gradient vector becomes a matrix is
+a reading (row-major, c columns); it is pinned against the Eckart-Young optimum
+(squared error = sum of the discarded squared singular values, not improved by any
+other rank-K matrix tried), exact recovery of matrices of rank <= K, and the
+contractive inequality with alpha = K / min(rows, columns).
 """
 from __future__ import annotations
 
@@ -44,6 +50,7 @@ import numpy as np
 TOPK = 0
 QUANT = 1
 QUANT_BLOCK = 2      # level = (QUANT_BLOCK, (b, B)): b bits, one scale per block of B consecutive coordinates
+RANK = 3             # level = (RANK, (K, c)): best rank-K approximation of the vector read as a (d/c) x c matrix
 
 INIT_FULLGRAD = 0
 INIT_ZERO = 1
@@ -255,6 +262,22 @@ def quant_block_expected_sqerr(v: np.ndarray, b: int, B: int) -> float:
 
 
 # --------------------------------------------------------------------------
+# Rank-K (Section 2.1): truncated singular value decomposition of the matrix-shaped argument
+# --------------------------------------------------------------------------
+def rank_k(v: np.ndarray, K: int, c: int):
+    """Best rank-K approximation (in the Frobenius norm) of v read row-major as a matrix X of
+    d/c rows and c columns: X_K = sum_{k<K} sigma_k u_k v_k^T from a singular value decomposition in
+    float64, rounded once to v's dtype.  It is unique when sigma_K > sigma_{K+1}.
+    Returns (C(v) as a vector of length d, the singular values)."""
+    d = v.shape[0]
+    assert d % c == 0 and 1 <= K <= c
+    X = np.asarray(v, dtype=np.float64).reshape(d // c, c)
+    U, sig, Vt = np.linalg.svd(X, full_matrices=False)
+    XK = (U[:, :K] * sig[:K]) @ Vt[:K]
+    return XK.reshape(d).astype(v.dtype), sig
+
+
+# --------------------------------------------------------------------------
 # level sets
 # --------------------------------------------------------------------------
 def level_alpha(level, d: int) -> float:
@@ -263,6 +286,9 @@ def level_alpha(level, d: int) -> float:
         return param / d
     if kind == QUANT:
         return quant_alpha(d, param)
+    if kind == RANK:
+        K, c = param
+        return K / min(c, d // c)     # ||X_K - X||_F^2 = sum of the min(r, c) - K smallest sigma^2 <= (1 - K/min(r, c)) ||X||_F^2
     b, B = param
     return quant_alpha(B, b)          # every block is contractive with the parameter of a length-B vector
 
@@ -289,6 +315,7 @@ class CompressResult:
     codes: np.ndarray | None = None
     scale: float = 0.0
     scales: np.ndarray | None = None   # block-wise quantiser level: one scale per block
+    sigma: np.ndarray | None = None    # Rank-K level: the singular values of the matrix-shaped argument
     margins: list = field(default_factory=list)   # |lhs - tau| / max(tau, tiny) of every comparison made
 
 
@@ -333,6 +360,9 @@ def adacgd_compress(h, y, x, levels, zeta, *, seed=0, node=0, step=0, D_given=No
                 order = magnitude_order(v)
             c = topk(v, param, order)
             cands.append(("topk", c, topk_support(v, param, order)))
+        elif kind == RANK:
+            c, sig = rank_k(v, param[0], param[1])
+            cands.append(("rank", c, None, sig))
         else:
             if u is None:
                 u = dither_uniforms(d, seed, node, step)
@@ -376,6 +406,8 @@ def adacgd_compress(h, y, x, levels, zeta, *, seed=0, node=0, step=0, D_given=No
         return CompressResult(level, S, D, err, h_new, idx.astype(np.int32), v[idx].copy(), None, margins=margins)
     c = cand[1]
     h_new = (h + c).astype(dt)
+    if cand[0] == "rank":
+        return CompressResult(level, S, D, err, h_new, empty_i, empty_v, c, sigma=cand[3], margins=margins)
     blockwise = np.ndim(cand[3]) > 0
     return CompressResult(level, S, D, err, h_new, empty_i, empty_v, c, codes=cand[2],
                           scale=0.0 if blockwise else float(cand[3]), scales=cand[3] if blockwise else None,
@@ -531,6 +563,9 @@ class AdaCGDOracle:
             return idb + param * (32 + max(1, math.ceil(math.log2(d))))
         if kind == QUANT:
             return idb + d * param + 32
+        if kind == RANK:
+            K, c = param
+            return idb + 32 * K * (d // c + c)            # K left factors (scaled) of d/c floats, K right factors of c
         b, B = param
         return idb + d * b + 32 * ((d + B - 1) // B)      # one float scale per block
 
@@ -539,4 +574,6 @@ class AdaCGDOracle:
         if level == 0:
             return 0
         kind, param = levels[level - 1]
+        if kind == RANK:
+            return param[0] * (d // param[1] + param[1])
         return param if kind == TOPK else d

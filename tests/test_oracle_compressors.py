@@ -308,3 +308,68 @@ def test_block_quantizer_level_in_the_cascade_and_its_message_cost():
     assert abs(r.err[1] - O.sum_sq_diff(v, c)) <= 1e-15 * r.err[1]
     assert O.AdaCGDOracle.message_bits(2, levels[:2], d) == 2 + d * b + 32 * 3
     assert O.AdaCGDOracle.message_values(2, levels[:2], d) == d
+
+
+# ---------------------------------------------------------------- Rank-K
+def test_rank_k_is_the_eckart_young_optimum():
+    """Rank-K against what the mathematics fixes: its squared error is the sum of the discarded squared
+    singular values (computed here from the eigenvalues of X^T X, another route than the SVD the oracle
+    calls), no other rank-K matrix tried does better, its rank is K, matrices of rank <= K come back
+    unchanged, and the contractive inequality holds with alpha = K / min(rows, columns)."""
+    rng = np.random.default_rng(31)
+    for r, c, K in ((40, 8, 3), (64, 16, 1), (33, 16, 16), (100, 4, 2)):
+        d = r * c
+        X = rng.standard_normal((r, c)) * np.linspace(3.0, 0.2, c)      # columns of different weight
+        v = X.reshape(d).astype(np.float32)
+        C, sig = O.rank_k(v, K, c)
+        X32 = v.astype(np.float64).reshape(r, c)
+        lam = np.sort(np.linalg.eigvalsh(X32.T @ X32))[::-1]              # sigma^2, descending
+        assert np.allclose(sig ** 2, lam, rtol=1e-9, atol=1e-9 * lam[0])
+        err = O.sum_sq_diff(v, C)
+        tail = float(np.sum(lam[K:]))
+        assert abs(err - tail) <= 1e-5 * float(np.sum(lam)) + 1e-12       # (C is rounded to fp32)
+        assert np.linalg.matrix_rank(C.astype(np.float64).reshape(r, c), tol=1e-4 * np.sqrt(lam[0])) == min(K, c)
+        assert err <= (1 - O.level_alpha((O.RANK, (K, c)), d)) * O.sum_squares(v) * (1 + 1e-6)
+        for _ in range(20):                                               # random rank-K competitors: never better
+            A, B = rng.standard_normal((r, K)), rng.standard_normal((K, c))
+            # best fit within the column space of A and, separately, the row space of B
+            for Y in (A @ np.linalg.lstsq(A, X32, rcond=None)[0], (np.linalg.lstsq(B.T, X32.T, rcond=None)[0]).T @ B):
+                assert np.sum((X32 - Y) ** 2) >= tail * (1 - 1e-9)
+    # exact recovery of a matrix of rank 2 with K = 2 and K = 5
+    r, c = 50, 8
+    L = (rng.standard_normal((r, 2)) @ rng.standard_normal((2, c))).astype(np.float32)
+    for K in (2, 5):
+        C, sig = O.rank_k(L.reshape(-1), K, c)
+        assert np.abs(C - L.reshape(-1)).max() <= 1e-5 * np.abs(L).max()
+    assert np.all(sig[2:] <= 1e-5 * sig[0])
+    # a diagonal example by hand: X = diag(5, -3, 1) padded; rank 1 keeps the 5, rank 2 the 5 and the -3
+    X = np.zeros((4, 3), dtype=np.float32)
+    X[0, 0], X[1, 1], X[2, 2] = 5.0, -3.0, 1.0
+    C1, sig = O.rank_k(X.reshape(-1), 1, 3)
+    assert np.allclose(sig, [5, 3, 1]) and np.allclose(C1.reshape(4, 3), np.diag([5.0, 0, 0, 0])[:, :3], atol=1e-6)
+    C2, _ = O.rank_k(X.reshape(-1), 2, 3)
+    assert np.allclose(C2.reshape(4, 3), np.diag([5.0, -3.0, 0, 0])[:, :3], atol=1e-6)
+
+
+def test_rank_k_level_in_the_cascade():
+    rng = np.random.default_rng(32)
+    d, c = 40 * 8, 8
+    h = rng.standard_normal(d).astype(np.float32)
+    x = (h + (rng.standard_normal((40, c)) * np.linspace(2, 0.1, c)).reshape(d)).astype(np.float32)
+    y = (x + rng.standard_normal(d) * 0.3).astype(np.float32)
+    levels = [(O.RANK, (1, c)), (O.RANK, (4, c)), (O.TOPK, d)]
+    assert O.check_levels(levels, d) and O.level_alpha(levels[1], d) == 0.5
+    v = (x - h).astype(np.float32)
+    D = O.sum_squares((x - y).astype(np.float32))
+    e1 = O.sum_sq_diff(v, O.rank_k(v, 1, c)[0])
+    e4 = O.sum_sq_diff(v, O.rank_k(v, 4, c)[0])
+    assert e4 < e1 < O.sum_squares(v)
+    for zeta, want in ((0.0, 3), (e4 / D * 1.01, 2), (e1 / D * 1.01, 1), (O.sum_squares(v) / D * 1.01, 0)):
+        r = O.adacgd_compress(h, y, x, levels, zeta)
+        assert r.level == want, (zeta, r.level)
+        if want in (1, 2):
+            C = O.rank_k(v, levels[want - 1][1][0], c)[0]
+            assert np.array_equal(r.h_new.view(np.uint32), (h + C).astype(np.float32).view(np.uint32))
+            assert r.sigma is not None and len(r.sigma) == c and len(r.msg_idx) == 0
+    assert O.AdaCGDOracle.message_bits(2, levels, d) == 2 + 32 * 4 * (40 + 8)
+    assert O.AdaCGDOracle.message_values(1, levels, d) == 48
