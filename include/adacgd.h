@@ -57,15 +57,21 @@ enum adacgd_status {
 enum adacgd_level_kind {
   ADACGD_TOPK = 0,
   ADACGD_QUANT = 1,      /* b-bit stochastic quantiser, one max-norm scale for the whole vector          */
-  ADACGD_QUANT_BLOCK = 2 /* the same quantiser applied to every block of B consecutive coordinates on its
+  ADACGD_QUANT_BLOCK = 2, /* the same quantiser applied to every block of B consecutive coordinates on its
                             own (one max-norm scale per block; the last block may be shorter); omega, and
                             with it alpha = 1/(1+omega), are those of a length-B vector; the message is the
                             d codes plus one float per block                                              */
+  ADACGD_RANK = 3        /* Rank-K (Section 2.1): the argument, read row-major as a matrix of d/c rows and c
+                            columns, is replaced by its best rank-K approximation (truncated singular value
+                            decomposition, fp64, rounded once to fp32); alpha = K/c; the message is K scaled
+                            left factors of d/c floats and K right factors of c floats.  All Rank-K levels of
+                            a level set use the same c                                                     */
 };
 typedef struct {
   int32_t kind;  /* adacgd_level_kind                                   */
-  int32_t block; /* QUANT_BLOCK: block length B, a power of two in [64, 2048]; otherwise 0 */
-  int64_t param; /* TOPK: K in [1,d] (K = d is the identity); QUANT, QUANT_BLOCK: b in [2,16] */
+  int32_t block; /* QUANT_BLOCK: block length B, a power of two in [64, 2048]; RANK: columns c, one of 16, 32,
+                    64, with d a multiple of c and d >= c^2; otherwise 0 */
+  int64_t param; /* TOPK: K in [1,d] (K = d is the identity); QUANT, QUANT_BLOCK: b in [2,16]; RANK: K in [1,c] */
 } adacgd_level;
 
 #define ADACGD_MAX_LEVELS 16
@@ -239,6 +245,9 @@ enum adacgd_field {
                                 entry k of a row is the scale of block k (the first ceil(d/B) entries; the rest
                                 and the rows of workers that chose another level are unspecified); only kept
                                 when the worker level set holds a block-wise quantiser                        */
+  ADACGD_F_RANK_SPECTRUM = 32, /* double [n x c] squared singular values, descending, of every worker's matrix-shaped
+                                argument at the last step (rows of workers that skipped are unspecified); only
+                                with Rank-K levels in the worker level set                                  */
   ADACGD_F_CANDIDATES = 30,  /* uint64 [2]     coordinates (workers, master) that the last step's one-pass scan kept as
                                 candidates for the largest Top-K size, summed over the nodes (0 where the
                                 one-pass sequence is not in use); a diagnostic of the sampled cut         */
@@ -276,7 +285,9 @@ enum adacgd_kernel {
   ADACGD_K_M_TALLY = 17,
   ADACGD_K_M_COMPACT = 18,
   ADACGD_K_M_QAPPLY = 19,
-  ADACGD_NUM_KERNELS = 20
+  ADACGD_K_W_RANK = 20,    /* Rank-K levels: Gram matrix, eigen-decomposition, realised errors, dense update */
+  ADACGD_K_M_RANK = 21,
+  ADACGD_NUM_KERNELS = 22
 };
 
 /* Copies one field to dst (host memory, or device memory if dst_on_device != 0)

@@ -25,13 +25,16 @@ constexpr int kSmallServeMax = 64;      // ... which also aggregates when there 
 constexpr int kSeg = 64;                // block-wise quantiser scales are built from maxima over segments of 64 coordinates
 constexpr int kSegPerGroup = kWaveTile / kSeg;   // 32
 
-enum { kTopK = 0, kQuant = 1 };
+enum { kTopK = 0, kQuant = 1, kRank = 2 };
 
 // The ordered level set of one side, in the form the kernels use.
 struct LevelTable {
   int m;                      // levels in cascade order (strongest compression first)
-  int kind[kMaxLevels];       // kTopK / kQuant
-  int ref[kMaxLevels];        // kTopK: slot index into K[]; kQuant: index into qs[]
+  int kind[kMaxLevels];       // kTopK / kQuant / kRank
+  int ref[kMaxLevels];        // kTopK: slot index into K[]; kQuant: index into qs[]; kRank: index into rK[]
+  int nr;                     // Rank-K levels (the vector read row-major as a (d / rcols) x rcols matrix)
+  int rcols;                  // their common number of columns: 16, 32 or 64 (0 if there is none)
+  int rK[kMaxLevels];         // their ranks
   int p;                      // distinct Top-K sizes ("slots")
   uint32_t K[kMaxLevels];     // ascending
   int nq;                     // quantiser levels
@@ -113,6 +116,17 @@ struct NodeSet {
   int16_t* qcodes;      // [nn][d] (only with quantiser levels)
   float* qscale;        // [nn]
   double* accbuf;       // [d] fp64 sums of the sparse messages (only with quantiser levels)
+  // Rank-K levels (allocated only when the level set has any; c = lv.rcols, nr = lv.nr)
+  int GR;               // blocks per node of the Rank-K kernels
+  double* gram_part;    // [nn][GR][c*c]  partial Gram matrices X^T X of the blocks
+  double* gram;         // [nn][c*c]
+  double* rk_vec;       // [nn][c*c]      eigenvectors of X^T X in columns
+  double* rk_lambda;    // [nn][c]        its eigenvalues (squared singular values of X), descending
+  double* rk_P;         // [nn][nr][c*c]  projector onto the K leading right singular vectors, per Rank-K level
+  double* rk_part;      // [nn][GR][nr]   partial realised errors
+  double* rk_err;       // [nn][nr]       realised error of every Rank-K level
+  float* rdense;        // [nn][d]        C(v) of the last Rank-K message (the aggregation adds it)
+  int32_t* sel_rk;      // [nn]           Rank-K level (index into rK) of the chosen level, -1 otherwise
   int AS;               // aggregation: blocks that share one group's workers (1 = one block per group)
   double* agg_part;     // [AS][groups][kWaveTile] their partial sums (AS > 1)
   uint32_t* agg_done;   // [groups][kArriveFan+1] arrival counters (AS > 1); zero between launches
@@ -180,6 +194,8 @@ hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, bool repair, hipSt
 hipError_t launch_tally(const NodeSet& ns, hipStream_t st);
 hipError_t launch_compact(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_qapply(const NodeSet& ns, const PassArgs& a, hipStream_t st);
+hipError_t launch_rank_errors(const NodeSet& ns, const PassArgs& a, hipStream_t st);
+hipError_t launch_rank_apply(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 
 hipError_t launch_xupdate(float* x, const float* g, double gamma, int64_t d, hipStream_t st);
 hipError_t launch_mean(const float* gi, float* out0, float* out1, float* out2, int n, int64_t d, hipStream_t st);

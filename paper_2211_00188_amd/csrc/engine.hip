@@ -50,6 +50,7 @@ double quant_omega(int b, double len) {
 
 double level_alpha(const adacgd_level& lv, int64_t d) {
   if (lv.kind == ADACGD_TOPK) return (double)lv.param / (double)d;
+  if (lv.kind == ADACGD_RANK) return (double)lv.param / (double)lv.block;     // K / min(rows, columns), rows >= columns
   return 1.0 / (1.0 + quant_omega((int)lv.param, lv.kind == ADACGD_QUANT_BLOCK ? (double)lv.block : (double)d));
 }
 
@@ -85,6 +86,25 @@ int build_levels(const adacgd_level* in, int m, float zeta, const adacgd_trigger
         set_err(err, "level %d: block length must be a power of two in [64, 2048], got %d", j + 1, B);
         return ADACGD_ERR_ARG;
       }
+    } else if (in[j].kind == ADACGD_RANK) {
+      const int c = in[j].block;
+      if (c != 16 && c != 32 && c != 64) {
+        set_err(err, "level %d: Rank-K needs 16, 32 or 64 columns, got %d", j + 1, c);
+        return ADACGD_ERR_ARG;
+      }
+      if (d % c != 0 || d / c < c) {
+        set_err(err, "level %d: Rank-K with %d columns needs d to be a multiple of %d and at least %d", j + 1, c, c, c * c);
+        return ADACGD_ERR_ARG;
+      }
+      if (in[j].param < 1 || in[j].param > c) {
+        set_err(err, "level %d: Rank-K needs 1 <= K <= columns, got %lld", j + 1, (long long)in[j].param);
+        return ADACGD_ERR_ARG;
+      }
+      if (lt->rcols && lt->rcols != c) {
+        set_err(err, "level %d: all Rank-K levels of a level set must use the same number of columns", j + 1);
+        return ADACGD_ERR_ARG;
+      }
+      lt->rcols = c;
     } else {
       set_err(err, "level %d: unknown kind %d", j + 1, in[j].kind);
       return ADACGD_ERR_ARG;
@@ -104,8 +124,11 @@ int build_levels(const adacgd_level* in, int m, float zeta, const adacgd_trigger
   lt->p = nk;
   for (int s = 0; s < lt->p; ++s) lt->K[s] = ks[s];
   for (int j = 0; j < m; ++j) {
-    lt->kind[j] = in[j].kind == ADACGD_TOPK ? kTopK : kQuant;      // (block-wise or not is a property of the quantiser entry)
-    if (in[j].kind == ADACGD_TOPK) {
+    lt->kind[j] = in[j].kind == ADACGD_TOPK ? kTopK : in[j].kind == ADACGD_RANK ? kRank : kQuant;
+    if (in[j].kind == ADACGD_RANK) {
+      lt->ref[j] = lt->nr;
+      lt->rK[lt->nr++] = (int)in[j].param;
+    } else if (in[j].kind == ADACGD_TOPK) {
       lt->ref[j] = (int)(std::lower_bound(ks, ks + nk, (uint32_t)in[j].param) - ks);
     } else {
       const int b = (int)in[j].param;
@@ -182,7 +205,19 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   ns.nseg = (int)((ns.d + kSeg - 1) / kSeg);
   ns.segmax = ns.lv.nqb ? c.take<uint32_t>(nn * (size_t)ns.nseg) : nullptr;
   ns.qbscale = ns.lv.nqb ? c.take<float>(nn * (size_t)ns.nseg) : nullptr;
-  ns.accbuf = nq ? c.take<double>((size_t)ns.d) : nullptr;
+  ns.accbuf = (nq || ns.lv.nr) ? c.take<double>((size_t)ns.d) : nullptr;
+  if (ns.lv.nr) {
+    const size_t cc = (size_t)ns.lv.rcols * ns.lv.rcols, nr = ns.lv.nr;
+    ns.gram_part = c.take<double>(nn * ns.GR * cc);
+    ns.gram = c.take<double>(nn * cc);
+    ns.rk_vec = c.take<double>(nn * cc);
+    ns.rk_lambda = c.take<double>(nn * ns.lv.rcols);
+    ns.rk_P = c.take<double>(nn * nr * cc);
+    ns.rk_part = c.take<double>(nn * ns.GR * nr);
+    ns.rk_err = c.take<double>(nn * nr);
+    ns.rdense = c.take<float>(nn * (size_t)ns.d);
+    ns.sel_rk = c.take<int32_t>(nn);
+  }
   ns.agg_part = ns.AS > 1 ? c.take<double>((size_t)ns.AS * ns.groups * kWaveTile) : nullptr;
 }
 
@@ -204,6 +239,14 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
   ns.onepass = (!force_two_pass && ns.lv.nq == 0 && ns.lv.p > 0 && d % 4 == 0 && ns.tiles >= 128 &&
                 4 * (int64_t)ns.Kcap <= d) ? 1 : 0;
   ns.small = (!force_two_pass && d <= kSmallMax) ? 1 : 0;
+  if (ns.lv.nr > 0) {            // Rank-K levels: the general two-pass sequence plus the Rank-K kernels
+    ns.onepass = 0;
+    ns.small = 0;
+    const int64_t rows = d / ns.lv.rcols;
+    int64_t gr = (rows + 63) / 64;                 // at least 64 rows per block, about 1024 blocks in all, at most 64 per node
+    const int64_t cap = std::min<int64_t>(64, std::max<int64_t>(1, 1024 / nn));
+    ns.GR = (int)std::max<int64_t>(1, std::min(gr, cap));
+  }
   // streaming kernels: about 5120 blocks in all for the fused scan (several short blocks per CU
   // interleave better with kernels of another stream than few long ones), about 2048 for the
   // two-pass scan (whose blocks each flush a full histogram); at most 640 per node
@@ -485,12 +528,16 @@ int compress(adacgd_ctx* c, NodeSet& ns, const PassArgs& a, int slot0, hipEvent_
     if ((rc = timed(c, slot0 + 1, [&] { return launch_scan(ns, a, c->cs); }))) return rc;
     if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->cs); }))) return rc;
   }
+  if (ns.lv.nr > 0 && (rc = timed(c, slot0 == ADACGD_K_W_SAMPLE ? ADACGD_K_W_RANK : ADACGD_K_M_RANK,
+                                  [&] { return launch_rank_errors(ns, a, c->cs); }))) return rc;
   if (ns.lv.p > 0 && (rc = timed(c, slot0 + 3, [&] { return launch_gather(ns, c->cs); }))) return rc;
   if (ns.lv.p > 0 && (rc = timed(c, slot0 + 4, [&] { return launch_select(ns, c->cs); }))) return rc;
   if (before_tally) HIPCHK(c, hipStreamWaitEvent(c->cs, before_tally, 0));
   if ((rc = timed(c, slot0 + 5, [&] { return launch_tally(ns, c->cs); }))) return rc;
   if (ns.lv.p > 0 && (rc = timed(c, slot0 + 6, [&] { return launch_compact(ns, a, c->cs); }))) return rc;
   if (ns.lv.nq > 0 && (rc = timed(c, slot0 + 7, [&] { return launch_qapply(ns, a, c->cs); }))) return rc;
+  if (ns.lv.nr > 0 && (rc = timed(c, slot0 == ADACGD_K_W_SAMPLE ? ADACGD_K_W_RANK : ADACGD_K_M_RANK,
+                                  [&] { return launch_rank_apply(ns, a, c->cs); }))) return rc;
   return ADACGD_OK;
 }
 
@@ -516,7 +563,7 @@ int one_step(adacgd_ctx* c, const float* ext, const double* extD) {
   }
   // Short vectors, few workers, Top-K messages only: the one-block kernel of the workers also does the
   // aggregation (its last block), and the kernel that finishes g the next iterate update.
-  const bool serve = c->W.small && c->W.lv.nq == 0 && c->n <= kSmallServeMax && !ov;
+  const bool serve = c->W.small && c->W.lv.nq == 0 && c->W.lv.nr == 0 && c->n <= kSmallServeMax && !ov;
   PassArgs a{};
   a.h = c->gi;
   a.seed = c->seed;
@@ -616,6 +663,9 @@ void comm_of(const NodeSet& ns, const unsigned long long* hist, uint64_t copies,
       if (ns.lv.kind[j - 1] == kTopK) {
         v = ns.lv.K[ns.lv.ref[j - 1]];
         b += v * (32 + ib);
+      } else if (ns.lv.kind[j - 1] == kRank) {          // K scaled left factors of d/c floats and K right factors of c
+        v = (uint64_t)ns.lv.rK[ns.lv.ref[j - 1]] * ((uint64_t)ns.d / ns.lv.rcols + ns.lv.rcols);
+        b += 32 * v;
       } else {
         const int q = ns.lv.ref[j - 1];
         v = (uint64_t)ns.d;
@@ -895,6 +945,8 @@ static int init_impl(const adacgd_config* cfg, adacgd_ctx** out, int static_dev)
   // message tables start empty
   INITCHK(launch_fill_u32((uint32_t*)c->W.sel_slot, 0xFFFFFFFFu, (size_t)c->n, c->st));
   INITCHK(launch_fill_u32((uint32_t*)c->W.sel_q, 0xFFFFFFFFu, (size_t)c->n, c->st));
+  if (c->W.lv.nr) INITCHK(launch_fill_u32((uint32_t*)c->W.sel_rk, 0xFFFFFFFFu, (size_t)c->n, c->st));
+  if (c->has_master && c->M.lv.nr) INITCHK(launch_fill_u32((uint32_t*)c->M.sel_rk, 0xFFFFFFFFu, 1, c->st));
   INITCHK(launch_fill_u32(c->W.msg_count, 0u, (size_t)c->n, c->st));
   INITCHK(launch_fill_u32((uint32_t*)c->W.level, 0u, (size_t)c->n, c->st));
   if (c->has_master) {
@@ -1082,6 +1134,7 @@ int adacgd_state(adacgd_ctx* c, int32_t field, void* dst, int64_t dst_bytes, int
     case ADACGD_F_QCODES: return copy(W.qcodes, n * d * 2);
     case ADACGD_F_QSCALE: return copy(W.qscale, n * 4);
     case ADACGD_F_QBSCALE: return copy(W.qbscale, n * (int64_t)W.nseg * 4);
+    case ADACGD_F_RANK_SPECTRUM: return copy(W.lv.nr ? W.rk_lambda : nullptr, n * (int64_t)W.lv.rcols * 8);
     case ADACGD_F_KERNEL_MS: {
       int rc = drain_spans(c);
       if (rc) return rc;

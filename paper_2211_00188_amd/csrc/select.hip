@@ -1211,6 +1211,8 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
         const double tv = (double)__uint_as_float(ns.prefix[node * p + s]);
         const double left = (double)(ns.eqcnt[node * p + s] - ns.rank[node * p + s]);   // ties not taken
         err[j] = Eb + s_strict[s] + left * (tv * tv);
+      } else if (lv.kind[j] == kRank) {
+        err[j] = ns.rk_err[node * lv.nr + lv.ref[j]];
       } else {
         err[j] = ns.qerr[node * lv.nq + lv.ref[j]];
       }
@@ -1227,13 +1229,15 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
     ns.level[node] = jstar;
     atomicAdd(&ns.level_hist[jstar], 1ull);
     if (p > 0) ns.gcur[(size_t)node * kCurStride] = 0;
-    int slot = -1, q = -1;
+    int slot = -1, q = -1, rk = -1;
     if (jstar > 0) {
       if (lv.kind[jstar - 1] == kTopK) slot = lv.ref[jstar - 1];
+      else if (lv.kind[jstar - 1] == kRank) rk = lv.ref[jstar - 1];
       else q = lv.ref[jstar - 1];
     }
     ns.sel_slot[node] = slot;
     ns.sel_q[node] = q;
+    if (lv.nr > 0) ns.sel_rk[node] = rk;
     ns.msg_count[node] = slot >= 0 ? lv.K[slot] : 0u;
     // (the message tables, this scale among them, are read by the previous step's aggregation: the first
     // kernel that may write them is this one, which in overlap mode is ordered behind that aggregation)

@@ -140,6 +140,16 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_aggregate_dense(NodeSet ws
     const float mag = (float)(code < 0 ? -code : code) * sc;
     return (double)(code < 0 ? -mag : mag);
   };
+  // Rank-K messages are dense fp32 vectors: workers that chose one, in ascending order after this
+  // wavefront's quantised ones
+  if (ws.lv.nr > 0) {
+    for (int i = i0; i < i1; ++i) {
+      if (ws.sel_rk[i] < 0) continue;
+      const float* __restrict__ rd = ws.rdense + (size_t)i * d;
+      if (ok0) a0 += (double)rd[c0];
+      if (ok1) a1 += (double)rd[c0 + 1];
+    }
+  }
   constexpr int U = 8;
   for (int i = i0; i < i1; i += U) {
     int k0[U], k1[U];
@@ -147,7 +157,7 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_aggregate_dense(NodeSet ws
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int ii = i + u;
-      const int qi = ii < i1 ? ws.sel_q[ii] : -1;
+      const int qi = (ii < i1 && ws.lv.nq > 0) ? ws.sel_q[ii] : -1;
       const bool dense = qi >= 0;
       const int B = dense ? ws.lv.qblock[qi] : 0;          // block-wise level: the scale of this coordinate pair's block
       sc[u] = !dense ? 0.f : (B ? ws.qbscale[(size_t)ii * ws.nseg + (ok0 ? c0 / B : 0)] : ws.qscale[ii]);
@@ -420,7 +430,7 @@ hipError_t launch_mean(const float* gi, float* o0, float* o1, float* o2, int n, 
 hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_new, const IterateUpdate& xu,
                             hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
-  if (ws.lv.nq == 0) {
+  if (ws.lv.nq == 0 && ws.lv.nr == 0) {
     hipLaunchKernelGGL((k_aggregate<false>), dim3(ws.groups, ws.AS), dim3(kBlock), 0, st, ws, gt_old, gt_new, xu);
     return hipGetLastError();
   }

@@ -16,7 +16,7 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libadacgd.so")
 
-TOPK, QUANT, QUANT_BLOCK = 0, 1, 2      # a QUANT_BLOCK level is (QUANT_BLOCK, (b, B))
+TOPK, QUANT, QUANT_BLOCK, RANK = 0, 1, 2, 3      # levels: (QUANT_BLOCK, (b, B)), (RANK, (K, c))
 GRAD_LOGISTIC, GRAD_EXTERNAL, DIFF_EXTERNAL, GRAD_LOGISTIC_CSR = 0, 1, 2, 3
 INIT_FULLGRAD, INIT_ZERO, INIT_COMPRESSED = 0, 1, 2
 FLAG_ANY_LEVEL_ORDER, FLAG_RETAIN_EXT, FLAG_KERNEL_TIMING, FLAG_TWO_PASS, FLAG_OVERLAP = 1, 2, 4, 8, 16
@@ -25,11 +25,12 @@ MAX_LEVELS = 16
 (F_X, F_G, F_GTILDE, F_GTILDE_PREV, F_GI, F_PREV_GRAD, F_LEVEL, F_SQNORM, F_D, F_ERR, F_MSG_COUNT, F_MSG_IDX,
  F_MSG_VAL, F_M_LEVEL, F_M_SQNORM, F_M_D, F_M_ERR, F_M_MSG_COUNT, F_M_MSG_IDX, F_M_MSG_VAL, F_STEP, F_LEVEL_HIST,
  F_M_LEVEL_HIST, F_COMM, F_QCODES, F_QSCALE, F_KERNEL_MS, F_GRAD, F_REPAIRS, F_ESTIMATOR_ERR,
- F_CANDIDATES, F_QBSCALE) = range(32)
+ F_CANDIDATES, F_QBSCALE, F_RANK_SPECTRUM) = range(33)
 
 KERNELS = ["xupdate", "grad_margin", "grad_cols", "aggregate",
            "w_sample", "w_scan", "w_filter", "w_gather", "w_select", "w_tally", "w_compact", "w_qapply",
-           "m_sample", "m_scan", "m_filter", "m_gather", "m_select", "m_tally", "m_compact", "m_qapply"]
+           "m_sample", "m_scan", "m_filter", "m_gather", "m_select", "m_tally", "m_compact", "m_qapply",
+           "w_rank", "m_rank"]
 
 EXPORTS = ["adacgd_workspace_bytes", "adacgd_init", "adacgd_init_static", "adacgd_step", "adacgd_state", "adacgd_set_state",
            "adacgd_destroy", "adacgd_last_error"]
@@ -102,8 +103,8 @@ def _levels(levels):
     arr = (Level * max(1, len(levels)))()
     for j, (kind, param) in enumerate(levels):
         block = 0
-        if int(kind) == QUANT_BLOCK:
-            param, block = param                   # (bits, block length)
+        if int(kind) in (QUANT_BLOCK, RANK):
+            param, block = param                   # (bits, block length) / (rank, columns)
         arr[j].kind, arr[j].block, arr[j].param = int(kind), int(block), int(param)
     return arr
 
@@ -310,6 +311,9 @@ class AdaCGD:
             return self._get(field, (n,), f32)
         if field == F_QBSCALE:
             return self._get(field, (n, (d + 63) // 64), f32)
+        if field == F_RANK_SPECTRUM:
+            cols = [p[1] for k, p in self.worker_levels if k == RANK]
+            return self._get(field, (n, cols[0]), f64)
         if field == F_KERNEL_MS:
             return self._get(field, (2, len(KERNELS)), f64)
         raise ValueError(field)

@@ -30,6 +30,13 @@ def _cfg(**kw):
     return E.make_config(**base)
 
 
+def test_new_level_kinds_are_accepted():
+    base = E.adacgd_workspace_bytes(_cfg(d=4096)[0])
+    blk = E.adacgd_workspace_bytes(_cfg(d=4096, worker_levels=[(E.TOPK, 4), (E.QUANT_BLOCK, (4, 256))])[0])
+    rnk = E.adacgd_workspace_bytes(_cfg(d=4096, worker_levels=[(E.RANK, (1, 16)), (E.RANK, (8, 16)), (E.TOPK, 4096)])[0])
+    assert blk > base and rnk > base
+
+
 def test_workspace_size_is_reported_and_grows_with_problem():
     a = E.adacgd_workspace_bytes(_cfg()[0])
     b = E.adacgd_workspace_bytes(_cfg(n=8, d=100000)[0])
@@ -52,6 +59,14 @@ def test_workspace_size_is_reported_and_grows_with_problem():
     (dict(worker_triggers=[(1.0, 0.0), (1.0, -0.1)]), 1),
     (dict(worker_triggers=[(float("inf"), 0.0), (1.0, 0.0)]), 1),
     (dict(master_triggers=[(0.0, float("nan"))]), 1),
+    (dict(worker_levels=[(E.QUANT_BLOCK, (4, 100))]), 1),          # block length not a power of two
+    (dict(worker_levels=[(E.QUANT_BLOCK, (4, 32))]), 1), (dict(worker_levels=[(E.QUANT_BLOCK, (4, 4096))]), 1),
+    (dict(worker_levels=[(E.QUANT_BLOCK, (1, 64))]), 1),
+    (dict(worker_levels=[(E.RANK, (2, 16))]), 1),                  # d = 100 is not a multiple of 16
+    (dict(d=512, worker_levels=[(E.RANK, (2, 8))]), 1), (dict(d=512, worker_levels=[(E.RANK, (17, 16))]), 1),
+    (dict(d=512, worker_levels=[(E.RANK, (2, 32))]), 1),           # fewer rows than columns
+    (dict(d=4096, worker_levels=[(E.RANK, (2, 16)), (E.RANK, (4, 32))]), 1),   # two column counts
+    (dict(d=512, worker_levels=[(E.RANK, (8, 16)), (E.RANK, (2, 16))]), 2),    # alpha = K/c not ascending
 ])
 def test_bad_configurations_are_rejected(kw, code):
     with pytest.raises(E.AdaCGDError) as ei:
@@ -132,7 +147,8 @@ def test_header_is_plain_c_and_matches_the_binding(tmp_path):
         "int main(void) {\n"
         '  printf("%zu %zu %zu\\n", sizeof(adacgd_config), sizeof(adacgd_level), sizeof(adacgd_trigger));\n'
         + "".join('  printf("%%zu\\n", offsetof(adacgd_config, %s));\n' % renamed.get(f, f) for f in fields)
-        + "  return (int)(ADACGD_NUM_KERNELS - 20 + ADACGD_F_ESTIMATOR_ERR - 29);\n}\n")
+        + "  return (int)(ADACGD_NUM_KERNELS - %d + ADACGD_F_ESTIMATOR_ERR - %d + ADACGD_F_RANK_SPECTRUM - %d"
+          " + ADACGD_RANK - %d);\n}\n" % (len(E.KERNELS), E.F_ESTIMATOR_ERR, E.F_RANK_SPECTRUM, E.RANK))
     exe = tmp_path / "abi"
     subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
                     str(src), "-o", str(exe)], check=True)

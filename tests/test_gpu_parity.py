@@ -1101,3 +1101,90 @@ def test_block_wise_quantiser_levels_bit_exact(n, d, flags, blocks):
                 int(orc.level_hist_w[j]) * O.AdaCGDOracle.message_bits(j, wl, d) for j in range(len(wl) + 1))
         eng.close()
     assert any(k == O.QUANT_BLOCK for k, _ in seen), seen
+
+
+def compare_step_rank(eng, orc, res, rm, tag, cols):
+    """Comparison of one step when the level set holds Rank-K levels.  The projector comes from an
+    eigen-decomposition on one side and a library SVD on the other: the fp64 products X P agree to about
+    1e-13 and are then rounded to fp32, so C(v) -- and with it the estimators and everything downstream --
+    agrees bit for bit except where that difference straddles an fp32 rounding boundary (one unit in the
+    last place, rarely).  Levels must agree; reductions to 1e-12, the Rank-K errors and spectrum to 1e-9;
+    vectors to 1e-6 of their largest element with at most one coordinate in a thousand differing at all."""
+    E = _eng()
+    if min_margin(res + ([rm] if rm is not None else [])) < 1e-7:
+        raise NearTie(repr(tag))
+    lev = eng.state(E.F_LEVEL)
+    S, D, err = eng.state(E.F_SQNORM), eng.state(E.F_D), eng.state(E.F_ERR)
+    spec = eng.state(E.F_RANK_SPECTRUM)
+    assert lev.tolist() == [r.level for r in res], (tag, "levels")
+    for i, r in enumerate(res):
+        assert abs(S[i] - r.S) <= RED_RTOL * max(r.S, 1e-300) and abs(D[i] - r.D) <= RED_RTOL * max(r.D, 1e-300), (tag, i)
+        if r.level == 0:
+            continue
+        for j, e in enumerate(r.err):
+            tol = 1e-9 if orc.wl[j][0] == O.RANK else RED_RTOL
+            assert abs(err[i, j] - e) <= tol * max(e, r.S * 1e-6, 1e-300), (tag, i, j, err[i, j], e)
+        if r.sigma is not None:
+            lam = r.sigma.astype(np.float64) ** 2
+            assert np.all(np.diff(spec[i]) <= 0)
+            assert np.abs(spec[i] - lam).max() <= 1e-9 * lam[0], (tag, i, "spectrum")
+    for name, got, want in (("g_i", eng.state(E.F_GI), orc.gi), ("g~", eng.state(E.F_GTILDE), orc.gt),
+                            ("g", eng.state(E.F_G), orc.g), ("x", eng.state(E.F_X), orc.x)):
+        assert_close_rel(got, want, 1e-6, (tag, name))
+        assert np.mean(bits(got) != bits(want)) <= 1e-3, (tag, name, "coordinates that differ")
+    if rm is not None:
+        assert int(eng.state(E.F_M_LEVEL)[0]) == rm.level, (tag, "master level")
+
+
+@pytest.mark.parametrize("n,rows,c,mode", [(3, 160, 16, "grad"), (2, 300, 32, "grad"), (2, 1000, 64, "grad"),
+                                           (3, 4 * 8192 // 16 + 5, 16, "diff"), (1, 64, 64, "grad")])
+def test_rank_k_levels_match_the_oracle(n, rows, c, mode):
+    """Level sets with Rank-K levels (the argument read as a rows x c matrix, truncated SVD) next to Top-K
+    levels, worker and master side, for every supported column count; gradients with a few dominant
+    directions plus noise, so that the cascade stops at different ranks."""
+    E = _eng()
+    d = rows * c
+    rng = np.random.default_rng(rows + c)
+    wl = [(O.RANK, (1, c)), (O.TOPK, max(1, d // 40)), (O.RANK, (3, c)), (O.RANK, (c // 2, c)), (O.TOPK, d)]
+    ml = [(O.RANK, (2, c)), (O.TOPK, max(1, d // 10))]
+
+    def structured():
+        k = 4
+        X = (rng.standard_normal((n, rows, k)) * np.array([8.0, 4.0, 2.0, 1.0])) @ rng.standard_normal((n, k, c))
+        return (X + 0.3 * rng.standard_normal((n, rows, c))).reshape(n, d).astype(np.float32)
+
+    steps = 4
+    grads = [structured() for _ in range(steps + 1)]
+    for t in range(1, steps + 1):
+        grads[t] = (grads[t - 1] + grads[t] * np.float32(10.0 ** rng.uniform(-1.5, 0))).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    seen = set()
+    for zeta in (0.0, 0.02, 0.3, 2.0):
+        kw = dict(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zeta, master_levels=ml, zeta_master=0.05)
+        orc = O.AdaCGDOracle(**kw)
+        if mode == "diff":
+            orc.init(x0, None, O.INIT_ZERO)
+            eng = E.AdaCGD(grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), flags=E.FLAG_ANY_LEVEL_ORDER, **kw)
+        else:
+            orc.init(x0, grads[0], O.INIT_ZERO)
+            eng = E.AdaCGD(grad_mode=E.GRAD_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), grad0=_cuda(grads[0]),
+                           flags=E.FLAG_ANY_LEVEL_ORDER, **kw)
+        with until_near_tie(("rank", n, rows, c, mode, zeta)):
+            for t in range(1, steps + 1):
+                if mode == "diff":
+                    Dt = np.sum(grads[t].astype(np.float64) ** 2, axis=1) * 10.0 ** rng.uniform(-2, 1, n)
+                    res, rm = orc.step(diffs=grads[t], D=Dt)
+                    eng.step(_cuda(grads[t]), _cuda(Dt))
+                else:
+                    res, rm = orc.step(grads=grads[t])
+                    eng.step(_cuda(grads[t]))
+                compare_step_rank(eng, orc, res, rm, ("rank", n, rows, c, mode, zeta, t), c)
+                seen.update(wl[r.level - 1] for r in res if r.level > 0)
+                # put the engine's state into the oracle: later steps then start from identical vectors
+                orc.gi, orc.gt, orc.gt_prev = eng.state(E.F_GI), eng.state(E.F_GTILDE), eng.state(E.F_GTILDE_PREV)
+                orc.g, orc.x = eng.state(E.F_G), eng.state(E.F_X)
+            assert eng.state(E.F_LEVEL_HIST).tolist() == orc.level_hist_w.tolist()
+            assert eng.state(E.F_COMM).tolist()[1] == sum(
+                int(orc.level_hist_w[j]) * O.AdaCGDOracle.message_bits(j, wl, d) for j in range(len(wl) + 1))
+        eng.close()
+    assert any(k == O.RANK for k, _ in seen), seen
