@@ -193,6 +193,75 @@ def extra_kernel_stress(E, W, torch, counters, steps=50, warmup=4):
                     "memory-side cache, so HBM traffic is below the algorithmic bytes"}
 
 
+def extra_block_quant(E, W, torch, steps=50, warmup=4):
+    """Secondary workload: the kernel-stress vectors with block-wise quantiser levels (one scale per 256 coordinates)."""
+    wk = W.kernel_stress_blockwise()
+    pool = [W.kernel_stress_diffs(wk, t) for t in range(4)]
+    dv = [(torch.from_numpy(v).cuda(), torch.from_numpy(D).cuda()) for v, D in pool]
+    x0 = torch.zeros(wk.d, dtype=torch.float32, device="cuda")
+    eng = E.AdaCGD(n=wk.n, d=wk.d, gamma=0.1, worker_levels=wk.worker_levels, zeta_worker=wk.zeta_worker,
+                   master_levels=wk.master_levels, zeta_master=0.0, grad_mode=E.DIFF_EXTERNAL,
+                   init_mode=E.INIT_ZERO, x0=x0, seed=wk.seed, flags=E.FLAG_KERNEL_TIMING)
+    dt, hist, kms = _timed_steps(eng, E, torch, lambda t: eng.step(*dv[t % 4]), warmup, steps)
+    eng.close()
+    sent = 0.0
+    for j in range(1, len(hist)):
+        kind, param = wk.worker_levels[j - 1]
+        sent += float(hist[j]) * (12.0 * param if kind == 0 else wk.d * (8.0 + param[0] / 8.0) + 4.0 * wk.d / param[1])
+    alg = 4.0 * wk.n * wk.d + sent / steps
+    group = ["w_scan", "w_filter", "w_gather", "w_select", "w_tally", "w_compact", "w_qapply"]
+    return {"workload": "kernel stress with block-wise quantisers: n=%d, d=%d, levels %s, master Top-%d"
+                        % (wk.n, wk.d, wk.worker_levels, wk.master_levels[0][1]),
+            "steps": steps, "ms_per_step": dt / steps * 1e3, "floats_per_sec": wk.n * wk.d * steps / dt,
+            "zeta_worker": wk.zeta_worker,
+            "level_histogram_skip_then_levels": [int(v) for v in hist], "kernels_avg_ms": kms,
+            "roofline": _two_ceilings(kms, group, alg, wk.n * wk.d, None),
+            "note": "one stream, HIP events around every kernel; no instruction counters were taken for this workload"}
+
+
+def extra_rank_k(E, W, torch, steps=20, warmup=3):
+    """Secondary workload: matrix-shaped gradients (16384 x 64 per worker) with Rank-K levels."""
+    wk = W.matrix_shaped()
+    gen = W.MatrixShapedGrads(wk)
+    g0 = torch.from_numpy(gen.next()).cuda()
+    pool = [torch.from_numpy(gen.next()).cuda() for _ in range(4)]
+    x0 = torch.zeros(wk.d, dtype=torch.float32, device="cuda")
+    eng = E.AdaCGD(n=wk.n, d=wk.d, gamma=0.1, worker_levels=wk.worker_levels, zeta_worker=wk.zeta_worker,
+                   master_levels=wk.master_levels, zeta_master=0.0, grad_mode=E.GRAD_EXTERNAL,
+                   init_mode=E.INIT_FULLGRAD, x0=x0, grad0=g0, flags=E.FLAG_KERNEL_TIMING | E.FLAG_RETAIN_EXT)
+    for t in range(warmup):
+        eng.step(pool[t % 4])
+    torch.cuda.synchronize()
+    eng.kernel_ms()
+    h0 = eng.state(E.F_LEVEL_HIST).astype(np.int64)
+    t0 = time.perf_counter()
+    for t in range(warmup, warmup + steps):
+        eng.step(pool[t % 4])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    hist = eng.state(E.F_LEVEL_HIST).astype(np.int64) - h0
+    raw = eng.kernel_ms()
+    eng.close()
+    per_step = {k: round(ms / steps, 5) for k, (ms, cnt) in raw.items() if cnt}      # summed over the launches of a step
+    c, nr = wk.cols, sum(1 for k, _ in wk.worker_levels if k == W.RANK)
+    active = float(hist[1:].sum()) / steps                      # workers per step that did not skip
+    applied = float(sum(hist[j] for j in range(1, len(hist)) if wk.worker_levels[j - 1][0] == W.RANK)) / steps
+    # fp64 flops of the Rank-K kernels: Gram matrix 2 d c, one projection 2 d c per Rank-K level for the
+    # realised errors and one more for the level applied (the c x c eigen-decomposition is negligible)
+    flops = 2.0 * wk.d * c * (active * (1 + nr) + applied)
+    t_rank = per_step.get("w_rank", 0.0) * 1e-3
+    return {"workload": "matrix-shaped gradients: n=%d workers, %d x %d per worker (d=%d), shared directions + noise, "
+                        "levels %s, master Top-%d" % (wk.n, wk.rows, wk.cols, wk.d, wk.worker_levels, wk.master_levels[0][1]),
+            "steps": steps, "ms_per_step": dt / steps * 1e3, "floats_per_sec": wk.n * wk.d * steps / dt,
+            "zeta_worker": wk.zeta_worker,
+            "level_histogram_skip_then_levels": [int(v) for v in hist], "kernels_ms_per_step": per_step,
+            "roofline": {"bound": "alu", "kernel": "w_rank (Gram matrix, eigen-decomposition, projections)",
+                         "achieved": flops / t_rank / 1e12 if t_rank else None, "peak": 78.6, "unit": "TFLOP/s (fp64)",
+                         "frac": flops / t_rank / 1e12 / 78.6 if t_rank else None, "traffic": None,
+                         "fp64_flops_per_step": flops, "ms_per_step": t_rank * 1e3},
+            "note": "one stream, HIP events around every kernel"}
+
+
 def extra_federated(E, W, torch, n, counters, steps=10, warmup=2):
     """Secondary workload: logistic-regression shards (engine computes the gradients), d=65536, 32 samples each."""
     wl = W.federated(n=n)
@@ -312,7 +381,7 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the zeta sweep of the main workload")
     ap.add_argument("--federated-n", type=int, default=1000,
                     help="workers of the secondary federated workload (1000 = the full configuration, 8.4 GB of features)")
-    ap.add_argument("--secondary", choices=["kernel_stress", "federated", "sparse_features"],
+    ap.add_argument("--secondary", choices=["kernel_stress", "federated", "sparse_features", "block_quant", "rank_k"],
                     help="run only this secondary workload and print its record (for profiling it on its own)")
     ap.add_argument("--no-overlap", action="store_true", help="skip the two-stream run")
     args = ap.parse_args()
@@ -342,7 +411,9 @@ def main():
     if args.secondary:
         rec = {"kernel_stress": lambda: extra_kernel_stress(E, W, torch, counters),
                "federated": lambda: extra_federated(E, W, torch, args.federated_n, counters),
-               "sparse_features": lambda: extra_sparse_features(E, W, torch)}[args.secondary]()
+               "sparse_features": lambda: extra_sparse_features(E, W, torch),
+               "block_quant": lambda: extra_block_quant(E, W, torch),
+               "rank_k": lambda: extra_rank_k(E, W, torch)}[args.secondary]()
         print(json.dumps({"secondary_workload": rec}))
         return
     n, d = wk.n, wk.d
@@ -447,6 +518,8 @@ def main():
     other = []
     if not args.no_extras:
         other.append(extra_kernel_stress(E, W, torch, counters))
+        other.append(extra_block_quant(E, W, torch))
+        other.append(extra_rank_k(E, W, torch))
         other.append(extra_federated(E, W, torch, args.federated_n, counters))
         other.append(extra_small_logistic(E, W, torch, W.tiny(), 2000))
         other.append(extra_small_logistic(E, W, torch, W.sparse_logreg(), 2000))

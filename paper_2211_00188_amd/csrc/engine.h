@@ -120,7 +120,6 @@ struct NodeSet {
   int GR;               // blocks per node of the Rank-K kernels
   double* gram_part;    // [nn][GR][c*c]  partial Gram matrices X^T X of the blocks
   double* gram;         // [nn][c*c]
-  double* rk_vec;       // [nn][c*c]      eigenvectors of X^T X in columns
   double* rk_lambda;    // [nn][c]        its eigenvalues (squared singular values of X), descending
   double* rk_P;         // [nn][nr][c*c]  projector onto the K leading right singular vectors, per Rank-K level
   double* rk_part;      // [nn][GR][nr]   partial realised errors

@@ -210,7 +210,6 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
     const size_t cc = (size_t)ns.lv.rcols * ns.lv.rcols, nr = ns.lv.nr;
     ns.gram_part = c.take<double>(nn * ns.GR * cc);
     ns.gram = c.take<double>(nn * cc);
-    ns.rk_vec = c.take<double>(nn * cc);
     ns.rk_lambda = c.take<double>(nn * ns.lv.rcols);
     ns.rk_P = c.take<double>(nn * nr * cc);
     ns.rk_part = c.take<double>(nn * ns.GR * nr);
@@ -243,8 +242,8 @@ void shape_nodeset(NodeSet& ns, int nn, int64_t d, bool force_two_pass) {
     ns.onepass = 0;
     ns.small = 0;
     const int64_t rows = d / ns.lv.rcols;
-    int64_t gr = (rows + 63) / 64;                 // at least 64 rows per block, about 1024 blocks in all, at most 64 per node
-    const int64_t cap = std::min<int64_t>(64, std::max<int64_t>(1, 1024 / nn));
+    int64_t gr = (rows + 63) / 64;                 // at least 64 rows per block, about 512 blocks in all, at most 64 per node
+    const int64_t cap = std::min<int64_t>(64, std::max<int64_t>(1, 512 / nn));
     ns.GR = (int)std::max<int64_t>(1, std::min(gr, cap));
   }
   // streaming kernels: about 5120 blocks in all for the fused scan (several short blocks per CU

@@ -4,8 +4,8 @@
 // P_K the projector onto the K leading right singular vectors.  Per node:
 //   gram      : G = X^T X (c x c, fp64: products of fp32 values are exact, sums in fp64), block partial
 //               sums added in block order by the node's last block
-//   eig       : one block diagonalises G by cyclic Jacobi rotations in a parallel (round-robin) order,
-//               sorts the eigenvalues (squared singular values) and forms P_K for every Rank-K level
+//   eig       : one block diagonalises G by cyclic Jacobi rotations in a parallel (round-robin) order, all in
+//               LDS, sorts the eigenvalues (squared singular values) and forms P_K for every Rank-K level
 //   rank_err  : realised error || v - fl32(X P_K) ||^2 of every Rank-K level (left side of the trigger,
 //               Eq. (10), evaluated on the rounded message like every other level's)
 //   rank_apply: for nodes whose chosen level is a Rank-K level: C(v) = fl32(X P_K), h <- h + C(v)
@@ -91,40 +91,61 @@ __global__ __launch_bounds__(kBlock) void k_gram(NodeSet ns, PassArgs a) {
 // ---------------------------------------------------------------------------
 // eig: cyclic Jacobi on the c x c Gram matrix, one block per node.  A round rotates c/2 disjoint
 // index pairs at once (round-robin order: c - 1 rounds visit every pair once); a sweep is c - 1
-// rounds.  Sweeps stop when the off-diagonal mass has vanished against the diagonal, at most kMaxSweeps.
+// rounds.  Sweeps stop when the off-diagonal mass has reached its rounding floor, at most kMaxSweeps.
 // ---------------------------------------------------------------------------
 constexpr int kMaxSweeps = 40;
 
+// one work item per thread in the matrix update of a round: (c/2)^2 threads, at least one block of 256
 template <int C>
-__global__ __launch_bounds__(kBlock) void k_eig(NodeSet ns) {
-  __shared__ double A[C][C];
+constexpr int eig_threads() { return (C / 2) * (C / 2) > kBlock ? (C / 2) * (C / 2) : kBlock; }
+
+template <int C>
+__global__ __launch_bounds__(eig_threads<C>()) void k_eig(NodeSet ns) {
+  constexpr int NT = eig_threads<C>();
+  // Two copies of the matrix (a round reads one and writes the other: every new entry is a combination of
+  // four old ones, so no barrier is needed between the row and the column half of the rotation) and the
+  // eigenvector matrix, rows padded by one entry so that walking a column touches every LDS bank.
+  __shared__ double Abuf[2][C][C + 1];
+  __shared__ double V[C][C + 1];
   __shared__ double s_cs[C / 2], s_sn[C / 2];
   __shared__ int s_p[C / 2], s_q[C / 2];
-  __shared__ double red[4];
+  __shared__ double red[2][NT / 64];
   __shared__ int s_rank[C];
   __shared__ int s_stop;
   const int node = blockIdx.x, tid = threadIdx.x;
   if (ns.skip[node] != 0) return;
   const double* __restrict__ G = ns.gram + (size_t)node * (C * C);
-  double* __restrict__ V = ns.rk_vec + (size_t)node * (C * C);     // eigenvectors in columns (global, L2-resident)
-  for (int e = tid; e < C * C; e += kBlock) {
-    A[e / C][e % C] = G[e];
-    V[e] = (e / C == e % C) ? 1.0 : 0.0;
+  for (int e = tid; e < C * C; e += NT) {
+    Abuf[0][e / C][e % C] = G[e];
+    V[e / C][e % C] = (e / C == e % C) ? 1.0 : 0.0;
   }
+  int cur = 0;
+  double off_prev = 0.0;
   __syncthreads();
   for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
     // off-diagonal against diagonal mass
     double off = 0.0, dia = 0.0;
-    for (int e = tid; e < C * C; e += kBlock) {
-      const double v = A[e / C][e % C];
+    for (int e = tid; e < C * C; e += NT) {
+      const double v = Abuf[cur][e / C][e % C];
       if (e / C == e % C) dia = fma(v, v, dia); else off = fma(v, v, off);
     }
-    off = block_sum(off, red);
-    dia = block_sum(dia, red);
-    if (tid == 0) s_stop = (off <= 1e-30 * dia) ? 1 : 0;
+    off = wave_sum(off);
+    dia = wave_sum(dia);
+    if ((tid & 63) == 0) { red[0][tid >> 6] = off; red[1][tid >> 6] = dia; }
+    __syncthreads();
+    // Convergence is quadratic until the rounding floor is reached: stop when the off-diagonal mass is
+    // negligible, or when a sweep no longer reduces it fourfold (the floor).
+    if (tid == 0) {
+      off = dia = 0.0;
+      for (int i = 0; i < NT / 64; ++i) { off += red[0][i]; dia += red[1][i]; }
+      s_stop = (off <= 1e-34 * dia || (sweep >= 3 && off >= 0.25 * off_prev)) ? 1 : 0;
+      off_prev = off;
+    }
     __syncthreads();
     if (s_stop) break;                            // (the same in every thread)
     for (int m = 0; m < C - 1; ++m) {
+      double (*A)[C + 1] = Abuf[cur];
+      double (*B)[C + 1] = Abuf[cur ^ 1];
       if (tid < C / 2) {
         int p, q;
         if (tid == 0) { p = C - 1; q = m; }
@@ -141,30 +162,35 @@ __global__ __launch_bounds__(kBlock) void k_eig(NodeSet ns) {
         s_p[tid] = p; s_q[tid] = q; s_cs[tid] = cs; s_sn[tid] = sn;
       }
       __syncthreads();
-      for (int e = tid; e < (C / 2) * C; e += kBlock) {       // rows p, q of every pair
-        const int k = e / C, j = e % C;
-        const int p = s_p[k], q = s_q[k];
-        const double cs = s_cs[k], sn = s_sn[k];
-        const double ap = A[p][j], aq = A[q][j];
-        A[p][j] = cs * ap - sn * aq;
-        A[q][j] = sn * ap + cs * aq;
+      // B = J^T A J, one 2 x 2 block (rows of pair ka, columns of pair kb) per work item
+      for (int e = tid; e < (C / 2) * (C / 2); e += NT) {
+        const int ka = e / (C / 2), kb = e % (C / 2);
+        const int p = s_p[ka], q = s_q[ka], r = s_p[kb], u = s_q[kb];
+        const double ca = s_cs[ka], sa = s_sn[ka], cb = s_cs[kb], sb = s_sn[kb];
+        const double apr = A[p][r], apu = A[p][u], aqr = A[q][r], aqu = A[q][u];
+        // rows first (J^T A) ...
+        const double tpr = ca * apr - sa * aqr, tpu = ca * apu - sa * aqu;
+        const double tqr = sa * apr + ca * aqr, tqu = sa * apu + ca * aqu;
+        // ... then columns
+        B[p][r] = cb * tpr - sb * tpu;
+        B[p][u] = sb * tpr + cb * tpu;
+        B[q][r] = cb * tqr - sb * tqu;
+        B[q][u] = sb * tqr + cb * tqu;
       }
-      __syncthreads();
-      for (int e = tid; e < (C / 2) * C; e += kBlock) {       // columns p, q of every pair, and of V
+      for (int e = tid; e < (C / 2) * C; e += NT) {       // V <- V J: columns p, q of every pair
         const int k = e / C, i = e % C;
         const int p = s_p[k], q = s_q[k];
         const double cs = s_cs[k], sn = s_sn[k];
-        const double ap = A[i][p], aq = A[i][q];
-        A[i][p] = cs * ap - sn * aq;
-        A[i][q] = sn * ap + cs * aq;
-        const double vp = V[i * C + p], vq = V[i * C + q];
-        V[i * C + p] = cs * vp - sn * vq;
-        V[i * C + q] = sn * vp + cs * vq;
+        const double vp = V[i][p], vq = V[i][q];
+        V[i][p] = cs * vp - sn * vq;
+        V[i][q] = sn * vp + cs * vq;
       }
+      cur ^= 1;
       __syncthreads();
     }
   }
   __syncthreads();
+  double (*A)[C + 1] = Abuf[cur];
   // eigenvalues in descending order (ties by index): position of each, then the sorted list
   if (tid < C) {
     const double li = A[tid][tid];
@@ -181,11 +207,11 @@ __global__ __launch_bounds__(kBlock) void k_eig(NodeSet ns) {
   for (int r = 0; r < ns.lv.nr; ++r) {
     const int K = ns.lv.rK[r];
     double* __restrict__ P = ns.rk_P + ((size_t)node * ns.lv.nr + r) * (C * C);
-    for (int e = tid; e < C * C; e += kBlock) {
+    for (int e = tid; e < C * C; e += NT) {
       const int i = e / C, j = e % C;
       double t = 0.0;
       for (int k = 0; k < C; ++k)
-        if (s_rank[k] < K) t = fma(V[i * C + k], V[j * C + k], t);
+        if (s_rank[k] < K) t = fma(V[i][k], V[j][k], t);
       P[e] = t;
     }
   }
@@ -315,7 +341,7 @@ static hipError_t launch_rank_c(int which, const NodeSet& ns, const PassArgs& a,
       else hipLaunchKernelGGL((k_gram<false, C>), grid, block, 0, st, ns, a);
       break;
     case 1:
-      hipLaunchKernelGGL((k_eig<C>), dim3(ns.nn), block, 0, st, ns);
+      hipLaunchKernelGGL((k_eig<C>), dim3(ns.nn), dim3(eig_threads<C>()), 0, st, ns);
       break;
     case 2:
       if (a.diff) hipLaunchKernelGGL((k_rank_err<true, C>), grid, block, 0, st, ns, a);

@@ -1731,8 +1731,10 @@ template <bool DIFF, bool VEC>
 static void launch_filter_q(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   const dim3 grid(ns.G, ns.nn), block(kBlock);
   const int nq = ns.lv.nq;
-  if (ns.lv.nqb > 0) {       // block-wise quantiser levels: the general kernel, or the one for a single level
+  if (ns.lv.nqb > 0) {       // some of the quantiser levels are block-wise
     if (VEC && nq == 1) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 1 : kMaxLevels, true>), grid, block, 0, st, ns, a);
+    else if (VEC && nq == 2) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 2 : kMaxLevels, true>), grid, block, 0, st, ns, a);
+    else if (VEC && nq == 3) hipLaunchKernelGGL((k_filter<DIFF, VEC, VEC ? 3 : kMaxLevels, true>), grid, block, 0, st, ns, a);
     else hipLaunchKernelGGL((k_filter<DIFF, VEC, kMaxLevels, true>), grid, block, 0, st, ns, a);
     return;
   }

@@ -18,6 +18,8 @@ import numpy as np
 
 TOPK = 0
 QUANT = 1
+QUANT_BLOCK = 2     # level (QUANT_BLOCK, (bits, block length))
+RANK = 3            # level (RANK, (rank, columns))
 
 
 def _rng(seed):
@@ -176,6 +178,45 @@ def kernel_stress_diffs(wl: VectorWorkload, step: int):
     S = np.sum(v.astype(np.float64) ** 2, axis=1)
     D = S * 10.0 ** rng.uniform(-3.0, 0.2, size=wl.n) / max(wl.zeta_worker, 1e-30)
     return v, D
+
+
+def kernel_stress_blockwise(seed=3, n=32, d=1 << 20, T=50, zeta=1.0, block=256) -> VectorWorkload:
+    """The kernel-stress vectors with block-wise quantisers (one scale per `block` coordinates) in place of
+    the whole-vector ones, in the cascade's order at d = 2^20 and block = 256."""
+    lv = [(TOPK, ratio_K(0.001, d)), (TOPK, ratio_K(0.01, d)), (QUANT_BLOCK, (2, block)), (TOPK, ratio_K(0.1, d)),
+          (QUANT_BLOCK, (4, block)), (QUANT_BLOCK, (8, block))]
+    return VectorWorkload("kernel_stress_blockwise", n, d, lv, [(TOPK, ratio_K(0.01, d))], zeta, 0.0, T, seed)
+
+
+def matrix_shaped(seed=7, n=16, rows=16384, cols=64, T=20, zeta=1.0) -> VectorWorkload:
+    """Matrix-shaped gradients (a layer's rows x cols weight gradient, flattened row-major) with Rank-K
+    levels K in {1, 4, 16} next to the identity; master Top-K at 1 %."""
+    d = rows * cols
+    lv = [(RANK, (1, cols)), (RANK, (min(4, cols), cols)), (RANK, (min(16, cols), cols)), (TOPK, d)]
+    lv = list(dict.fromkeys(lv))
+    wl = VectorWorkload("matrix_shaped", n, d, lv, [(TOPK, ratio_K(0.01, d))], zeta, 0.0, T, seed)
+    wl.rows, wl.cols = rows, cols
+    return wl
+
+
+class MatrixShapedGrads:
+    """grad_i^t = L_i^t R + 0.3 E_i^t as a rows x cols matrix: R (8 x cols) is a fixed set of shared
+    directions with weights 8, 4, 2, 1, 1/2, ...; the per-worker left factors follow an AR(1) drift
+    L^t = 0.9 L^{t-1} + sqrt(1 - 0.81) xi^t; E is fresh N(0,1) noise.  Returns [n, d] float32."""
+
+    def __init__(self, wl: VectorWorkload, k=8):
+        self.wl, self.k = wl, k
+        rng = _rng([wl.seed, 2_000_003])
+        self.R = (rng.standard_normal((k, wl.cols)) * (8.0 * 0.5 ** np.arange(k))[:, None]).astype(np.float32)
+        self.rng = _rng([wl.seed, 2_000_029])
+        self.L = self.rng.standard_normal((wl.n, wl.rows, k), dtype=np.float32)
+
+    def next(self):
+        wl = self.wl
+        out = (self.L @ self.R + np.float32(0.3) * self.rng.standard_normal((wl.n, wl.rows, wl.cols), dtype=np.float32))
+        xi = self.rng.standard_normal(self.L.shape, dtype=np.float32)
+        self.L = (np.float32(0.9) * self.L + np.float32(math.sqrt(1 - 0.81)) * xi).astype(np.float32)
+        return np.ascontiguousarray(out.reshape(wl.n, wl.d), dtype=np.float32)
 
 
 def model_sized(seed=4, n=16, d=11_200_000, T=20, zeta=1.0) -> VectorWorkload:

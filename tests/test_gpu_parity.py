@@ -1103,12 +1103,13 @@ def test_block_wise_quantiser_levels_bit_exact(n, d, flags, blocks):
     assert any(k == O.QUANT_BLOCK for k, _ in seen), seen
 
 
-def compare_step_rank(eng, orc, res, rm, tag, cols):
+def compare_step_rank(eng, orc, res, rm, tag, vmax):
     """Comparison of one step when the level set holds Rank-K levels.  The projector comes from an
     eigen-decomposition on one side and a library SVD on the other: the fp64 products X P agree to about
     1e-13 and are then rounded to fp32, so C(v) -- and with it the estimators and everything downstream --
     agrees bit for bit except where that difference straddles an fp32 rounding boundary (one unit in the
-    last place, rarely).  Levels must agree; reductions to 1e-12, the Rank-K errors and spectrum to 1e-9;
+    last place, rarely; `vmax` = largest |v| per worker bounds what one such coordinate does to an error).
+    Levels must agree; reductions to 1e-12, the Rank-K errors and spectrum to 1e-9;
     vectors to 1e-6 of their largest element with at most one coordinate in a thousand differing at all."""
     E = _eng()
     if min_margin(res + ([rm] if rm is not None else [])) < 1e-7:
@@ -1122,8 +1123,10 @@ def compare_step_rank(eng, orc, res, rm, tag, cols):
         if r.level == 0:
             continue
         for j, e in enumerate(r.err):
-            tol = 1e-9 if orc.wl[j][0] == O.RANK else RED_RTOL
-            assert abs(err[i, j] - e) <= tol * max(e, r.S * 1e-6, 1e-300), (tag, i, j, err[i, j], e)
+            tol = (1e-9 if orc.wl[j][0] == O.RANK else RED_RTOL) * max(e, r.S * 1e-6, 1e-300)
+            if orc.wl[j][0] == O.RANK:      # plus two coordinates whose fp32 rounding of C(v) falls the other way
+                tol += 2 * 2.0 * np.sqrt(e) * 2.0 ** -23 * vmax[i]
+            assert abs(err[i, j] - e) <= tol, (tag, i, j, err[i, j], e)
         if r.sigma is not None:
             lam = r.sigma.astype(np.float64) ** 2
             assert np.all(np.diff(spec[i]) <= 0)
@@ -1178,7 +1181,8 @@ def test_rank_k_levels_match_the_oracle(n, rows, c, mode):
                 else:
                     res, rm = orc.step(grads=grads[t])
                     eng.step(_cuda(grads[t]))
-                compare_step_rank(eng, orc, res, rm, ("rank", n, rows, c, mode, zeta, t), c)
+                vmax = np.abs(grads[t]).max(axis=1) + np.abs(orc.gi).max(axis=1)
+                compare_step_rank(eng, orc, res, rm, ("rank", n, rows, c, mode, zeta, t), vmax)
                 seen.update(wl[r.level - 1] for r in res if r.level > 0)
                 # put the engine's state into the oracle: later steps then start from identical vectors
                 orc.gi, orc.gt, orc.gt_prev = eng.state(E.F_GI), eng.state(E.F_GTILDE), eng.state(E.F_GTILDE_PREV)

@@ -208,7 +208,8 @@ def test_configuration_level_sets_are_listed_in_cascade_order():
     configurations in a fixed order (they hold none of the method's arithmetic): at the
     configurations' full sizes that order is the one the AdaCGD definition asks for."""
     from paper_2211_00188_amd import workloads as W
-    for lv, d in ((W.kernel_stress_levels(1 << 20), 1 << 20), (W.federated_levels(65536), 65536)):
+    for lv, d in ((W.kernel_stress_levels(1 << 20), 1 << 20), (W.federated_levels(65536), 65536),
+                  (W.kernel_stress_blockwise().worker_levels, 1 << 20), (W.matrix_shaped().worker_levels, 16384 * 64)):
         assert O.check_levels(lv, d), lv
         al = [O.level_alpha(l, d) for l in lv]
         assert all(a < b for a, b in zip(al, al[1:]))        # strictly: the order is the only valid one
