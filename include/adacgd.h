@@ -29,6 +29,13 @@
  *  - All work is enqueued on the caller's stream; adacgd_step does not
  *    synchronise.  adacgd_state synchronises the stream before copying.
  *  - One context must not be used from two threads at once.
+ *  - Server aggregation: every coordinate's sum over the workers' messages is taken in fp64 and rounded
+ *    to fp32 once.  With Top-K levels only and at most 64 workers the messages are added in ascending
+ *    worker index (the sequential sum, reproducible for any data).  With more workers, or with quantiser
+ *    or Rank-K levels in the set, partial sums are formed in another (for dense messages fixed, for
+ *    Top-K messages unspecified) order: the fp64 sum is then the same for every order as long as the
+ *    exponents of the values met at one coordinate spread over fewer than 53 - 24 - log2(n) bits; beyond
+ *    that the last place of the fp64 sum, 29 bits below the fp32 result, may depend on the order.
  */
 #ifndef ADACGD_H
 #define ADACGD_H

@@ -119,6 +119,67 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
   }
 }
 
+// Top-K messages of at most kOrderedMax workers: the same sums taken in ASCENDING WORKER INDEX, so that the
+// result is the sequential fp64 sum whatever the data (the kernel above adds in arbitrary order, which gives
+// the same bits only while the exponents met at one coordinate spread over less than 53 - 24 - log2 n bits).
+// One block per group; the group's range of every worker's message is loaded for sixteen workers at a time
+// and the workers are then added one after the other (the coordinates of one message are distinct, so the
+// threads of a round do not meet; a barrier separates the rounds).
+constexpr int kOrderedMax = 64;
+constexpr int kAggChunk = 16;
+
+__global__ __launch_bounds__(kBlock) void k_aggregate_ordered(NodeSet ws, const float* __restrict__ gt_old,
+                                                               float* __restrict__ gt_new, IterateUpdate xu) {
+  __shared__ double acc[kWaveTile];
+  const int g = blockIdx.x, tid = threadIdx.x;
+  const int64_t d = ws.d;
+  const int64_t base = (int64_t)g * kWaveTile;
+  for (int c = tid; c < kWaveTile; c += kBlock) acc[c] = 0.0;
+  for (int i0 = 0; i0 < ws.nn; i0 += kAggChunk) {
+    uint32_t lo[kAggChunk], cnt[kAggChunk];
+    int32_t pidx[kAggChunk];
+    float pval[kAggChunk];
+#pragma unroll
+    for (int u = 0; u < kAggChunk; ++u) {
+      const int i = i0 + u;
+      lo[u] = 0; cnt[u] = 0;
+      if (i < ws.nn && __builtin_amdgcn_readfirstlane(ws.sel_slot[i]) >= 0) {
+        const uint32_t l = ws.grp_off[(size_t)i * (ws.groups + 1) + g];
+        lo[u] = l;
+        cnt[u] = __builtin_amdgcn_readfirstlane(ws.grp_off[(size_t)i * (ws.groups + 1) + g + 1] - l);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kAggChunk; ++u) {                 // first entry per thread of every range
+      pidx[u] = 0; pval[u] = 0.f;
+      if ((uint32_t)tid < cnt[u]) {
+        const size_t off = (size_t)(i0 + u) * ws.Kcap + lo[u] + tid;
+        pidx[u] = ws.msg_idx[off];
+        pval[u] = ws.msg_val[off];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kAggChunk; ++u) {
+      if (cnt[u] == 0) continue;                          // (the same in every thread)
+      __syncthreads();
+      if ((uint32_t)tid < cnt[u]) acc[pidx[u] - base] += (double)pval[u];
+      for (uint32_t e = tid + kBlock; e < cnt[u]; e += kBlock) {
+        const size_t off = (size_t)(i0 + u) * ws.Kcap + lo[u] + e;
+        acc[ws.msg_idx[off] - base] += (double)ws.msg_val[off];
+      }
+    }
+  }
+  __syncthreads();
+  const double n = (double)ws.nn;
+  for (int c = tid; c < kWaveTile; c += kBlock) {
+    if (base + c < d) {
+      const float gn = (float)((double)gt_old[base + c] + acc[c] / n);
+      gt_new[base + c] = gn;
+      if (xu.out) xu.out[base + c] = (float)((double)xu.x[base + c] - xu.gamma * (double)gn);
+    }
+  }
+}
+
 // Dense (quantised) messages: a block owns 128 coordinates, each lane two of them (one 4-byte
 // load per worker); its eight wavefronts take one eighth of the workers each, in ascending order,
 // eight workers' loads in flight at a time, and their partial sums are combined in wavefront
@@ -431,7 +492,10 @@ hipError_t launch_aggregate(const NodeSet& ws, const float* gt_old, float* gt_ne
                             hipStream_t st) {
   (void)hipGetLastError();   // drop a stale error left by earlier runtime calls of this thread
   if (ws.lv.nq == 0 && ws.lv.nr == 0) {
-    hipLaunchKernelGGL((k_aggregate<false>), dim3(ws.groups, ws.AS), dim3(kBlock), 0, st, ws, gt_old, gt_new, xu);
+    if (ws.nn <= kOrderedMax)
+      hipLaunchKernelGGL(k_aggregate_ordered, dim3(ws.groups), dim3(kBlock), 0, st, ws, gt_old, gt_new, xu);
+    else
+      hipLaunchKernelGGL((k_aggregate<false>), dim3(ws.groups, ws.AS), dim3(kBlock), 0, st, ws, gt_old, gt_new, xu);
     return hipGetLastError();
   }
   hipLaunchKernelGGL((k_aggregate<true>), dim3(ws.groups, ws.AS), dim3(kBlock), 0, st, ws, gt_old, gt_new, IterateUpdate{});

@@ -1013,10 +1013,12 @@ def test_two_contexts_interleaved_on_two_streams():
 def test_aggregation_with_wide_exponent_spread(dense):
     """Messages that put values more than 2^30 apart in magnitude on the same coordinate (per-worker scales
     from 1e-12 to 1e+12).  The oracle adds the messages of a coordinate in ascending worker index in fp64;
-    the aggregation kernels add them in another order, which can differ in the last place of the fp64 sum
-    once the exponents spread over more than 53 - 24 bits.  The aggregate is that sum divided by n, added to
-    the old value and rounded to fp32, 29 bits coarser: the results must still agree bit for bit, for Top-K
-    messages (every coordinate sent) and for dense quantised ones."""
+    for Top-K level sets with up to 64 workers so does the aggregation kernel, and the results agree bit for
+    bit whatever the data (a hundred coordinates here carry values whose sum in another order would differ
+    already in fp32).  Dense quantised messages are added as partial sums in a fixed other order, which can
+    differ in the last place of the fp64 sum once the exponents spread over more than 53 - 24 bits; the
+    aggregate is that sum divided by n, added to the old value and rounded to fp32, 29 bits coarser, and
+    must still agree bit for bit on data like these."""
     E = _eng()
     n, d = 12, 3 * 8192 + 516
     rng = np.random.default_rng(2030)
@@ -1038,6 +1040,11 @@ def test_aggregation_with_wide_exponent_spread(dense):
     with until_near_tie(("wide spread", dense)):
         for t in range(1, steps + 1):
             v = (rng.standard_normal((n, d)) * scales[:, None]).astype(np.float32)
+            if not dense:
+                # coordinates whose fp64 sum depends on the order of the additions, visibly in fp32:
+                # ((1 + 2^-60) - 1) + 2^-60 = 2^-60 in ascending worker order, 2^-59 if the two ones meet first
+                v[:, :100] = 0.0
+                v[0, :100], v[1, :100], v[2, :100], v[3, :100] = 1.0, 2.0 ** -60, -1.0, 2.0 ** -60
             if dense:
                 D = np.ones(n)
                 res, rm = orc.step(diffs=v, D=D)
