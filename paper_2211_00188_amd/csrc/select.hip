@@ -642,17 +642,28 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 // dither u in [0,1) of coordinate l: word l%4 of the block l/4, top 24 bits
 __device__ __forceinline__ float dither_of(uint32_t word) { return (float)(word >> 8) * 5.9604644775390625e-8f; }
 
-// b-bit stochastic quantiser of one coordinate: returns the signed code xi and the decoded value.
-// a = max |v| (> 0), s = magnitude levels, c = fl(a / (s (1+omega))).
-__device__ __forceinline__ float quant_one(float v, float a, float s, float c, float u, int* code) {
-  const float av = fabsf(v);
-  const float r = (av / a) * s;       // two rounded fp32 operations
+// b-bit stochastic quantiser of one coordinate from t = fl(|v| / a): the magnitude code xi (as a float) and
+// the decoded magnitude fl(xi c).  s = magnitude levels, c = fl(a / (s (1+omega))).
+__device__ __forceinline__ float quant_mag(float t, float s, float c, float u, float* xi_out) {
+  const float r = t * s;              // the second of the two rounded fp32 operations
   const float fl = floorf(r);
   const float pfrac = r - fl;
   const float xi = fl + ((u < pfrac) ? 1.f : 0.f);
-  const float mag = xi * c;
+  *xi_out = xi;
+  return xi * c;
+}
+
+// ... with the sign of v: returns the signed code and the decoded value.
+__device__ __forceinline__ float quant_ratio(float v, float t, float s, float c, float u, int* code) {
+  float xi;
+  const float mag = quant_mag(t, s, c, u, &xi);
   *code = (__float_as_uint(v) >> 31) ? -(int)xi : (int)xi;
   return copysignf(mag, v);
+}
+
+// The same with a = max |v| (> 0) given.
+__device__ __forceinline__ float quant_one(float v, float a, float s, float c, float u, int* code) {
+  return quant_ratio(v, fabsf(v) / a, s, c, u, code);
 }
 
 // Block-wise quantiser scales of one group of 2048 coordinates (one wavefront's share of a tile).
@@ -775,12 +786,18 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
               word = r4[l & 3];
             }
             const float u = dither_of(word);
+            // |v| / a once for all levels that share the whole-vector scale (a division is a dozen
+            // instructions, and the compiler does not merge the divisions of separately guarded levels)
+            const float av = fabsf(vv[c]);
+            const float tg = qa > 0.f ? av / qa : 0.f;
 #pragma unroll
             for (int q = 0; q < NQA; ++q) {
               if (EXACT || q < nq) {
-                int code;
-                const float cq = qa_l[q] > 0.f ? quant_one(vv[c], qa_l[q], ns.lv.qs[q], qc_l[q], u, &code) : 0.f;
-                const double e = dv - (double)cq;
+                float xi, t = tg;
+                if (BLK && ns.lv.qblock[q]) t = qa_l[q] > 0.f ? av / qa_l[q] : 0.f;
+                // the error of a coordinate is | |v| - decoded magnitude |: the sign is common to both
+                const float mag = qa_l[q] > 0.f ? quant_mag(t, ns.lv.qs[q], qc_l[q], u, &xi) : 0.f;
+                const double e = (double)av - (double)mag;
                 qacc[q] = fma(e, e, qacc[q]);
               }
             }
