@@ -118,10 +118,9 @@ struct NodeSet {
   double* accbuf;       // [d] fp64 sums of the sparse messages (only with quantiser levels)
   // Rank-K levels (allocated only when the level set has any; c = lv.rcols, nr = lv.nr)
   int GR;               // blocks per node of the Rank-K kernels
-  double* gram_part;    // [nn][GR][c*c]  partial Gram matrices X^T X of the blocks
-  double* gram;         // [nn][c*c]
+  double* gram_part;    // [nn][GR][c*c]  partial Gram matrices X^T X of the blocks (upper triangle, tile by tile)
   double* rk_lambda;    // [nn][c]        its eigenvalues (squared singular values of X), descending
-  double* rk_P;         // [nn][nr][c*c]  projector onto the K leading right singular vectors, per Rank-K level
+  double* rk_V;         // [nn][c*c]      its eigenvectors (right singular vectors of X) as columns, in the same order
   double* rk_part;      // [nn][GR][nr]   partial realised errors
   double* rk_err;       // [nn][nr]       realised error of every Rank-K level
   float* rdense;        // [nn][d]        C(v) of the last Rank-K message (the aggregation adds it)

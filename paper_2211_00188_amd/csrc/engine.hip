@@ -209,9 +209,8 @@ void carve_nodeset(Carver& c, NodeSet& ns) {
   if (ns.lv.nr) {
     const size_t cc = (size_t)ns.lv.rcols * ns.lv.rcols, nr = ns.lv.nr;
     ns.gram_part = c.take<double>(nn * ns.GR * cc);
-    ns.gram = c.take<double>(nn * cc);
     ns.rk_lambda = c.take<double>(nn * ns.lv.rcols);
-    ns.rk_P = c.take<double>(nn * nr * cc);
+    ns.rk_V = c.take<double>(nn * cc);
     ns.rk_part = c.take<double>(nn * ns.GR * nr);
     ns.rk_err = c.take<double>(nn * nr);
     ns.rdense = c.take<float>(nn * (size_t)ns.d);
