@@ -376,15 +376,20 @@ struct ProjLds {
       for (int v = 0; v < 4; ++v) Ys[(w * 16 + (l >> 4) + 4 * v) * ld + kb * 16 + (l & 15)] = acc[v];
     }
   }
-  // the 16 x 16 tile (wavefront's rows, column block cb) of X_K = Y V_K^T
-  __device__ d4 expand(int w, int l, int cb, int K) const {
-    d4 acc = {0.0, 0.0, 0.0, 0.0};
+  // the wavefront's 16 rows of X_K = Y V_K^T, one 16 x 16 tile per column block (independent accumulators:
+  // the matrix instructions of the c / 16 tiles follow each other without waiting)
+  __device__ void expand(int w, int l, int K, d4 (&out)[C / 16]) const {
+#pragma unroll
+    for (int cb = 0; cb < C / 16; ++cb) out[cb] = d4{0.0, 0.0, 0.0, 0.0};
     for (int kk = 0; kk < K; kk += 4) {
       const int k = kk + (l >> 4);                                     // < KP: a whole number of 16-column blocks
-      const double b = k < K ? Vs[(cb * 16 + (l & 15)) * ld + k] : 0.0;
-      acc = mma(Ys[(w * 16 + (l & 15)) * ld + k], b, acc);
+      const double y = Ys[(w * 16 + (l & 15)) * ld + k];
+      double b[C / 16];
+#pragma unroll
+      for (int cb = 0; cb < C / 16; ++cb) b[cb] = k < K ? Vs[(cb * 16 + (l & 15)) * ld + k] : 0.0;
+#pragma unroll
+      for (int cb = 0; cb < C / 16; ++cb) out[cb] = mma(y, b[cb], out[cb]);
     }
-    return acc;
   }
 };
 
@@ -399,20 +404,18 @@ __host__ __device__ inline int proj_columns(const LevelTable& lv, int only) {
 template <bool DIFF, int C>
 __global__ __launch_bounds__(kBlock) void k_rank_err(NodeSet ns, PassArgs a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  __shared__ double red[4];
+  __shared__ double s_err[4][kMaxLevels];                  // per wavefront and level
   __shared__ int s_flag;
   const int node = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63;
   if (ns.skip[node] != 0) return;
   const int nr = ns.lv.nr;
+  if (tid < 4 * kMaxLevels) s_err[tid / kMaxLevels][tid % kMaxLevels] = 0.0;
   ProjLds<C> L(lds_raw, proj_columns(ns.lv, -1));
   const int64_t d = ns.d, rows = d / C;
   const size_t row = (size_t)node * (size_t)d;
   const float* __restrict__ x = a.x + row;
   const float* __restrict__ h = a.h + row;
   L.load_vectors(ns.rk_V + (size_t)node * (C * C));
-  double err[kMaxLevels];
-#pragma unroll
-  for (int r = 0; r < kMaxLevels; ++r) err[r] = 0.0;
   const int64_t per = (rows + gridDim.x - 1) / gridDim.x;
   const int64_t rlo = (int64_t)blockIdx.x * per, rhi = min(rows, rlo + per);
   Stager<DIFF, C> stg;
@@ -423,28 +426,30 @@ __global__ __launch_bounds__(kBlock) void k_rank_err(NodeSet ns, PassArgs a) {
     __syncthreads();
     if (r0 + kRankRows < rhi) stg.fetch(x, h, r0 + kRankRows, rhi);
     L.project(w, l);          // (a wavefront reads back only its own rows of Ys, in program order)
+    double xt[C / 16][4];     // this lane's entries of X in the layout the tiles come out in
 #pragma unroll
-    for (int r = 0; r < kMaxLevels; ++r) {
-      if (r < nr) {
-        const int K = ns.lv.rK[r];
-        for (int cb = 0; cb < C / 16; ++cb) {
-          const d4 out = L.expand(w, l, cb, K);
+    for (int cb = 0; cb < C / 16; ++cb)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const float c32 = (float)out[v];                       // the message is fp32
-            const double e = (double)L.tile[16 * w + (l >> 4) + 4 * v][cb * 16 + (l & 15)] - (double)c32;
-            err[r] = fma(e, e, err[r]);
-          }
+      for (int v = 0; v < 4; ++v) xt[cb][v] = (double)L.tile[16 * w + (l >> 4) + 4 * v][cb * 16 + (l & 15)];
+    for (int r = 0; r < nr; ++r) {
+      d4 out[C / 16];
+      L.expand(w, l, ns.lv.rK[r], out);
+      double e2 = 0.0;
+#pragma unroll
+      for (int cb = 0; cb < C / 16; ++cb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const double e = xt[cb][v] - (double)(float)out[cb][v];     // the message is fp32
+          e2 = fma(e, e, e2);
         }
-      }
+      e2 = wave_sum(e2);
+      if (l == 0) s_err[w][r] += e2;        // (only this wavefront touches its row of s_err)
     }
   }
-#pragma unroll
-  for (int r = 0; r < kMaxLevels; ++r) {
-    if (r < nr) {
-      const double e = block_sum(err[r], red);
-      if (tid == 0) st_coherent(&ns.rk_part[((size_t)node * ns.GR + blockIdx.x) * nr + r], e);
-    }
+  __syncthreads();
+  if (tid < nr) {
+    const double e = ((s_err[0][tid] + s_err[1][tid]) + s_err[2][tid]) + s_err[3][tid];
+    st_coherent(&ns.rk_part[((size_t)node * ns.GR + blockIdx.x) * nr + tid], e);
   }
   if (!arrive_last_few(&ns.done[(size_t)node * (kArriveFan + 1) * kCounterStride], gridDim.x, &s_flag)) return;
   // last block of the node: all partial errors in one round trip, then each level's sum in block order
@@ -484,16 +489,21 @@ __global__ __launch_bounds__(kBlock) void k_rank_apply(NodeSet ns, PassArgs a) {
     // (the next chunk's rows of h are other addresses than the ones written below)
     if (r0 + kRankRows < rhi) stg.fetch(x, h, r0 + kRankRows, rhi);
     L.project(w, l);
-    for (int cb = 0; cb < C / 16; ++cb) {
-      const d4 out = L.expand(w, l, cb, K);
+    d4 out[C / 16];
+    L.expand(w, l, K, out);
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int64_t rr = r0 + 16 * w + (l >> 4) + 4 * v;
-        if (rr < rhi) {
+    for (int v = 0; v < 4; ++v) {
+      const int64_t rr = r0 + 16 * w + (l >> 4) + 4 * v;
+      if (rr < rhi) {
+        float hv[C / 16];
+#pragma unroll
+        for (int cb = 0; cb < C / 16; ++cb) hv[cb] = h[rr * C + cb * 16 + (l & 15)];
+#pragma unroll
+        for (int cb = 0; cb < C / 16; ++cb) {
           const int64_t g = rr * C + cb * 16 + (l & 15);
-          const float c32 = (float)out[v];
+          const float c32 = (float)out[cb][v];
           dense[g] = c32;
-          h[g] = h[g] + c32;
+          h[g] = hv[cb] + c32;
         }
       }
     }
