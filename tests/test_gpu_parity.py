@@ -1199,3 +1199,52 @@ def test_rank_k_levels_match_the_oracle(n, rows, c, mode):
                 int(orc.level_hist_w[j]) * O.AdaCGDOracle.message_bits(j, wl, d) for j in range(len(wl) + 1))
         eng.close()
     assert any(k == O.RANK for k, _ in seen), seen
+
+
+@pytest.mark.parametrize("rows,c", [(96, 16), (128, 64)])
+def test_rank_k_levels_on_degenerate_matrices(rows, c):
+    """Rank-K levels on arguments that stress the eigen-decomposition: a matrix of exact rank two (a singular
+    Gram matrix; every level of rank two or more then recovers it: its entries are non-zero integers, so the
+    rounded message is the matrix itself), magnitudes near both ends of the fp32 range, a zero vector (the
+    node keeps its estimator), columns and rows a million times smaller than the rest.  (Entries that are
+    exactly zero are left out on purpose: what a decomposition leaves there is rounding noise of its own,
+    not comparable bit for bit.)"""
+    E = _eng()
+    d = rows * c
+    rng = np.random.default_rng(7 * rows + c)
+    wl = [(O.RANK, (1, c)), (O.RANK, (3, c)), (O.RANK, (c // 2, c)), (O.TOPK, d)]
+
+    def structured():
+        X = (rng.standard_normal((rows, 4)) * np.array([8.0, 4.0, 2.0, 1.0])) @ rng.standard_normal((4, c))
+        return X + 0.3 * rng.standard_normal((rows, c))
+
+    sign = lambda m: rng.choice([-1.0, 1.0], m)
+    low = (4.0 * np.outer(sign(rows) * rng.integers(1, 4, rows), sign(c) * rng.integers(1, 4, c))
+           + np.outer(sign(rows) * rng.choice([1.0, 3.0], rows), sign(c) * rng.choice([1.0, 3.0], c)))     # 4 a b + odd: never zero
+    skewed = structured()
+    skewed[:, 3] *= 1e-6
+    skewed[:, c - 1] *= 1e-6
+    skewed[rows // 2:, :] *= 1e-6
+    cases = [low, structured() * 1e-18, structured() * 1e15, np.zeros((rows, c)), skewed]
+    n = len(cases)
+    v = np.stack([m.reshape(d) for m in cases]).astype(np.float32)
+    assert np.linalg.matrix_rank(low) == 2 and np.all(low != 0)
+    x0 = np.zeros(d, dtype=np.float32)
+    for zeta, scale in ((1.0, 1e-9), (1.0, 0.05)):
+        kw = dict(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=zeta, master_levels=[], zeta_master=0.0)
+        orc = O.AdaCGDOracle(**kw)
+        orc.init(x0, None, O.INIT_ZERO)
+        eng = E.AdaCGD(grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), flags=E.FLAG_ANY_LEVEL_ORDER, **kw)
+        Dt = np.sum(v.astype(np.float64) ** 2, axis=1) * scale
+        res, rm = orc.step(diffs=v, D=Dt)
+        eng.step(_cuda(v), _cuda(Dt))
+        vmax = np.abs(v).max(axis=1)
+        with until_near_tie(("rank degenerate", rows, c, scale)):
+            compare_step_rank(eng, orc, res, None, ("rank degenerate", rows, c, scale), vmax)
+        lev = eng.state(E.F_LEVEL)
+        assert lev[3] == 0                                   # the zero vector: nothing to send
+        if scale == 1e-9:
+            assert lev[0] == 2                               # exact rank two: the first level of rank >= 2 reproduces it
+            assert np.array_equal(eng.state(E.F_GI)[0], v[0])
+        assert np.isfinite(eng.state(E.F_RANK_SPECTRUM)).all() and np.isfinite(eng.state(E.F_GI)).all()
+        eng.close()
