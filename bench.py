@@ -243,22 +243,42 @@ def extra_rank_k(E, W, torch, steps=20, warmup=3):
     raw = eng.kernel_ms()
     eng.close()
     per_step = {k: round(ms / steps, 5) for k, (ms, cnt) in raw.items() if cnt}      # summed over the launches of a step
-    c, nr = wk.cols, sum(1 for k, _ in wk.worker_levels if k == W.RANK)
+    c, rows = wk.cols, wk.rows
+    ks = [prm[0] for k, prm in wk.worker_levels if k == W.RANK]
     active = float(hist[1:].sum()) / steps                      # workers per step that did not skip
-    applied = float(sum(hist[j] for j in range(1, len(hist)) if wk.worker_levels[j - 1][0] == W.RANK)) / steps
-    # fp64 flops of the Rank-K kernels: Gram matrix 2 d c, one projection 2 d c per Rank-K level for the
-    # realised errors and one more for the level applied (the c x c eigen-decomposition is negligible)
-    flops = 2.0 * wk.d * c * (active * (1 + nr) + applied)
+    sent = [float(hist[j]) / steps if wk.worker_levels[j - 1][0] == W.RANK else 0.0 for j in range(1, len(hist))]
+    # fp64 flops as issued to the matrix cores (16 x 16 x 4 instructions of 2048 flops).  Per 16 rows of X:
+    # the Gram matrix takes 4 instructions for each of the nb (nb + 1) / 2 upper tiles (nb = c / 16); Y = X V
+    # c / 4 for each block of 16 eigenvectors; X_K = Y V_K^T nb ceil(K / 4) per level.
+    nb = c // 16
+    kp = lambda kmax: (kmax + 15) // 16
+    per16_gram = 4 * nb * (nb + 1) // 2
+    per16_err = (c // 4) * kp(max(ks)) + sum(nb * ((k + 3) // 4) for k in ks)
+    flops = 2048.0 * (rows / 16.0) * (active * (per16_gram + per16_err)
+                                      + sum(sj * ((c // 4) * kp(wk.worker_levels[j][1][0]) + nb * ((wk.worker_levels[j][1][0] + 3) // 4))
+                                            for j, sj in enumerate(sent) if sj))
+    # algorithmic bytes: Gram and error kernels read x and the estimator (8 B per coordinate each); the update
+    # reads both, writes the message and the estimator (16 B)
+    nbytes = wk.d * (active * 16.0 + sum(sent) * 16.0)
     t_rank = per_step.get("w_rank", 0.0) * 1e-3
+    t_eig = per_step.get("w_eig", 0.0) * 1e-3
+    hbm = {"achieved": nbytes / t_rank / 1e9 if t_rank else None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": nbytes / t_rank / 1e9 / HBM_PEAK_GBS if t_rank else None}
+    mfma = {"achieved": flops / t_rank / 1e12 if t_rank else None, "peak": 78.6, "unit": "TFLOP/s (fp64)",
+            "frac": flops / t_rank / 1e12 / 78.6 if t_rank else None}
+    bound = "hbm" if (hbm["frac"] or 0) >= (mfma["frac"] or 0) else "mfma"
+    main = hbm if bound == "hbm" else mfma
     return {"workload": "matrix-shaped gradients: n=%d workers, %d x %d per worker (d=%d), shared directions + noise, "
                         "levels %s, master Top-%d" % (wk.n, wk.rows, wk.cols, wk.d, wk.worker_levels, wk.master_levels[0][1]),
             "steps": steps, "ms_per_step": dt / steps * 1e3, "floats_per_sec": wk.n * wk.d * steps / dt,
             "zeta_worker": wk.zeta_worker,
             "level_histogram_skip_then_levels": [int(v) for v in hist], "kernels_ms_per_step": per_step,
-            "roofline": {"bound": "alu", "kernel": "w_rank (Gram matrix, eigen-decomposition, projections)",
-                         "achieved": flops / t_rank / 1e12 if t_rank else None, "peak": 78.6, "unit": "TFLOP/s (fp64)",
-                         "frac": flops / t_rank / 1e12 / 78.6 if t_rank else None, "traffic": None,
-                         "fp64_flops_per_step": flops, "ms_per_step": t_rank * 1e3},
+            "roofline": {"bound": bound, "kernel": "w_rank (Gram matrix, realised errors and update of the Rank-K levels)",
+                         "achieved": main["achieved"], "peak": main["peak"], "unit": main["unit"], "frac": main["frac"],
+                         "traffic": None, "ms_per_step": t_rank * 1e3, "algorithmic_bytes_per_step": nbytes,
+                         "fp64_flops_per_step": flops, "hbm_ceiling": hbm, "mfma_ceiling": mfma},
+            "eigen_decomposition": {"ms_per_step": t_eig * 1e3, "matrices_per_step": active, "size": c,
+                                    "note": "one block per matrix (cyclic Jacobi in LDS): latency-bound, no roofline applies"},
             "note": "one stream, HIP events around every kernel"}
 
 
@@ -309,12 +329,24 @@ def extra_sparse_features(E, W, torch, steps=20, warmup=3):
     nnz = int(wl.csr[0][-1])
     rows = wl.labels.shape[0]
     x0 = torch.zeros(wl.d, dtype=torch.float32, device="cuda")
-    eng = E.AdaCGD(n=wl.n, d=wl.d, gamma=wl.gamma, lam=wl.lam, worker_levels=wl.worker_levels,
-                   zeta_worker=wl.zeta_worker, master_levels=wl.master_levels, zeta_master=wl.zeta_master,
-                   grad_mode=E.GRAD_LOGISTIC_CSR, labels=torch.from_numpy(wl.labels).cuda(),
-                   shard_offsets=wl.shard_offsets, csr=wl.csr, x0=x0, flags=E.FLAG_KERNEL_TIMING)
+    labels = torch.from_numpy(wl.labels).cuda()
+
+    def engine(zeta, flags):
+        return E.AdaCGD(n=wl.n, d=wl.d, gamma=wl.gamma, lam=wl.lam, worker_levels=wl.worker_levels,
+                        zeta_worker=zeta, master_levels=wl.master_levels, zeta_master=wl.zeta_master,
+                        grad_mode=E.GRAD_LOGISTIC_CSR, labels=labels, shard_offsets=wl.shard_offsets, csr=wl.csr, x0=x0,
+                        flags=flags)
+
+    eng = engine(wl.zeta_worker, E.FLAG_KERNEL_TIMING)
     dt, hist, kms = _timed_steps(eng, E, torch, lambda t: eng.step(), warmup, steps)
     eng.close()
+    sweep = []
+    for zeta in (0.0, 1.0, 4.0, 16.0, 64.0, 256.0):      # up to where every worker keeps its estimator in most steps
+        eng = engine(zeta, 0)
+        dz, hz, _ = _timed_steps(eng, E, torch, lambda t: eng.step(), warmup, steps)
+        eng.close()
+        sweep.append({"zeta_worker": zeta, "ms_per_step": dz / steps * 1e3,
+                      "level_histogram_skip_then_levels": [int(v) for v in hz]})
     # stored entries: column + gathered x (margins), row + gathered fp64 margin (column sums); per row the
     # pointer, label and margin; per (worker, column) the column pointer and the gradient written
     alg = nnz * (4 + 4 + 4 + 8) + rows * (8 + 4 + 8) + wl.n * wl.d * (4 + 4)
@@ -328,7 +360,8 @@ def extra_sparse_features(E, W, torch, steps=20, warmup=3):
             "gradient_kernels": {"algorithmic_bytes": alg, "avg_ms": grad_ms,
                                  "GB/s": alg / (grad_ms * 1e-3) / 1e9 if grad_ms else None,
                                  "dense_matrix_bytes_for_comparison": 4.0 * rows * wl.d},
-            "note": "one stream, HIP events around every kernel"}
+            "zeta_sweep": sweep,
+            "note": "one stream; the first record has HIP events around every kernel, the sweep has none"}
 
 
 def extra_small_logistic(E, W, torch, wl, steps, sparse_rows=False):

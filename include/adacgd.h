@@ -292,9 +292,11 @@ enum adacgd_kernel {
   ADACGD_K_M_TALLY = 17,
   ADACGD_K_M_COMPACT = 18,
   ADACGD_K_M_QAPPLY = 19,
-  ADACGD_K_W_RANK = 20,    /* Rank-K levels: Gram matrix, eigen-decomposition, realised errors, dense update */
+  ADACGD_K_W_RANK = 20,    /* Rank-K levels: Gram matrix, realised errors, dense update (the contractions) */
   ADACGD_K_M_RANK = 21,
-  ADACGD_NUM_KERNELS = 22
+  ADACGD_K_W_EIG = 22,     /* Rank-K levels: eigen-decomposition of the Gram matrix */
+  ADACGD_K_M_EIG = 23,
+  ADACGD_NUM_KERNELS = 24
 };
 
 /* Copies one field to dst (host memory, or device memory if dst_on_device != 0)

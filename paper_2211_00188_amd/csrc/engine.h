@@ -192,6 +192,8 @@ hipError_t launch_scanx(const NodeSet& ns, const PassArgs& a, bool repair, hipSt
 hipError_t launch_tally(const NodeSet& ns, hipStream_t st);
 hipError_t launch_compact(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_qapply(const NodeSet& ns, const PassArgs& a, hipStream_t st);
+hipError_t launch_rank_gram(const NodeSet& ns, const PassArgs& a, hipStream_t st);
+hipError_t launch_rank_eig(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_rank_errors(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 hipError_t launch_rank_apply(const NodeSet& ns, const PassArgs& a, hipStream_t st);
 

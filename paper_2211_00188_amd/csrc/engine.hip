@@ -526,8 +526,13 @@ int compress(adacgd_ctx* c, NodeSet& ns, const PassArgs& a, int slot0, hipEvent_
     if ((rc = timed(c, slot0 + 1, [&] { return launch_scan(ns, a, c->cs); }))) return rc;
     if ((rc = timed(c, slot0 + 2, [&] { return launch_filter(ns, a, c->cs); }))) return rc;
   }
-  if (ns.lv.nr > 0 && (rc = timed(c, slot0 == ADACGD_K_W_SAMPLE ? ADACGD_K_W_RANK : ADACGD_K_M_RANK,
-                                  [&] { return launch_rank_errors(ns, a, c->cs); }))) return rc;
+  if (ns.lv.nr > 0) {
+    const int rank_slot = slot0 == ADACGD_K_W_SAMPLE ? ADACGD_K_W_RANK : ADACGD_K_M_RANK;
+    const int eig_slot = slot0 == ADACGD_K_W_SAMPLE ? ADACGD_K_W_EIG : ADACGD_K_M_EIG;
+    if ((rc = timed(c, rank_slot, [&] { return launch_rank_gram(ns, a, c->cs); }))) return rc;
+    if ((rc = timed(c, eig_slot, [&] { return launch_rank_eig(ns, a, c->cs); }))) return rc;
+    if ((rc = timed(c, rank_slot, [&] { return launch_rank_errors(ns, a, c->cs); }))) return rc;
+  }
   if (ns.lv.p > 0 && (rc = timed(c, slot0 + 3, [&] { return launch_gather(ns, c->cs); }))) return rc;
   if (ns.lv.p > 0 && (rc = timed(c, slot0 + 4, [&] { return launch_select(ns, c->cs); }))) return rc;
   if (before_tally) HIPCHK(c, hipStreamWaitEvent(c->cs, before_tally, 0));

@@ -559,14 +559,11 @@ static hipError_t launch_rank(int which, const NodeSet& ns, const PassArgs& a, h
   }
 }
 
-// Gram matrix, its eigen-decomposition and the realised error of every Rank-K level (before the level choice)
-hipError_t launch_rank_errors(const NodeSet& ns, const PassArgs& a, hipStream_t st) {
-  hipError_t e = launch_rank(0, ns, a, st);
-  if (e != hipSuccess) return e;
-  e = launch_rank(1, ns, a, st);
-  if (e != hipSuccess) return e;
-  return launch_rank(2, ns, a, st);
-}
+// Gram matrix, its eigen-decomposition and the realised error of every Rank-K level, in this order (before the
+// level choice)
+hipError_t launch_rank_gram(const NodeSet& ns, const PassArgs& a, hipStream_t st) { return launch_rank(0, ns, a, st); }
+hipError_t launch_rank_eig(const NodeSet& ns, const PassArgs& a, hipStream_t st) { return launch_rank(1, ns, a, st); }
+hipError_t launch_rank_errors(const NodeSet& ns, const PassArgs& a, hipStream_t st) { return launch_rank(2, ns, a, st); }
 
 // Estimator update and dense message of the nodes whose chosen level is a Rank-K level
 hipError_t launch_rank_apply(const NodeSet& ns, const PassArgs& a, hipStream_t st) { return launch_rank(3, ns, a, st); }

@@ -30,7 +30,7 @@ MAX_LEVELS = 16
 KERNELS = ["xupdate", "grad_margin", "grad_cols", "aggregate",
            "w_sample", "w_scan", "w_filter", "w_gather", "w_select", "w_tally", "w_compact", "w_qapply",
            "m_sample", "m_scan", "m_filter", "m_gather", "m_select", "m_tally", "m_compact", "m_qapply",
-           "w_rank", "m_rank"]
+           "w_rank", "m_rank", "w_eig", "m_eig"]
 
 EXPORTS = ["adacgd_workspace_bytes", "adacgd_init", "adacgd_init_static", "adacgd_step", "adacgd_state", "adacgd_set_state",
            "adacgd_destroy", "adacgd_last_error"]
