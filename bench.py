@@ -419,7 +419,7 @@ def main():
     ap.add_argument("--no-overlap", action="store_true", help="skip the two-stream run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (all n workers are batched on it); "
+        print("bench.py: the engine runs on one GPU only (all n workers are batched on it); "
               "--gpus > 1 is not supported", file=sys.stderr)
         sys.exit(2)
 
