@@ -920,9 +920,9 @@ static int init_impl(const adacgd_config* cfg, adacgd_ctx** out, int static_dev)
   else INITCHK(launch_fill_u32((uint32_t*)c->gi, 0u, nd, c->st));
   if (cfg->init_mode == ADACGD_INIT_COMPRESSED) {
     // g~_i^0 = C_m(grad f_i(x^0)) (the CLAG / EF21 start, Section 2.3): one application of the compressor
-    // with the last level as the only one, h = 0 (so v is the gradient, bit for bit), a zero trigger (h is
-    // kept only if the gradient is zero, and then h = 0 is the answer) and the selected values stored as
-    // they are, so that a selected -0 stays -0
+    // with the last level as the only one, h = 0 (so v is the gradient, bit for bit), applied unconditionally
+    // (a zero gradient still selects K zeros) and the selected values stored as they are, so that a selected
+    // -0 stays -0
     NodeSet one = c->W;
     const LevelTable& lv = c->W.lv;
     one.lv.m = 1;

@@ -327,7 +327,8 @@ __global__ __launch_bounds__(kBlock) void k_scan(NodeSet ns, PassArgs a) {
     ns.D[node] = dnode;
     // first condition of the cascade: the trigger keeps h, and nothing after this kernel has work
     // to do for the node (the tally kernel takes the same decision from the same two numbers)
-    ns.skip[node] = s <= trigger_bound(ns.lv, 0, s, dnode) ? 1u : 0u;
+    // (the compressed start applies its one level unconditionally: a zero gradient still selects K zeros, signs kept)
+    ns.skip[node] = (!a.assign && s <= trigger_bound(ns.lv, 0, s, dnode)) ? 1u : 0u;
     ns.bmin[node] = p > 0 ? s_bin[p - 1] : (uint32_t)kBins0;   // largest K reaches lowest
     if (ns.lv.nq > 0) ns.amax[node] = s_kmax;
   }
@@ -610,7 +611,7 @@ __global__ __launch_bounds__(kBlock) void k_scanx(NodeSet ns, PassArgs a) {
     ns.D[node] = dnode;
     // first condition of the cascade: the trigger keeps h, and nothing after this kernel has work
     // to do for the node (the tally kernel takes the same decision from the same two numbers)
-    const bool skip = s <= trigger_bound(ns.lv, 0, s, dnode);
+    const bool skip = !a.assign && s <= trigger_bound(ns.lv, 0, s, dnode);       // (see the two-pass scan)
     ns.skip[node] = skip ? 1u : 0u;
     ns.Eb[node] = el;
     // the K largest all have keys >= cut  <=>  at least K candidates were found
@@ -1236,7 +1237,7 @@ __global__ __launch_bounds__(kBlock) void k_tally(NodeSet ns) {
       ns.err[node * lv.m + j] = err[j];
     }
     int jstar;
-    if (S <= trigger_bound(lv, 0, S, D)) {
+    if (skip) {                                    // (the scan took this decision: S <= bound of position 0)
       jstar = 0;                                   // keep h: communication skipped
     } else {
       jstar = lv.m;
@@ -1513,7 +1514,8 @@ __global__ __launch_bounds__(1024) void k_small(NodeSet ns, PassArgs a) {
   __syncthreads();
   for (int i = 0; i < nw; ++i) kmax = redu[i] > kmax ? redu[i] : kmax;
   const double Dn = DIFF ? a.extD[node] : D;
-  const bool skip = S <= trigger_bound(lv, 0, S, Dn);   // first condition of the cascade: nothing else is evaluated
+  // first condition of the cascade: nothing else is evaluated (the compressed start applies its level unconditionally)
+  const bool skip = !a.assign && S <= trigger_bound(lv, 0, S, Dn);
 
   if (!skip) {
     // ---- bitonic sort, descending ----

@@ -802,7 +802,8 @@ def test_compressed_initial_estimators_bit_exact(n, d):
     grads[0][1, ::3] = -0.0                            # and g~_i^0 = C(grad) keeps the sign of each
     grads[0][1, min(5, d - 1)] = 1.0
     if n > 2:
-        grads[0][2] = 0.0                              # ... and one that is zero
+        grads[0][2] = 0.0                              # ... and one that is zero, with zeros of both signs: the
+        grads[0][2, 1::2] = -0.0                       # level applies all the same and keeps K of them as they are
     for t in range(1, 4):
         grads[t] = (grads[t - 1] + grads[t] * np.float32(0.2)).astype(np.float32)
     x0 = rng.standard_normal(d).astype(np.float32)

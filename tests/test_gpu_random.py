@@ -16,10 +16,20 @@ DIMS = [1, 2, 3, 63, 64, 65, 255, 1000, 2047, 2048, 2049, 4095, 4096, 4097, 8191
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
 def test_random_configurations_bit_exact(seed):
+    _sweep(seed, 100, False)
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_configurations_with_block_wise_quantisers_bit_exact(seed):
+    """The same sweep with block-wise quantiser levels (one scale per 64 ... 2048 coordinates) in most level sets."""
+    _sweep(seed, 60, True)
+
+
+def _sweep(seed, cases, with_blocks):
     E = _eng()
     rng = np.random.default_rng(seed)
     near_ties = 0
-    for case in range(100):
+    for case in range(cases):
         d = int(rng.choice(DIMS))
         n = int(rng.integers(1, 3)) if d > 100000 else int(rng.integers(1, 7))
         Ks = sorted({int(max(1, min(d, round(d * 10 ** rng.uniform(-4, -0.3))))) for _ in range(int(rng.integers(1, 5)))})
@@ -27,9 +37,12 @@ def test_random_configurations_bit_exact(seed):
         if rng.random() < 0.4:
             for b in rng.choice([2, 3, 4, 6, 8], size=int(rng.integers(1, 3)), replace=False):
                 levels.append((O.QUANT, int(b)))
+        if with_blocks and rng.random() < 0.8:
+            for _ in range(int(rng.integers(1, 3))):
+                levels.append((O.QUANT_BLOCK, (int(rng.choice([2, 3, 4, 8])), int(rng.choice([64, 128, 256, 1024, 2048])))))
         if rng.random() < 0.3:
             levels.append((O.TOPK, d))
-        levels = sorted(set(levels), key=lambda l: (O.level_alpha(l, d), l[0], l[1]))
+        levels = sorted(set(levels), key=lambda l: (O.level_alpha(l, d), l[0], str(l[1])))
         ml = [] if rng.random() < 0.2 else [(O.TOPK, int(max(1, min(d, round(d * 10 ** rng.uniform(-3, -0.5))))))]
         zw = float(rng.choice([0.0, 0.3, 1.0, 3.0]))
         zm = float(rng.choice([0.0, 0.0, 0.5]))
