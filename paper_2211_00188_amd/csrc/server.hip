@@ -122,19 +122,24 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(NodeSet ws, const float* _
 // Top-K messages of at most kOrderedMax workers: the same sums taken in ASCENDING WORKER INDEX, so that the
 // result is the sequential fp64 sum whatever the data (the kernel above adds in arbitrary order, which gives
 // the same bits only while the exponents met at one coordinate spread over less than 53 - 24 - log2 n bits).
-// One block per group; the group's range of every worker's message is loaded for sixteen workers at a time
-// and the workers are then added one after the other (the coordinates of one message are distinct, so the
-// threads of a round do not meet; a barrier separates the rounds).
+// One block per group of 2048 coordinates, and inside it every wavefront owns a quarter of them: it walks
+// the group's range of every worker's message, worker after worker, and adds the entries that fall into its
+// quarter.  A wavefront's LDS operations execute in the order they are issued, and the coordinates of one
+// message are distinct, so every coordinate receives its additions in worker order without any barrier; the
+// four wavefronts read the same few kilobytes of messages (the later ones from the cache).
 constexpr int kOrderedMax = 64;
-constexpr int kAggChunk = 16;
+constexpr int kAggChunk = 8;          // workers whose first 64 entries are in flight at once
 
 __global__ __launch_bounds__(kBlock) void k_aggregate_ordered(NodeSet ws, const float* __restrict__ gt_old,
                                                                float* __restrict__ gt_new, IterateUpdate xu) {
   __shared__ double acc[kWaveTile];
-  const int g = blockIdx.x, tid = threadIdx.x;
+  constexpr int QUARTER = kWaveTile / 4;
+  const int g = blockIdx.x, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int64_t d = ws.d;
   const int64_t base = (int64_t)g * kWaveTile;
-  for (int c = tid; c < kWaveTile; c += kBlock) acc[c] = 0.0;
+  double* mine = acc + w * QUARTER;                       // only this wavefront touches these entries
+  const int32_t first = (int32_t)base + w * QUARTER;      // (d < 2^31)
+  for (int c = lane; c < QUARTER; c += 64) mine[c] = 0.0;
   for (int i0 = 0; i0 < ws.nn; i0 += kAggChunk) {
     uint32_t lo[kAggChunk], cnt[kAggChunk];
     int32_t pidx[kAggChunk];
@@ -144,38 +149,39 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_ordered(NodeSet ws, const 
       const int i = i0 + u;
       lo[u] = 0; cnt[u] = 0;
       if (i < ws.nn && __builtin_amdgcn_readfirstlane(ws.sel_slot[i]) >= 0) {
-        const uint32_t l = ws.grp_off[(size_t)i * (ws.groups + 1) + g];
+        const uint32_t l = __builtin_amdgcn_readfirstlane(ws.grp_off[(size_t)i * (ws.groups + 1) + g]);
         lo[u] = l;
-        cnt[u] = __builtin_amdgcn_readfirstlane(ws.grp_off[(size_t)i * (ws.groups + 1) + g + 1] - l);
+        cnt[u] = __builtin_amdgcn_readfirstlane(ws.grp_off[(size_t)i * (ws.groups + 1) + g + 1]) - l;
       }
     }
 #pragma unroll
-    for (int u = 0; u < kAggChunk; ++u) {                 // first entry per thread of every range
-      pidx[u] = 0; pval[u] = 0.f;
-      if ((uint32_t)tid < cnt[u]) {
-        const size_t off = (size_t)(i0 + u) * ws.Kcap + lo[u] + tid;
+    for (int u = 0; u < kAggChunk; ++u) {                 // first entry per lane of every range
+      pidx[u] = first; pval[u] = 0.f;
+      if ((uint32_t)lane < cnt[u]) {
+        const size_t off = (size_t)(i0 + u) * ws.Kcap + lo[u] + lane;
         pidx[u] = ws.msg_idx[off];
         pval[u] = ws.msg_val[off];
       }
     }
 #pragma unroll
     for (int u = 0; u < kAggChunk; ++u) {
-      if (cnt[u] == 0) continue;                          // (the same in every thread)
-      __syncthreads();
-      if ((uint32_t)tid < cnt[u]) acc[pidx[u] - base] += (double)pval[u];
-      for (uint32_t e = tid + kBlock; e < cnt[u]; e += kBlock) {
+      if (cnt[u] == 0) continue;                          // (the same in every lane)
+      uint32_t r = (uint32_t)(pidx[u] - first);
+      if ((uint32_t)lane < cnt[u] && r < (uint32_t)QUARTER) mine[r] += (double)pval[u];
+      for (uint32_t e = lane + 64; e < cnt[u]; e += 64) {
         const size_t off = (size_t)(i0 + u) * ws.Kcap + lo[u] + e;
-        acc[ws.msg_idx[off] - base] += (double)ws.msg_val[off];
+        r = (uint32_t)(ws.msg_idx[off] - first);
+        if (r < (uint32_t)QUARTER) mine[r] += (double)ws.msg_val[off];
       }
     }
   }
-  __syncthreads();
   const double n = (double)ws.nn;
-  for (int c = tid; c < kWaveTile; c += kBlock) {
-    if (base + c < d) {
-      const float gn = (float)((double)gt_old[base + c] + acc[c] / n);
-      gt_new[base + c] = gn;
-      if (xu.out) xu.out[base + c] = (float)((double)xu.x[base + c] - xu.gamma * (double)gn);
+  for (int c = lane; c < QUARTER; c += 64) {
+    const int64_t l = (int64_t)first + c;
+    if (l < d) {
+      const float gn = (float)((double)gt_old[l] + mine[c] / n);
+      gt_new[l] = gn;
+      if (xu.out) xu.out[l] = (float)((double)xu.x[l] - xu.gamma * (double)gn);
     }
   }
 }
