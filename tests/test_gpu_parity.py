@@ -463,7 +463,7 @@ def test_long_vectors_one_pass_selection_bit_exact(kind):
     eng.close()
 
 
-@pytest.mark.parametrize("mode", ["grad", "diff", "diff_quant"])
+@pytest.mark.parametrize("mode", ["grad", "diff", "diff_quant", "diff_block_rank"])
 def test_overlap_mode_gives_identical_results(mode):
     """Worker compression on the library's own stream, overlapped with the previous step's
     server work: every state vector and message must equal the single-stream run bit for bit,
@@ -475,6 +475,11 @@ def test_overlap_mode_gives_identical_results(mode):
     wl = [(O.TOPK, 100), (O.TOPK, 5000), (O.TOPK, d // 25)]
     if mode == "diff_quant":       # dense quantised messages: their scales and codes are message tables too
         wl = by_alpha([(O.TOPK, 100), (O.QUANT, 2), (O.QUANT, 4), (O.TOPK, d // 25), (O.QUANT, 8)], d)
+    any_order = 0
+    if mode == "diff_block_rank":  # block-wise scales and Rank-K reconstructions are message tables as well
+        wl = [(O.RANK, (1, 64)), (O.TOPK, 100), (O.RANK, (32, 64)), (O.QUANT_BLOCK, (2, 256)), (O.TOPK, d // 25),
+              (O.QUANT_BLOCK, (8, 256))]
+        any_order = E.FLAG_ANY_LEVEL_ORDER
     ml = [(O.TOPK, d // 100)]
     steps = 6
     x0 = _cuda(np.zeros(d, dtype=np.float32))
@@ -495,7 +500,7 @@ def test_overlap_mode_gives_identical_results(mode):
                            grad_mode=E.GRAD_EXTERNAL, x0=x0, grad0=arrs[0], flags=flags | E.FLAG_RETAIN_EXT)
         else:
             eng = E.AdaCGD(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0, master_levels=ml,
-                           grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_ZERO, x0=x0, flags=flags)
+                           grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_ZERO, x0=x0, flags=flags | any_order)
         levels = []
         for t in range(1, steps + 1):
             if mode == "grad":
@@ -512,6 +517,10 @@ def test_overlap_mode_gives_identical_results(mode):
         hist = outs[1][7]
         assert sum(int(hist[j]) for j in range(1, len(wl) + 1) if wl[j - 1][0] == O.QUANT) > 0, hist   # dense messages were aggregated
         assert sum(int(hist[j]) for j in range(1, len(wl) + 1) if wl[j - 1][0] == O.TOPK) > 0, hist
+    if mode == "diff_block_rank":
+        hist = outs[1][7]
+        for kind in (O.RANK, O.QUANT_BLOCK):
+            assert sum(int(hist[j]) for j in range(1, len(wl) + 1) if wl[j - 1][0] == kind) > 0, (kind, hist)
     for a, b in zip(outs[0][1:], outs[1][1:]):
         assert np.array_equal(np.ascontiguousarray(a).view(np.uint8), np.ascontiguousarray(b).view(np.uint8))
     if mode == "grad":
