@@ -513,14 +513,13 @@ __global__ __launch_bounds__(kBlock) void k_rank_apply(NodeSet ns, PassArgs a) {
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
-// Launch with `lds` bytes of dynamic LDS; sizes above 64 KB are announced to the runtime once per kernel.
+// Launch with `lds` bytes of dynamic LDS; sizes above 64 KB are announced to the runtime first (for the
+// current device: a host-side setting, no allocation).
 template <typename Kern>
-static hipError_t launch_lds(Kern kern, bool* announced, size_t lds, dim3 grid, hipStream_t st, const NodeSet& ns,
-                             const PassArgs& a) {
-  if (lds > 64 * 1024 && !*announced) {
+static hipError_t launch_lds(Kern kern, size_t lds, dim3 grid, hipStream_t st, const NodeSet& ns, const PassArgs& a) {
+  if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    *announced = true;
   }
   hipLaunchKernelGGL(kern, grid, dim3(kBlock), lds, st, ns, a);
   return hipGetLastError();
@@ -530,7 +529,6 @@ template <int C>
 static hipError_t launch_rank_c(int which, const NodeSet& ns, const PassArgs& a, hipStream_t st) {
   const dim3 grid(ns.GR, ns.nn), block(kBlock);
   const size_t lds = ProjLds<C>::bytes(proj_columns(ns.lv, -1));      // (the apply kernel needs at most this)
-  static bool announced[4] = {false, false, false, false};
   switch (which) {
     case 0:
       if (a.diff) hipLaunchKernelGGL((k_gram<true, C>), grid, block, 0, st, ns, a);
@@ -540,11 +538,11 @@ static hipError_t launch_rank_c(int which, const NodeSet& ns, const PassArgs& a,
       hipLaunchKernelGGL((k_eig<C>), dim3(ns.nn), dim3(eig_threads<C>()), 0, st, ns);
       break;
     case 2:
-      if (a.diff) return launch_lds(k_rank_err<true, C>, &announced[0], lds, grid, st, ns, a);
-      return launch_lds(k_rank_err<false, C>, &announced[1], lds, grid, st, ns, a);
+      if (a.diff) return launch_lds(k_rank_err<true, C>, lds, grid, st, ns, a);
+      return launch_lds(k_rank_err<false, C>, lds, grid, st, ns, a);
     default:
-      if (a.diff) return launch_lds(k_rank_apply<true, C>, &announced[2], lds, grid, st, ns, a);
-      return launch_lds(k_rank_apply<false, C>, &announced[3], lds, grid, st, ns, a);
+      if (a.diff) return launch_lds(k_rank_apply<true, C>, lds, grid, st, ns, a);
+      return launch_lds(k_rank_apply<false, C>, lds, grid, st, ns, a);
   }
   return hipGetLastError();
 }

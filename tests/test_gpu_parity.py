@@ -1211,6 +1211,33 @@ def test_rank_k_levels_match_the_oracle(n, rows, c, mode):
     assert any(k == O.RANK for k, _ in seen), seen
 
 
+def test_rank_k_levels_of_large_rank():
+    """Ranks above half the column count (the projection kernels then hold all 64 eigenvectors in LDS, more
+    than 64 KB of it), up to the full rank, whose message is the argument itself up to rounding."""
+    E = _eng()
+    n, rows, c = 2, 300, 64
+    d = rows * c
+    rng = np.random.default_rng(99)
+    wl = [(O.RANK, (40, c)), (O.RANK, (57, c)), (O.RANK, (64, c))]
+    X = (rng.standard_normal((n, rows, 6)) * np.array([9.0, 5.0, 3.0, 2.0, 1.5, 1.0])) @ rng.standard_normal((n, 6, c))
+    v = (X + rng.standard_normal((n, rows, c)) * np.linspace(0.05, 1.0, c)).reshape(n, d).astype(np.float32)
+    x0 = np.zeros(d, dtype=np.float32)
+    for scale in (1e-4, 3e-3, 1e-12):          # the level the cascade stops at moves with the right-hand side
+        kw = dict(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0, master_levels=[], zeta_master=0.0)
+        orc = O.AdaCGDOracle(**kw)
+        orc.init(x0, None, O.INIT_ZERO)
+        eng = E.AdaCGD(grad_mode=E.DIFF_EXTERNAL, init_mode=E.INIT_ZERO, x0=_cuda(x0), **kw)
+        Dt = np.sum(v.astype(np.float64) ** 2, axis=1) * scale
+        res, rm = orc.step(diffs=v, D=Dt)
+        eng.step(_cuda(v), _cuda(Dt))
+        with until_near_tie(("rank, large", scale)):
+            compare_step_rank(eng, orc, res, None, ("rank, large", scale), np.abs(v).max(axis=1))
+        if scale == 1e-12:
+            assert eng.state(E.F_LEVEL).tolist() == [3] * n
+            assert np.mean(bits(eng.state(E.F_GI)) != bits(v)) <= 1e-3          # full rank: C(v) = v up to rounding
+        eng.close()
+
+
 @pytest.mark.parametrize("rows,c", [(96, 16), (128, 64)])
 def test_rank_k_levels_on_degenerate_matrices(rows, c):
     """Rank-K levels on arguments that stress the eigen-decomposition: a matrix of exact rank two (a singular
