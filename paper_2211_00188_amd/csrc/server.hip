@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_ordered(NodeSet ws, const 
   const int64_t d = ws.d;
   const int64_t base = (int64_t)g * kWaveTile;
   double* mine = acc + w * QUARTER;                       // only this wavefront touches these entries
-  const int32_t first = (int32_t)base + w * QUARTER;      // (d < 2^31)
+  const int64_t first = base + w * QUARTER;
   for (int c = lane; c < QUARTER; c += 64) mine[c] = 0.0;
   for (int i0 = 0; i0 < ws.nn; i0 += kAggChunk) {
     uint32_t lo[kAggChunk], cnt[kAggChunk];
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_ordered(NodeSet ws, const 
     }
 #pragma unroll
     for (int u = 0; u < kAggChunk; ++u) {                 // first entry per lane of every range
-      pidx[u] = first; pval[u] = 0.f;
+      pidx[u] = 0; pval[u] = 0.f;
       if ((uint32_t)lane < cnt[u]) {
         const size_t off = (size_t)(i0 + u) * ws.Kcap + lo[u] + lane;
         pidx[u] = ws.msg_idx[off];
@@ -166,18 +166,18 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_ordered(NodeSet ws, const 
 #pragma unroll
     for (int u = 0; u < kAggChunk; ++u) {
       if (cnt[u] == 0) continue;                          // (the same in every lane)
-      uint32_t r = (uint32_t)(pidx[u] - first);
-      if ((uint32_t)lane < cnt[u] && r < (uint32_t)QUARTER) mine[r] += (double)pval[u];
+      uint64_t r = (uint64_t)((int64_t)pidx[u] - first);         // (huge for coordinates below this quarter)
+      if ((uint32_t)lane < cnt[u] && r < (uint64_t)QUARTER) mine[r] += (double)pval[u];
       for (uint32_t e = lane + 64; e < cnt[u]; e += 64) {
         const size_t off = (size_t)(i0 + u) * ws.Kcap + lo[u] + e;
-        r = (uint32_t)(ws.msg_idx[off] - first);
-        if (r < (uint32_t)QUARTER) mine[r] += (double)ws.msg_val[off];
+        r = (uint64_t)((int64_t)ws.msg_idx[off] - first);
+        if (r < (uint64_t)QUARTER) mine[r] += (double)ws.msg_val[off];
       }
     }
   }
   const double n = (double)ws.nn;
   for (int c = lane; c < QUARTER; c += 64) {
-    const int64_t l = (int64_t)first + c;
+    const int64_t l = first + c;
     if (l < d) {
       const float gn = (float)((double)gt_old[l] + mine[c] / n);
       gt_new[l] = gn;
