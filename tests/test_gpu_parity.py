@@ -889,7 +889,8 @@ def test_overlap_mode_short_vectors(n, master):
     eng.close()
 
 
-@pytest.mark.parametrize("n,d,flags", [(4, 900, 0), (3, 3 * 8192 + 516, 0), (2, 130 * 8192, 0), (3, 20000, "retain")])
+@pytest.mark.parametrize("n,d,flags", [(4, 900, 0), (3, 3 * 8192 + 516, 0), (2, 130 * 8192, 0), (3, 20000, "retain"),
+                                       (3, 64 * 320, "block_rank")])
 def test_checkpoint_and_restore_continue_bit_for_bit(n, d, flags):
     """State copied out after three steps and restored into a context that was initialised from other
     data continues exactly like the uninterrupted run (mixed level set: the Philox counter is part of it)."""
@@ -898,13 +899,15 @@ def test_checkpoint_and_restore_continue_bit_for_bit(n, d, flags):
     wl = by_alpha([(O.TOPK, max(1, d // 300)), (O.QUANT, 4), (O.TOPK, max(2, d // 10))], d)
     if d >= 130 * 8192:
         wl = [(O.TOPK, d // 300), (O.TOPK, d // 10)]              # one-pass sequence
+    if flags == "block_rank":       # block-wise quantiser and Rank-K levels: nothing of theirs outlives a step
+        wl = [(O.RANK, (2, 64)), (O.TOPK, d // 300), (O.QUANT_BLOCK, (4, 256)), (O.RANK, (40, 64)), (O.TOPK, d // 10)]
     ml = [(O.TOPK, max(1, d // 50))]
     grads = [make_vectors(rng, n, d, "normal") for _ in range(7)]
     for t in range(1, 7):
         grads[t] = (grads[t - 1] + grads[t] * np.float32(0.3)).astype(np.float32)
     arrs = [_cuda(g) for g in grads]
     x0 = rng.standard_normal(d).astype(np.float32)
-    fl = E.FLAG_RETAIN_EXT if flags == "retain" else 0
+    fl = E.FLAG_RETAIN_EXT if flags == "retain" else E.FLAG_ANY_LEVEL_ORDER if flags == "block_rank" else 0
     kw = dict(n=n, d=d, gamma=0.05, worker_levels=wl, zeta_worker=1.0, master_levels=ml, zeta_master=0.3,
               grad_mode=E.GRAD_EXTERNAL, seed=9, flags=fl)
     a = E.AdaCGD(x0=_cuda(x0), grad0=arrs[0], **kw)
