@@ -9,7 +9,7 @@ import pytest
 
 pytestmark = pytest.mark.gpu
 
-TOPK, QUANT = 0, 1
+TOPK, QUANT, QUANT_BLOCK, RANK = 0, 1, 2, 3
 
 
 def _run(E, torch, static, n, d, levels, master, mode, steps, seed):
@@ -80,8 +80,11 @@ def test_static_workspace_entry_point_matches_adacgd_init():
     small = dict(n=2, d=5003, levels=[(TOPK, 5), (TOPK, 300), (QUANT, 8)], master=[(TOPK, 100)],
                  mode=E.DIFF_EXTERNAL, steps=3, seed=2)
     tiny = dict(n=3, d=700, levels=[(TOPK, 3), (TOPK, 80)], master=[(TOPK, 20)], mode=E.GRAD_EXTERNAL, steps=2, seed=3)
-    # two calls in a row on the one array, the second with a smaller input, then a third on the one-block path
-    for name, kw in (("big", big), ("small", small), ("tiny", tiny)):
+    kinds = dict(n=3, d=16 * 900, levels=[(RANK, (2, 16)), (TOPK, 50), (QUANT_BLOCK, (4, 128)), (TOPK, 1500)],
+                 master=[(TOPK, 200)], mode=E.DIFF_EXTERNAL, steps=2, seed=4)
+    # two calls in a row on the one array, the second with a smaller input, then one on the one-block path and
+    # one with block-wise quantiser and Rank-K levels
+    for name, kw in (("big", big), ("small", small), ("tiny", tiny), ("kinds", kinds)):
         got = _run(E, torch, True, **kw)
         ref = _run(E, torch, False, **kw)
         _same(got, ref, name)
