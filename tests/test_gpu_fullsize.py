@@ -9,6 +9,8 @@ kernel stress: n = 32, d = 2^20, all 50 steps, the pool of four difference array
                included), message sizes for all.
 federated    : the full dimension d = 65536 and length T = 200 with 64 workers, the oracle in the loop at
                1e-5, with a trigger constant at which skips, sparse levels and dense levels all occur.
+block-wise   : the kernel-stress vectors with block-wise quantiser levels, twelve steps, four workers.
+matrix shaped: n = 16, 16384 x 64 per worker, Rank-K levels, the benchmark's start and pool, three steps.
 The oracle's per-worker work runs on a thread pool here (its arithmetic is unchanged)."""
 from concurrent.futures import ThreadPoolExecutor
 
@@ -65,17 +67,25 @@ def test_model_sized_benchmark_setup_all_workers_both_stream_modes():
 
 
 def test_kernel_stress_full_size_all_steps():
+    _kernel_stress(W.kernel_stress(), None, (0, 5, 9, 13, 18, 22, 27, 31), O.QUANT)
+
+
+def test_kernel_stress_with_block_wise_quantisers_full_size():
+    """The benchmark's block-wise variant of the kernel-stress workload at its size, twelve steps (the pool of
+    four difference arrays three times over), four workers coordinate by coordinate."""
+    _kernel_stress(W.kernel_stress_blockwise(), 12, (2, 11, 20, 29), O.QUANT_BLOCK)
+
+
+def _kernel_stress(wk, steps, sample, quant_kind):
     E = _eng()
     import torch
-    wk = W.kernel_stress()
-    n, d, T = wk.n, wk.d, wk.T
+    n, d, T = wk.n, wk.d, steps or wk.T
     pool = [W.kernel_stress_diffs(wk, t) for t in range(4)]
     dev = [(_cuda(v), _cuda(D)) for v, D in pool]
     x0 = np.zeros(d, dtype=np.float32)
     eng = E.AdaCGD(n=n, d=d, gamma=0.1, worker_levels=wk.worker_levels, zeta_worker=wk.zeta_worker,
                    master_levels=wk.master_levels, zeta_master=0.0, grad_mode=E.DIFF_EXTERNAL,
                    init_mode=E.INIT_ZERO, x0=_cuda(x0), seed=wk.seed)
-    sample = (0, 5, 9, 13, 18, 22, 27, 31)
     h = {i: np.zeros(d, dtype=np.float32) for i in sample}
     live = set(sample)            # workers still compared (a near tie ends a worker's comparison, counted below)
     near_ties = 0
@@ -111,14 +121,18 @@ def test_kernel_stress_full_size_all_steps():
                     if codes is None:
                         codes, scale = eng.state(E.F_QCODES), eng.state(E.F_QSCALE)
                     assert np.array_equal(codes[i].astype(np.int32), r.codes), (t, i)
-                    assert scale[i] == np.float32(r.scale), (t, i)
+                    if quant_kind == O.QUANT:
+                        assert scale[i] == np.float32(r.scale), (t, i)
+                    else:                   # one scale per block
+                        got = eng.state(E.F_QBSCALE)[i]
+                        assert np.array_equal(bits(got[: len(r.scales)]), bits(r.scales.astype(np.float32))), (t, i)
                 h[i] = r.h_new
             for i in range(n):
                 want = 0 if lev[i] == 0 or wk.worker_levels[lev[i] - 1][0] != O.TOPK else wk.worker_levels[lev[i] - 1][1]
                 assert len(msgs[i][0]) == want and np.all(np.diff(msgs[i][0]) > 0), (t, i)
     assert near_ties <= 1
     kinds = {wk.worker_levels[j - 1][0] for j in range(1, len(chosen)) if chosen[j]}
-    assert chosen[0] > 0 and kinds == {O.TOPK, O.QUANT}, chosen      # skips, sparse and dense messages all occurred
+    assert chosen[0] > 0 and kinds == {O.TOPK, quant_kind}, chosen      # skips, sparse and dense messages all occurred
     assert int(eng.state(E.F_STEP)[0]) == T
     eng.close()
     del dev, eng
@@ -177,4 +191,40 @@ def test_federated_full_dimension_full_length():
     kinds = {wl.worker_levels[j - 1][0] for j in range(1, len(hist)) if hist[j]}
     assert hist[0] > 0 and kinds == {O.TOPK, O.QUANT}, hist      # skips, sparse and dense messages all occurred
     del A, labels, eng
+    torch.cuda.empty_cache()
+
+
+def test_matrix_shaped_rank_k_workload_full_size():
+    """The benchmark's Rank-K workload at its size (n = 16, 16384 x 64 per worker, the benchmark's start and
+    pool of gradient arrays), three steps, every worker and the master against the oracle to the bar of the
+    Rank-K levels (the oracle is put on the engine's state after every step)."""
+    from test_gpu_parity import compare_step_rank, until_near_tie
+    E = _eng()
+    import torch
+    wk = W.matrix_shaped()
+    n, d = wk.n, wk.d
+    gen = W.MatrixShapedGrads(wk)
+    g0 = gen.next().copy()
+    pool = [gen.next().copy() for _ in range(3)]
+    x0 = np.zeros(d, dtype=np.float32)
+    kw = dict(n=n, d=d, gamma=0.1, worker_levels=wk.worker_levels, zeta_worker=wk.zeta_worker,
+              master_levels=wk.master_levels, zeta_master=0.0)
+    orc = O.AdaCGDOracle(**kw)
+    eng = E.AdaCGD(grad_mode=E.GRAD_EXTERNAL, init_mode=E.INIT_FULLGRAD, x0=_cuda(x0), grad0=_cuda(g0), **kw)
+    seen = set()
+    with ThreadPoolExecutor(THREADS) as ex:
+        orc.worker_map = ex.map
+        orc.init(x0, g0, O.INIT_FULLGRAD)
+        with until_near_tie("matrix shaped"):
+            for t in range(3):
+                vmax = np.abs(pool[t]).max(axis=1) + np.abs(orc.gi).max(axis=1)
+                res, rm = orc.step(grads=pool[t])
+                eng.step(_cuda(pool[t]))
+                compare_step_rank(eng, orc, res, rm, ("matrix shaped", t), vmax)
+                seen.update(r.level for r in res)
+                orc.gi, orc.gt, orc.gt_prev = eng.state(E.F_GI), eng.state(E.F_GTILDE), eng.state(E.F_GTILDE_PREV)
+                orc.g, orc.x = eng.state(E.F_G), eng.state(E.F_X)
+    assert any(j > 0 and wk.worker_levels[j - 1][0] == O.RANK for j in seen), seen        # a Rank-K message was sent
+    eng.close()
+    del eng
     torch.cuda.empty_cache()
