@@ -193,7 +193,7 @@ def extra_kernel_stress(E, W, torch, counters, steps=50, warmup=4):
                     "memory-side cache, so HBM traffic is below the algorithmic bytes"}
 
 
-def extra_block_quant(E, W, torch, steps=50, warmup=4):
+def extra_block_quant(E, W, torch, counters, steps=50, warmup=4):
     """Secondary workload: the kernel-stress vectors with block-wise quantiser levels (one scale per 256 coordinates)."""
     wk = W.kernel_stress_blockwise()
     pool = [W.kernel_stress_diffs(wk, t) for t in range(4)]
@@ -215,8 +215,8 @@ def extra_block_quant(E, W, torch, steps=50, warmup=4):
             "steps": steps, "ms_per_step": dt / steps * 1e3, "floats_per_sec": wk.n * wk.d * steps / dt,
             "zeta_worker": wk.zeta_worker,
             "level_histogram_skip_then_levels": [int(v) for v in hist], "kernels_avg_ms": kms,
-            "roofline": _two_ceilings(kms, group, alg, wk.n * wk.d, None),
-            "note": "one stream, HIP events around every kernel; no instruction counters were taken for this workload"}
+            "roofline": _two_ceilings(kms, group, alg, wk.n * wk.d, counters.get("block_quant")),
+            "note": "one stream, HIP events around every kernel"}
 
 
 def extra_rank_k(E, W, torch, steps=20, warmup=3):
@@ -445,7 +445,7 @@ def main():
         rec = {"kernel_stress": lambda: extra_kernel_stress(E, W, torch, counters),
                "federated": lambda: extra_federated(E, W, torch, args.federated_n, counters),
                "sparse_features": lambda: extra_sparse_features(E, W, torch),
-               "block_quant": lambda: extra_block_quant(E, W, torch),
+               "block_quant": lambda: extra_block_quant(E, W, torch, counters),
                "rank_k": lambda: extra_rank_k(E, W, torch)}[args.secondary]()
         print(json.dumps({"secondary_workload": rec}))
         return
@@ -551,7 +551,7 @@ def main():
     other = []
     if not args.no_extras:
         other.append(extra_kernel_stress(E, W, torch, counters))
-        other.append(extra_block_quant(E, W, torch))
+        other.append(extra_block_quant(E, W, torch, counters))
         other.append(extra_rank_k(E, W, torch))
         other.append(extra_federated(E, W, torch, args.federated_n, counters))
         other.append(extra_small_logistic(E, W, torch, W.tiny(), 2000))
