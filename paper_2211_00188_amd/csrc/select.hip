@@ -791,11 +791,16 @@ __global__ __launch_bounds__(kBlock) void k_filter(NodeSet ns, PassArgs a) {
             // instructions, and the compiler does not merge the divisions of separately guarded levels)
             const float av = fabsf(vv[c]);
             const float tg = qa > 0.f ? av / qa : 0.f;
+            float tb = 0.f;
 #pragma unroll
             for (int q = 0; q < NQA; ++q) {
               if (EXACT || q < nq) {
                 float xi, t = tg;
-                if (BLK && ns.lv.qblock[q]) t = qa_l[q] > 0.f ? av / qa_l[q] : 0.f;
+                if (BLK && ns.lv.qblock[q]) {
+                  // (levels with the same block length share the scale, hence the quotient)
+                  if (q == 0 || ns.lv.qblock[q] != ns.lv.qblock[q > 0 ? q - 1 : 0]) tb = qa_l[q] > 0.f ? av / qa_l[q] : 0.f;
+                  t = tb;
+                }
                 // the error of a coordinate is | |v| - decoded magnitude |: the sign is common to both
                 const float mag = qa_l[q] > 0.f ? quant_mag(t, ns.lv.qs[q], qc_l[q], u, &xi) : 0.f;
                 const double e = (double)av - (double)mag;
